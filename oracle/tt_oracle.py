@@ -1,0 +1,172 @@
+"""ctypes front-end of the CPU oracle -- TEST INFRASTRUCTURE, NOT THE PRODUCT PATH.
+
+Only `tests/`, `__graft_entry__.smoke()` and `bench.py`'s `cpu_baseline` leg may
+import this module.  It loads `libtt_oracle.so` (plain C, built from
+`tt_oracle.c` by `build_oracle()`), and adds the integer reorder-plan oracle,
+which is the plain definition written with library sort / unique routines.
+
+Nothing here imports, calls or shares code with the HIP library.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "tt_oracle.c")
+_LIB = os.path.join(_HERE, "libtt_oracle.so")
+_lib = None
+
+
+class _OraTable(ctypes.Structure):
+    _fields_ = [("num_rows", ctypes.c_int64), ("n", ctypes.c_int32 * 3), ("d", ctypes.c_int32 * 3),
+                ("r", ctypes.c_int32 * 4), ("g1", ctypes.c_void_p), ("g2", ctypes.c_void_p),
+                ("g3", ctypes.c_void_p)]
+
+
+def build_oracle(force: bool = False) -> str:
+    """Compile the C oracle with gcc (building the checker is not using it)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c99", "-Wall", "-Wextra",
+               "-o", _LIB, _SRC]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build_oracle()
+        lib = ctypes.CDLL(_LIB)
+        lib.ora_max_threads.restype = ctypes.c_int
+        lib.ora_split_index.argtypes = [ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]
+        lib.ora_row.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
+        for name in ("ora_forward", "ora_forward_dedup"):
+            f = getattr(lib, name)
+            f.restype = ctypes.c_int
+            f.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
+                          ctypes.c_int64, ctypes.c_void_p]
+        for name in ("ora_backward", "ora_backward_dedup"):
+            f = getattr(lib, name)
+            f.restype = ctypes.c_int
+            f.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
+                          ctypes.c_int64, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p,
+                          ctypes.c_void_p, ctypes.c_void_p]
+        lib.ora_sgd.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_float]
+        _lib = lib
+    return _lib
+
+
+def max_threads() -> int:
+    return int(_load().ora_max_threads())
+
+
+def _f32(a):
+    return np.ascontiguousarray(a, dtype=np.float32).reshape(-1)
+
+
+def _i64(a):
+    return np.ascontiguousarray(a, dtype=np.int64).reshape(-1)
+
+
+def _table(shape, cores):
+    g = [_f32(c) for c in cores]
+    for k in range(3):
+        assert g[k].size == shape.r[k] * shape.n[k] * shape.d[k] * shape.r[k + 1], "core %d size" % k
+    assert shape.r[0] == 1 and shape.r[3] == 1
+    t = _OraTable()
+    t.num_rows = int(shape.num_rows)
+    t.n[:] = list(shape.n)
+    t.d[:] = list(shape.d)
+    t.r[:] = list(shape.r)
+    t.g1, t.g2, t.g3 = (x.ctypes.data for x in g)
+    return t, g  # keep g alive while t is in use
+
+
+def split_index(idx: int, n) -> tuple:
+    nn = (ctypes.c_int32 * 3)(*n)
+    out = (ctypes.c_int64 * 3)()
+    _load().ora_split_index(int(idx), nn, out)
+    return tuple(int(x) for x in out)
+
+
+def row(shape, cores, idx: int) -> np.ndarray:
+    """One reconstructed embedding row, float64[D]."""
+    t, keep = _table(shape, cores)
+    out = np.zeros(shape.dim, dtype=np.float64)
+    _load().ora_row(ctypes.byref(t), int(idx), out.ctypes.data)
+    return out
+
+
+def forward(shape, cores, indices, offsets, dedup: bool = False) -> np.ndarray:
+    """Bag sums, float32[B][D].  `dedup` selects the re-associated (fast) mode."""
+    t, keep = _table(shape, cores)
+    idx, off = _i64(indices), _i64(offsets)
+    nb = off.size - 1
+    assert off[0] == 0 and off[-1] == idx.size and np.all(np.diff(off) >= 0)
+    out = np.zeros((nb, shape.dim), dtype=np.float32)
+    f = _load().ora_forward_dedup if dedup else _load().ora_forward
+    f(ctypes.byref(t), idx.ctypes.data, off.ctypes.data, idx.size, nb, out.ctypes.data)
+    return out
+
+
+def backward(shape, cores, indices, offsets, grad_out, dedup: bool = False, max_threads_: int = 0):
+    """TT-core gradients [dG1, dG2, dG3] (flat float32, core-shaped)."""
+    t, keep = _table(shape, cores)
+    idx, off, g = _i64(indices), _i64(offsets), _f32(grad_out)
+    nb = off.size - 1
+    assert g.size == nb * shape.dim
+    assert off[0] == 0 and off[-1] == idx.size and np.all(np.diff(off) >= 0)
+    dg = [np.zeros(keep[k].size, dtype=np.float32) for k in range(3)]
+    f = _load().ora_backward_dedup if dedup else _load().ora_backward
+    rc = f(ctypes.byref(t), idx.ctypes.data, off.ctypes.data, idx.size, nb, g.ctypes.data,
+           int(max_threads_), dg[0].ctypes.data, dg[1].ctypes.data, dg[2].ctypes.data)
+    if rc < 0:
+        raise MemoryError("oracle backward: accumulator allocation failed")
+    return dg
+
+
+def sgd(cores, dcores, lr: float):
+    """Plain gradient descent, returns new cores (inputs untouched)."""
+    out = []
+    for g, dg in zip(cores, dcores):
+        gg = _f32(g).copy()
+        d = _f32(dg)
+        _load().ora_sgd(gg.ctypes.data, d.ctypes.data, gg.size, ctypes.c_float(lr))
+        out.append(gg)
+    return out
+
+
+def reorder_plan(shape, indices, offsets, remap=None) -> dict:
+    """Integer oracle of the index-reordering pass (Sections III-C, III-E, III-G).
+
+    The lookups are (optionally remapped by the index bijection, then) stably
+    sorted by row; ties keep their original position, so the plan is unique.
+    Distinct rows and distinct (i1,i2) prefixes (prefix = row div n3, the key
+    of the paper's reuse buffer) are listed in increasing order.  Invalid
+    indices (negative or >= num_rows) take no part in the plan.
+    """
+    idx = _i64(indices)
+    off = _i64(offsets)
+    nnz = idx.size
+    rows = idx if remap is None else np.where((idx >= 0) & (idx < len(remap)),
+                                              _i64(remap)[np.clip(idx, 0, len(remap) - 1)], -1)
+    valid = (rows >= 0) & (rows < shape.num_rows)
+    bag_of_lookup = np.repeat(np.arange(off.size - 1, dtype=np.int64), np.diff(off))
+    pos = np.nonzero(valid)[0]
+    order = pos[np.argsort(rows[pos], kind="stable")]
+    sorted_row = rows[order]
+    uniq_row, first, inverse = np.unique(sorted_row, return_index=True, return_inverse=True)
+    row_seg = np.concatenate([first, [sorted_row.size]]).astype(np.int64)
+    lookup2row = np.full(nnz, -1, dtype=np.int64)
+    lookup2row[order] = inverse
+    pref_of_row = uniq_row // shape.n[2]
+    uniq_pref, pfirst, row2pref = np.unique(pref_of_row, return_index=True, return_inverse=True)
+    pref_seg = np.concatenate([pfirst, [uniq_row.size]]).astype(np.int64)
+    return dict(perm=order, sorted_row=sorted_row, bag_of_sorted=bag_of_lookup[order],
+                uniq_row=uniq_row, row_seg=row_seg, lookup2row=lookup2row,
+                uniq_pref=uniq_pref, pref_seg=pref_seg, row2pref=row2pref,
+                num_valid=int(sorted_row.size), any_invalid=bool((~valid).any()))
