@@ -1,0 +1,197 @@
+/*
+ * tt_emb.h -- C ABI of the Tensor-Train (TT) embedding-bag hot path for MI355X (gfx950).
+ *
+ * The operator is an nn.EmbeddingBag-style lookup (flat index list + CSR bag
+ * offsets, sum pooling) whose trainable parameters are three TT cores (paper,
+ * Section II-B; Section III-A..F for the optimised lookup / backward).
+ *
+ * Conventions shared by every call
+ * --------------------------------
+ * - "DEVICE" pointers are HIP device memory of the current device; "HOST"
+ *   pointers are ordinary host memory.  The library allocates nothing and keeps
+ *   no global state: every buffer, including the workspace a plan lives in, is
+ *   owned by the caller and merely borrowed until the work enqueued by the call
+ *   has finished on `stream`.
+ * - All work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
+ *   default stream).  No call synchronises or copies device->host, except
+ *   tt_plan_status.
+ * - Core k (k = 0,1,2) is a flat fp32 array indexed G_k[r[k]][n[k]][d[k]][r[k+1]],
+ *   row-major, with r[0] = r[3] = 1 (Section II-B: boundary ranks are 1).
+ *   A table has num_rows <= n[0]*n[1]*n[2] rows; rows >= num_rows are padding
+ *   and are never valid.  Row i uses slices (i1,i2,i3) with
+ *   i3 = i mod n[2], i2 = (i div n[2]) mod n[1], i1 = i div (n[1]*n[2])
+ *   (Section III-B, TT-index equation; i1 is the most significant digit), and
+ *   its D = d[0]*d[1]*d[2] columns are ordered j = (j1*d[1] + j2)*d[2] + j3.
+ * - Bags are CSR: offsets has num_bags+1 entries, offsets[0] = 0,
+ *   offsets[num_bags] = nnz, non-decreasing.  An empty bag gives a zero row.
+ *   Indices and offsets are int64 (the PyTorch default); everything else fp32.
+ * - Every call returns a tt_status and never throws.  Host-visible arguments
+ *   (NULL pointers, shapes, sizes) are validated synchronously.  Errors only
+ *   the device can see (an index < 0 or >= num_rows, offsets that are not
+ *   monotone) set a status word inside the plan; the offending lookup then
+ *   contributes nothing, and tt_plan_status reports it.  Without a plan
+ *   (naive arms) an out-of-range lookup is skipped silently.
+ * - With a plan every result is bitwise reproducible from run to run (sorted
+ *   segmented reductions, no floating-point atomics).  The plan == NULL
+ *   backward accumulates with floating-point atomics and is not.
+ * - Limits (TT_ERR_SHAPE otherwise): n[0]*n[1]*n[2] < 2^31 - 1, nnz < 2^31 - 1,
+ *   r[1], r[2] <= 128, d[0]*d[1]*r[2] <= 4096, d[1]*r[2] <= 4096, D <= 1024.
+ */
+#ifndef TT_EMB_H_
+#define TT_EMB_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  TT_OK = 0,
+  TT_ERR_INVALID_ARG = -1, /* NULL pointer, negative size                                */
+  TT_ERR_SHAPE = -2,       /* table shape violates the conventions or limits above       */
+  TT_ERR_WORKSPACE = -3,   /* workspace too small or misaligned (needs 256-byte align)   */
+  TT_ERR_INDEX_RANGE = -4, /* reported by tt_plan_status: bad index or bad offsets seen  */
+  TT_ERR_HIP = -5          /* a HIP runtime call or kernel launch failed                 */
+} tt_status;
+
+/* One TT table.  HOST struct, caller-owned, read during the call only. */
+typedef struct {
+  int64_t num_rows; /* N, number of valid rows                                         */
+  int32_t n[3];     /* row factors, n[0]*n[1]*n[2] >= N                                */
+  int32_t d[3];     /* column factors, D = d[0]*d[1]*d[2]                              */
+  int32_t r[4];     /* TT ranks, r[0] = r[3] = 1                                       */
+  float *core[3];   /* DEVICE, core k is [r[k]][n[k]][d[k]][r[k+1]] row-major          */
+} tt_table;
+
+/*
+ * The reorder plan: a HOST struct of DEVICE pointers into the caller's
+ * workspace, filled by tt_index_reorder.  It is the deterministic counterpart
+ * of the paper's reuse-buffer bookkeeping (Section III-C, pointer-preparation
+ * algorithm) and of the "distinct embeddings" bookkeeping of the gradient
+ * aggregation (Section III-E): lookups stably sorted by row, the distinct rows,
+ * and the distinct (i1,i2) prefixes (prefix = row div n[2], the reuse-buffer
+ * key), each in increasing order.  U_r = number of distinct valid rows, U_p =
+ * number of distinct prefixes; both live on the device (counts[0], counts[1]).
+ * All index arrays are int32.  Entries beyond the stated valid length are
+ * unspecified.  The same plan serves forward, backward and update of the batch
+ * it was built from, for this table shape only.
+ */
+typedef struct {
+  int64_t nnz, num_bags;  /* the batch the plan was built for                            */
+  int64_t max_rows;       /* capacity for distinct rows     = min(nnz, num_rows)          */
+  int64_t max_prefixes;   /* capacity for distinct prefixes = min(nnz, n[0]*n[1])         */
+  int32_t n[3], d[3], r[4];
+  /* -- lookup order ------------------------------------------------------------------ */
+  int32_t *sorted_row;    /* [nnz] row of the s-th lookup in (row, position) order; the
+                             valid lookups come first, invalid ones hold n0*n1*n2         */
+  int32_t *perm;          /* [nnz] original position of the s-th sorted lookup            */
+  int32_t *bag_of_sorted; /* [nnz] bag that holds the s-th sorted lookup                  */
+  int32_t *slot_of_sorted;/* [nnz] distinct-row slot of the s-th sorted lookup, -1 invalid*/
+  int32_t *lookup2row;    /* [nnz] distinct-row slot of original position l, -1 invalid   */
+  /* -- distinct rows and prefixes ------------------------------------------------------ */
+  int32_t *uniq_row;      /* [U_r] distinct rows, strictly increasing                     */
+  int32_t *row_seg;       /* [U_r+1] sorted-lookup range of each distinct row             */
+  int32_t *row2pref;      /* [U_r] prefix slot of each distinct row                       */
+  int32_t *uniq_pref;     /* [U_p] distinct prefixes i1*n[1]+i2, strictly increasing      */
+  int32_t *pref_seg;      /* [U_p+1] distinct-row range of each prefix                    */
+  /* -- groupings used by the core-gradient reductions ---------------------------------- */
+  int32_t *rows_by_i3;    /* [U_r] distinct-row slots stably sorted by i3                 */
+  int32_t *i3_of_sorted;  /* [U_r] the i3 key of rows_by_i3[.] (non-decreasing)           */
+  int32_t *i3_seg;        /* [n[2]+1] range in rows_by_i3 of each i3                      */
+  int32_t *prefs_by_i2;   /* [U_p] prefix slots stably sorted by i2                       */
+  int32_t *i2_seg;        /* [n[1]+1] range in prefs_by_i2 of each i2                     */
+  int32_t *i1_seg;        /* [n[0]+1] prefix-slot range of each i1                        */
+  int32_t *counts;        /* [16] counts[0]=U_r, [1]=U_p, [2]=valid lookups, [3]=nnz,
+                             [4]=status bits (1: index out of range, 2: bad offsets)      */
+  /* -- float scratch used by forward / backward (contents are transient) --------------- */
+  float *rowbuf;          /* [max_rows][D] reconstructed distinct rows                    */
+  float *gagg;            /* [max_rows][D] output gradients merged per distinct row       */
+  float *hbuf;            /* [max_prefixes][d0*d1*r2] per-prefix right partial gradients  */
+  float *t3buf;           /* [max_rows][r2*d2] per-row contributions to core 2            */
+  float *t1buf;           /* [max_prefixes][d0*r1] per-prefix contributions to core 0     */
+  float *partial;         /* segmented-reduction partials                                 */
+  void *sort_tmp;         /* radix-sort ping-pong buffers, histograms, scan temporaries   */
+  void *workspace;        /* the caller's workspace this plan points into                 */
+  size_t workspace_bytes;
+} tt_plan;
+
+/* Bytes of DEVICE workspace tt_index_reorder needs for this table shape and batch size
+ * (0 on invalid arguments).  The workspace must be 256-byte aligned. */
+size_t tt_workspace_bytes(const tt_table *table, int64_t nnz, int64_t num_bags);
+
+/*
+ * Index reordering (Section III-G: each batch's lookups are put in increasing
+ * index order so that equal TT prefixes become adjacent and reusable; Section
+ * III-C: detect which prefix products must be computed; Section III-E: find the
+ * distinct rows whose gradients are merged).
+ *   indices  DEVICE int64[nnz]        row index of each lookup
+ *   offsets  DEVICE int64[num_bags+1] CSR bag offsets
+ *   remap    DEVICE int64[num_rows] or NULL: the index bijection f_index of
+ *            Section III-G applied before the lookup (row = remap[index]);
+ *            NULL = identity.  It changes which row is read.
+ *   workspace DEVICE, workspace_bytes >= tt_workspace_bytes(...), 256-byte aligned
+ *   plan_out HOST, filled on return (its arrays become valid when the enqueued
+ *            work has run).
+ * Ties between equal rows keep their original order, so the plan is unique.
+ */
+tt_status tt_index_reorder(const tt_table *table, const int64_t *indices, const int64_t *offsets,
+                           int64_t nnz, int64_t num_bags, const int64_t *remap, void *workspace,
+                           size_t workspace_bytes, tt_plan *plan_out, void *stream);
+
+/*
+ * Forward (Section III-B): out[b][:] = sum over the lookups l of bag b of the
+ * reconstructed row W[index[l]][:], where W[i] = G1[i1] x G2[i2] x G3[i3].
+ *   plan != NULL: each distinct prefix product G1[i1] x G2[i2] and each distinct
+ *                 row is computed once (batch-level reuse, Section III-C), then
+ *                 bags are summed; `indices` may be NULL (the plan holds them).
+ *   plan == NULL: naive arm, every lookup runs the full chain (no reuse).
+ *   out  DEVICE float[num_bags][D], overwritten.
+ * The remap given to tt_index_reorder is baked into the plan; the naive arm
+ * reads `indices` as they are.
+ */
+tt_status tt_emb_bag_forward(const tt_table *table, const tt_plan *plan, const int64_t *indices,
+                             const int64_t *offsets, int64_t nnz, int64_t num_bags, float *out,
+                             void *stream);
+
+/*
+ * Backward (Section III-D backward equation; Section III-E in-advance gradient
+ * aggregation): gradients of L w.r.t. the three cores given grad_out[b][:] =
+ * dL/d out[b][:].  Gradients of repeated rows add up.
+ *   plan != NULL: output gradients are first merged per distinct row, then
+ *                 contracted once per distinct row / prefix, and slice gradients
+ *                 are combined by sorted segmented reductions.
+ *   plan == NULL: naive arm, one contraction per lookup, atomic accumulation.
+ *   grad_out DEVICE float[num_bags][D]
+ *   dcore    HOST array of 3 DEVICE pointers, core-shaped, fully overwritten
+ *            (slices no lookup touches are exactly 0).
+ */
+tt_status tt_emb_bag_backward(const tt_table *table, const tt_plan *plan, const int64_t *indices,
+                              const int64_t *offsets, int64_t nnz, int64_t num_bags,
+                              const float *grad_out, float *const dcore[3], void *stream);
+
+/*
+ * Gradient-descent update of the cores (training algorithm, update step):
+ * G_k <- G_k - lr * dG_k for k = 0,1,2, in place.
+ *   plan != NULL: only the slices the batch touched are visited (the others have
+ *                 zero gradient, so the result is identical);
+ *   plan == NULL: dense sweep over the three cores.
+ */
+tt_status tt_core_sgd_update(const tt_table *table, const tt_plan *plan,
+                             const float *const dcore[3], float lr, void *stream);
+
+/*
+ * Waits for `stream`, copies the plan's device-side counters to the host and
+ * reports deferred errors.  counts_out (HOST, nullable) receives
+ * {U_r, U_p, valid lookups, status bits}.  Returns TT_ERR_INDEX_RANGE if any
+ * index was out of range or the offsets were not a valid CSR array.
+ */
+tt_status tt_plan_status(const tt_plan *plan, void *stream, int64_t counts_out[4]);
+
+const char *tt_strerror(tt_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TT_EMB_H_ */

@@ -1,0 +1,242 @@
+"""Thin ctypes binding of libtt_emb.so: argument marshalling only.
+
+Every step of the path runs in the HIP kernels behind the C ABI declared in
+include/tt_emb.h; PyTorch is used here for device memory (tensors) and
+streams.  There is no CPU fallback: if the library is missing or a call
+returns an error status, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libtt_emb.so")
+
+TT_OK = 0
+TT_ERR_INVALID_ARG = -1
+TT_ERR_SHAPE = -2
+TT_ERR_WORKSPACE = -3
+TT_ERR_INDEX_RANGE = -4
+TT_ERR_HIP = -5
+
+EXPORTS = ("tt_workspace_bytes", "tt_index_reorder", "tt_emb_bag_forward", "tt_emb_bag_backward",
+           "tt_core_sgd_update", "tt_plan_status", "tt_strerror")
+
+
+class TTError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s: %s (status %d)" % (where, strerror(status), status))
+
+
+class CTable(ctypes.Structure):
+    _fields_ = [("num_rows", ctypes.c_int64), ("n", ctypes.c_int32 * 3), ("d", ctypes.c_int32 * 3),
+                ("r", ctypes.c_int32 * 4), ("core", ctypes.c_void_p * 3)]
+
+
+_I32P = ctypes.c_void_p
+_PLAN_INT_ARRAYS = ("sorted_row", "perm", "bag_of_sorted", "slot_of_sorted", "lookup2row", "uniq_row",
+                    "row_seg", "row2pref", "uniq_pref", "pref_seg", "rows_by_i3", "i3_of_sorted",
+                    "i3_seg", "prefs_by_i2", "i2_seg", "i1_seg", "counts")
+_PLAN_FLOAT_ARRAYS = ("rowbuf", "gagg", "hbuf", "t3buf", "t1buf", "partial")
+
+
+class CPlan(ctypes.Structure):
+    _fields_ = ([("nnz", ctypes.c_int64), ("num_bags", ctypes.c_int64), ("max_rows", ctypes.c_int64),
+                 ("max_prefixes", ctypes.c_int64), ("n", ctypes.c_int32 * 3), ("d", ctypes.c_int32 * 3),
+                 ("r", ctypes.c_int32 * 4)]
+                + [(name, _I32P) for name in _PLAN_INT_ARRAYS]
+                + [(name, ctypes.c_void_p) for name in _PLAN_FLOAT_ARRAYS]
+                + [("sort_tmp", ctypes.c_void_p), ("workspace", ctypes.c_void_p),
+                   ("workspace_bytes", ctypes.c_size_t)])
+
+
+_lib = None
+
+
+def load_library():
+    """Load libtt_emb.so; fails loudly when it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("%s is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                              "(hipcc, gfx950) first; there is no fallback path" % LIB_PATH)
+        lib = ctypes.CDLL(LIB_PATH)
+        vp, i64, f32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_float
+        lib.tt_workspace_bytes.restype = ctypes.c_size_t
+        lib.tt_workspace_bytes.argtypes = [vp, i64, i64]
+        lib.tt_index_reorder.restype = ctypes.c_int
+        lib.tt_index_reorder.argtypes = [vp, vp, vp, i64, i64, vp, vp, ctypes.c_size_t, vp, vp]
+        lib.tt_emb_bag_forward.restype = ctypes.c_int
+        lib.tt_emb_bag_forward.argtypes = [vp, vp, vp, vp, i64, i64, vp, vp]
+        lib.tt_emb_bag_backward.restype = ctypes.c_int
+        lib.tt_emb_bag_backward.argtypes = [vp, vp, vp, vp, i64, i64, vp, vp, vp]
+        lib.tt_core_sgd_update.restype = ctypes.c_int
+        lib.tt_core_sgd_update.argtypes = [vp, vp, vp, f32, vp]
+        lib.tt_plan_status.restype = ctypes.c_int
+        lib.tt_plan_status.argtypes = [vp, vp, vp]
+        lib.tt_strerror.restype = ctypes.c_char_p
+        lib.tt_strerror.argtypes = [ctypes.c_int]
+        _lib = lib
+    return _lib
+
+
+def strerror(status: int) -> str:
+    return load_library().tt_strerror(int(status)).decode()
+
+
+def _check(status: int, where: str):
+    if status != TT_OK:
+        raise TTError(status, where)
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _dev_i64(t, name):
+    if t is None:
+        return None
+    if not (t.is_cuda and t.dtype == torch.int64 and t.is_contiguous()):
+        raise TypeError("%s must be a contiguous CUDA int64 tensor" % name)
+    return t
+
+
+def _dev_f32(t, name):
+    if not (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()):
+        raise TypeError("%s must be a contiguous CUDA float32 tensor" % name)
+    return t
+
+
+class Table:
+    """A TT table: shape + three device-resident fp32 cores (flat, [r][n][d][r'] order)."""
+
+    def __init__(self, num_rows, n, d, r, cores):
+        self.num_rows, self.n, self.d, self.r = int(num_rows), tuple(n), tuple(d), tuple(r)
+        self.cores = [_dev_f32(c, "core") for c in cores]
+        for k in range(3):
+            want = self.r[k] * self.n[k] * self.d[k] * self.r[k + 1]
+            if self.cores[k].numel() != want:
+                raise ValueError("core %d has %d elements, expected %d" % (k, self.cores[k].numel(), want))
+        self.dim = self.d[0] * self.d[1] * self.d[2]
+        c = CTable()
+        c.num_rows = self.num_rows
+        c.n[:] = self.n
+        c.d[:] = self.d
+        c.r[:] = self.r
+        for k in range(3):
+            c.core[k] = self.cores[k].data_ptr()
+        self.c = c
+
+    @classmethod
+    def from_numpy(cls, shape, cores, device="cuda"):
+        return cls(shape.num_rows, shape.n, shape.d, shape.r,
+                   [torch.from_numpy(c).to(device).contiguous() for c in cores])
+
+    def core_grads_like(self):
+        return [torch.empty_like(c) for c in self.cores]
+
+
+class Plan:
+    """Host view of a reorder plan; owns (or borrows) the device workspace tensor."""
+
+    def __init__(self, workspace):
+        self.workspace = workspace
+        self.c = CPlan()
+
+    def _array(self, name, count, dtype):
+        addr = getattr(self.c, name)
+        off = addr - self.workspace.data_ptr()
+        esz = 4
+        return self.workspace[off:off + count * esz].view(dtype)
+
+    def counts(self, stream=None):
+        """(U_r, U_p, valid lookups, status bits); synchronises the stream."""
+        out = (ctypes.c_int64 * 4)()
+        st = load_library().tt_plan_status(ctypes.byref(self.c), _stream(stream), out)
+        return tuple(int(x) for x in out), st
+
+    def arrays(self, stream=None) -> dict:
+        """Copies of the plan's index arrays trimmed to their valid lengths (test helper)."""
+        (ur, up, nvalid, _), _ = self.counts(stream)
+        nnz = int(self.c.nnz)
+        lens = dict(sorted_row=nnz, perm=nnz, bag_of_sorted=nnz, slot_of_sorted=nnz, lookup2row=nnz,
+                    uniq_row=ur, row_seg=ur + 1, row2pref=ur, uniq_pref=up, pref_seg=up + 1,
+                    rows_by_i3=ur, i3_of_sorted=ur, i3_seg=self.c.n[2] + 1, prefs_by_i2=up,
+                    i2_seg=self.c.n[1] + 1, i1_seg=self.c.n[0] + 1)
+        out = {k: self._array(k, v, torch.int32).cpu().numpy() for k, v in lens.items()}
+        out.update(U_r=ur, U_p=up, num_valid=nvalid)
+        return out
+
+
+def tt_workspace_bytes(table: Table, nnz: int, num_bags: int) -> int:
+    return int(load_library().tt_workspace_bytes(ctypes.byref(table.c), int(nnz), int(num_bags)))
+
+
+def alloc_workspace(table: Table, nnz: int, num_bags: int, device="cuda"):
+    nbytes = tt_workspace_bytes(table, nnz, num_bags)
+    if nbytes == 0:
+        raise TTError(TT_ERR_SHAPE, "tt_workspace_bytes")
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def tt_index_reorder(table: Table, indices, offsets, remap=None, workspace=None, stream=None) -> Plan:
+    indices, offsets = _dev_i64(indices, "indices"), _dev_i64(offsets, "offsets")
+    remap = _dev_i64(remap, "remap")
+    nnz, nb = indices.numel(), offsets.numel() - 1
+    if workspace is None:
+        workspace = alloc_workspace(table, nnz, nb, indices.device)
+    plan = Plan(workspace)
+    st = load_library().tt_index_reorder(ctypes.byref(table.c), _ptr(indices), _ptr(offsets), nnz, nb,
+                                         _ptr(remap), _ptr(workspace), workspace.numel(),
+                                         ctypes.byref(plan.c), _stream(stream))
+    _check(st, "tt_index_reorder")
+    return plan
+
+
+def tt_emb_bag_forward(table: Table, plan, indices, offsets, out=None, stream=None):
+    indices, offsets = _dev_i64(indices, "indices"), _dev_i64(offsets, "offsets")
+    nnz, nb = indices.numel(), offsets.numel() - 1
+    if out is None:
+        out = torch.empty((nb, table.dim), dtype=torch.float32, device=offsets.device)
+    _dev_f32(out, "out")
+    st = load_library().tt_emb_bag_forward(ctypes.byref(table.c), ctypes.byref(plan.c) if plan else None,
+                                           _ptr(indices), _ptr(offsets), nnz, nb, _ptr(out), _stream(stream))
+    _check(st, "tt_emb_bag_forward")
+    return out
+
+
+def tt_emb_bag_backward(table: Table, plan, indices, offsets, grad_out, dcores=None, stream=None):
+    indices, offsets = _dev_i64(indices, "indices"), _dev_i64(offsets, "offsets")
+    _dev_f32(grad_out, "grad_out")
+    nnz, nb = indices.numel(), offsets.numel() - 1
+    if grad_out.numel() != nb * table.dim:
+        raise ValueError("grad_out must hold num_bags * D floats")
+    if dcores is None:
+        dcores = table.core_grads_like()
+    arr = (ctypes.c_void_p * 3)(*[_dev_f32(g, "dcore").data_ptr() for g in dcores])
+    st = load_library().tt_emb_bag_backward(ctypes.byref(table.c), ctypes.byref(plan.c) if plan else None,
+                                            _ptr(indices), _ptr(offsets), nnz, nb, _ptr(grad_out), arr,
+                                            _stream(stream))
+    _check(st, "tt_emb_bag_backward")
+    return dcores
+
+
+def tt_core_sgd_update(table: Table, plan, dcores, lr: float, stream=None):
+    arr = (ctypes.c_void_p * 3)(*[_dev_f32(g, "dcore").data_ptr() for g in dcores])
+    st = load_library().tt_core_sgd_update(ctypes.byref(table.c), ctypes.byref(plan.c) if plan else None,
+                                           arr, ctypes.c_float(lr), _stream(stream))
+    _check(st, "tt_core_sgd_update")
+
+
+def tt_plan_status(plan: Plan, stream=None) -> int:
+    _, st = plan.counts(stream)
+    return st

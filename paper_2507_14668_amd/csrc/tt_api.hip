@@ -1,0 +1,203 @@
+// C ABI of the TT embedding-bag library: argument validation, workspace layout, dispatch.
+#include <string.h>
+
+#include "tt_internal.h"
+
+namespace {
+
+bool derive_shape(const tt_table *t, TTShape *sh) {
+  if (!t) return false;
+  for (int k = 0; k < 3; ++k)
+    if (t->n[k] < 1 || t->d[k] < 1) return false;
+  if (t->r[0] != 1 || t->r[3] != 1 || t->r[1] < 1 || t->r[2] < 1) return false;
+  if (t->r[1] > 128 || t->r[2] > 128) return false;
+  const long long cap = (long long)t->n[0] * t->n[1] * t->n[2];
+  if (cap >= 2147483647LL || (long long)t->n[0] * t->n[1] >= 2147483647LL) return false;
+  if (t->num_rows < 1 || t->num_rows > cap) return false;
+  sh->n1 = t->n[0]; sh->n2 = t->n[1]; sh->n3 = t->n[2];
+  sh->d1 = t->d[0]; sh->d2 = t->d[1]; sh->d3 = t->d[2];
+  sh->R1 = t->r[1]; sh->R2 = t->r[2];
+  const long long D = (long long)sh->d1 * sh->d2 * sh->d3, P = (long long)sh->d1 * sh->d2 * sh->R2,
+                  S2 = (long long)sh->d2 * sh->R2;
+  if (D > 1024 || P > 4096 || S2 > 4096 || (long long)sh->d1 * sh->R1 > 4096) return false;
+  sh->D = (int)D;
+  sh->S1 = sh->d1 * sh->R1;
+  sh->S2 = (int)S2;
+  sh->S3 = sh->R2 * sh->d3;
+  sh->P = (int)P;
+  sh->R2p = sh->R2 | 1;
+  sh->sentinel = (int)cap;
+  sh->num_rows = t->num_rows;
+  // the per-prefix kernels keep one slice of every operand in LDS (64 KB static budget)
+  const long long lds_floats = (long long)sh->S1 + (long long)sh->d1 * sh->d2 * sh->R2p + sh->P +
+                               sh->D + 8LL * sh->S3;
+  if (sh->S3 > 4096 || lds_floats * 4 > 65536) return false;
+  return true;
+}
+
+bool cores_present(const tt_table *t) { return t->core[0] && t->core[1] && t->core[2]; }
+
+size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
+
+// Carves the workspace.  With base == nullptr only the total size is computed.
+size_t layout(const TTShape &sh, int64_t nnz, int64_t num_bags, char *base, tt_plan *p) {
+  (void)num_bags;
+  const int64_t max_rows = nnz < sh.num_rows ? nnz : sh.num_rows;
+  const int64_t pref_cap = (int64_t)sh.n1 * sh.n2;
+  const int64_t max_pref = nnz < pref_cap ? nnz : pref_cap;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    char *q = base ? base + off : nullptr;
+    off += align_up(bytes);
+    return q;
+  };
+  auto ints = [&](int64_t count) { return (int32_t *)take(sizeof(int32_t) * (size_t)(count + 1)); };
+  auto floats = [&](size_t count) { return (float *)take(sizeof(float) * (count + 4)); };
+  tt_plan q;
+  memset(&q, 0, sizeof(q));
+  q.nnz = nnz; q.num_bags = num_bags; q.max_rows = max_rows; q.max_prefixes = max_pref;
+  q.sorted_row = ints(nnz);
+  q.perm = ints(nnz);
+  q.bag_of_sorted = ints(nnz);
+  q.slot_of_sorted = ints(nnz);
+  q.lookup2row = ints(nnz);
+  q.uniq_row = ints(max_rows);
+  q.row_seg = ints(max_rows + 1);
+  q.row2pref = ints(max_rows);
+  q.uniq_pref = ints(max_pref);
+  q.pref_seg = ints(max_pref + 1);
+  q.rows_by_i3 = ints(max_rows);
+  q.i3_of_sorted = ints(max_rows);
+  q.i3_seg = ints(sh.n3 + 1);
+  q.prefs_by_i2 = ints(max_pref);
+  q.i2_seg = ints(sh.n2 + 1);
+  q.i1_seg = ints(sh.n1 + 1);
+  q.counts = ints(16);
+  q.rowbuf = floats((size_t)max_rows * sh.D);
+  q.gagg = floats((size_t)max_rows * sh.D);
+  q.hbuf = floats((size_t)max_pref * sh.P);
+  q.t3buf = floats((size_t)max_rows * sh.S3);
+  q.t1buf = floats((size_t)max_pref * sh.S1);
+  size_t part = (size_t)(tt_ceil_div(nnz, TT_SEG_CHUNK) + 1) * 2 * sh.D;
+  size_t part3 = (size_t)(tt_ceil_div(max_rows, TT_SEG_CHUNK) + 1) * 2 * sh.S3;
+  size_t part1 = (size_t)(tt_ceil_div(max_pref, TT_SEG_CHUNK) + 1) * 2 * sh.S1;
+  if (part3 > part) part = part3;
+  if (part1 > part) part = part1;
+  q.partial = floats(part);
+  q.sort_tmp = take(tt_sort_tmp_bytes(nnz, max_rows, max_pref));
+  if (p) *p = q;
+  return off;
+}
+
+bool plan_matches(const tt_plan *plan, const tt_table *t, int64_t nnz, int64_t num_bags) {
+  if (!plan->workspace || plan->nnz != nnz || plan->num_bags != num_bags) return false;
+  for (int k = 0; k < 3; ++k)
+    if (plan->n[k] != t->n[k] || plan->d[k] != t->d[k]) return false;
+  return plan->r[1] == t->r[1] && plan->r[2] == t->r[2];
+}
+
+bool batch_ok(int64_t nnz, int64_t num_bags) {
+  if (nnz < 0 || num_bags < 0 || nnz >= 2147483647LL || num_bags >= 2147483646LL) return false;
+  if (num_bags == 0 && nnz != 0) return false;
+  return true;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t tt_workspace_bytes(const tt_table *table, int64_t nnz, int64_t num_bags) {
+  TTShape sh;
+  if (!derive_shape(table, &sh) || !batch_ok(nnz, num_bags)) return 0;
+  return layout(sh, nnz, num_bags, nullptr, nullptr);
+}
+
+tt_status tt_index_reorder(const tt_table *table, const int64_t *indices, const int64_t *offsets,
+                           int64_t nnz, int64_t num_bags, const int64_t *remap, void *workspace,
+                           size_t workspace_bytes, tt_plan *plan_out, void *stream) {
+  if (!table || !plan_out || !workspace || !offsets || (nnz > 0 && !indices))
+    return TT_ERR_INVALID_ARG;
+  if (!batch_ok(nnz, num_bags)) return TT_ERR_INVALID_ARG;
+  TTShape sh;
+  if (!derive_shape(table, &sh)) return TT_ERR_SHAPE;
+  if (((uintptr_t)workspace & 255) != 0) return TT_ERR_WORKSPACE;
+  if (workspace_bytes < layout(sh, nnz, num_bags, nullptr, nullptr)) return TT_ERR_WORKSPACE;
+  layout(sh, nnz, num_bags, (char *)workspace, plan_out);
+  for (int k = 0; k < 3; ++k) { plan_out->n[k] = table->n[k]; plan_out->d[k] = table->d[k]; }
+  for (int k = 0; k < 4; ++k) plan_out->r[k] = table->r[k];
+  plan_out->workspace = workspace;
+  plan_out->workspace_bytes = workspace_bytes;
+  return ttk_reorder(sh, indices, offsets, nnz, num_bags, remap, plan_out, (hipStream_t)stream);
+}
+
+tt_status tt_emb_bag_forward(const tt_table *table, const tt_plan *plan, const int64_t *indices,
+                             const int64_t *offsets, int64_t nnz, int64_t num_bags, float *out,
+                             void *stream) {
+  if (!table || !offsets || (num_bags > 0 && !out)) return TT_ERR_INVALID_ARG;
+  if (!batch_ok(nnz, num_bags)) return TT_ERR_INVALID_ARG;
+  TTShape sh;
+  if (!derive_shape(table, &sh)) return TT_ERR_SHAPE;
+  if (!cores_present(table)) return TT_ERR_INVALID_ARG;
+  if (plan) {
+    if (!plan_matches(plan, table, nnz, num_bags)) return TT_ERR_INVALID_ARG;
+    return ttk_forward_plan(sh, table, plan, offsets, num_bags, out, (hipStream_t)stream);
+  }
+  if (nnz > 0 && !indices) return TT_ERR_INVALID_ARG;
+  return ttk_forward_naive(sh, table, indices, offsets, nnz, num_bags, out, (hipStream_t)stream);
+}
+
+tt_status tt_emb_bag_backward(const tt_table *table, const tt_plan *plan, const int64_t *indices,
+                              const int64_t *offsets, int64_t nnz, int64_t num_bags,
+                              const float *grad_out, float *const dcore[3], void *stream) {
+  if (!table || !offsets || !dcore || !dcore[0] || !dcore[1] || !dcore[2])
+    return TT_ERR_INVALID_ARG;
+  if (!batch_ok(nnz, num_bags) || (num_bags > 0 && !grad_out)) return TT_ERR_INVALID_ARG;
+  TTShape sh;
+  if (!derive_shape(table, &sh)) return TT_ERR_SHAPE;
+  if (!cores_present(table)) return TT_ERR_INVALID_ARG;
+  if (plan) {
+    if (!plan_matches(plan, table, nnz, num_bags)) return TT_ERR_INVALID_ARG;
+    return ttk_backward_plan(sh, table, plan, grad_out, dcore, (hipStream_t)stream);
+  }
+  if (nnz > 0 && !indices) return TT_ERR_INVALID_ARG;
+  return ttk_backward_naive(sh, table, indices, offsets, nnz, num_bags, grad_out, dcore,
+                            (hipStream_t)stream);
+}
+
+tt_status tt_core_sgd_update(const tt_table *table, const tt_plan *plan,
+                             const float *const dcore[3], float lr, void *stream) {
+  if (!table || !dcore || !dcore[0] || !dcore[1] || !dcore[2]) return TT_ERR_INVALID_ARG;
+  TTShape sh;
+  if (!derive_shape(table, &sh)) return TT_ERR_SHAPE;
+  if (!cores_present(table)) return TT_ERR_INVALID_ARG;
+  if (plan && !plan_matches(plan, table, plan->nnz, plan->num_bags)) return TT_ERR_INVALID_ARG;
+  return ttk_sgd(sh, table, plan, dcore, lr, (hipStream_t)stream);
+}
+
+tt_status tt_plan_status(const tt_plan *plan, void *stream, int64_t counts_out[4]) {
+  if (!plan || !plan->counts) return TT_ERR_INVALID_ARG;
+  int32_t host[16];
+  if (hipMemcpyAsync(host, plan->counts, sizeof(host), hipMemcpyDeviceToHost,
+                     (hipStream_t)stream) != hipSuccess)
+    return TT_ERR_HIP;
+  if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return TT_ERR_HIP;
+  if (counts_out) {
+    counts_out[0] = host[0]; counts_out[1] = host[1]; counts_out[2] = host[2];
+    counts_out[3] = host[4];
+  }
+  return host[4] ? TT_ERR_INDEX_RANGE : TT_OK;
+}
+
+const char *tt_strerror(tt_status status) {
+  switch (status) {
+    case TT_OK: return "ok";
+    case TT_ERR_INVALID_ARG: return "invalid argument (NULL pointer, negative size or plan/batch mismatch)";
+    case TT_ERR_SHAPE: return "table shape violates the conventions or limits";
+    case TT_ERR_WORKSPACE: return "workspace too small or not 256-byte aligned";
+    case TT_ERR_INDEX_RANGE: return "an index was out of range or the bag offsets are not a valid CSR array";
+    case TT_ERR_HIP: return "a HIP runtime call or kernel launch failed";
+  }
+  return "unknown status";
+}
+
+}  // extern "C"

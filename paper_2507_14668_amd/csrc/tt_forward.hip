@@ -1,0 +1,230 @@
+// Forward pass of the TT embedding bag (paper Section III-B; batch-level reuse, Section III-C).
+//
+// Planned arm: one workgroup per distinct (i1,i2) prefix forms the prefix product
+// P12 = G1[i1] x G2[i2] once in LDS and multiplies it with G3[i3] for every distinct row
+// under that prefix; a second kernel sums the rows of each bag (gather-bound).
+// Naive arm: one workgroup per bag runs the full three-slice chain for every lookup.
+#include "tt_internal.h"
+
+namespace {
+
+// P12[j1][j2][r2] = sum_r1 G1[i1][j1][r1] * G2[r1][i2][j2][r2], written to LDS with row stride
+// R2p over (j1,j2).  g1s must already hold the core-0 slice.  Consecutive threads take
+// consecutive (j2,r2) so the core-1 reads are coalesced 4-byte streams of S2 floats per r1.
+__device__ __forceinline__ void prefix_product(const TTShape &sh, const float *__restrict__ g2,
+                                               int i2, const float *g1s, float *p12) {
+  for (int o = threadIdx.x; o < sh.P; o += blockDim.x) {
+    const int j1 = o / sh.S2, c = o - j1 * sh.S2;
+    const float *col = g2 + (size_t)i2 * sh.S2 + c;
+    float acc = 0.f;
+    for (int r1 = 0; r1 < sh.R1; ++r1)
+      acc = fmaf(g1s[j1 * sh.R1 + r1], col[(size_t)r1 * sh.n2 * sh.S2], acc);
+    const int jj = j1 * sh.d2 + c / sh.R2, r2 = c % sh.R2;
+    p12[jj * sh.R2p + r2] = acc;
+  }
+}
+
+// row[(j1,j2)][j3] = sum_r2 P12[(j1,j2)][r2] * G3[r2][i3][j3] for output element o < D.
+__device__ __forceinline__ float row_element(const TTShape &sh, const float *p12,
+                                             const float *g3s, int o) {
+  const int jj = o / sh.d3, j3 = o - jj * sh.d3;
+  float acc = 0.f;
+  for (int r2 = 0; r2 < sh.R2; ++r2) acc = fmaf(p12[jj * sh.R2p + r2], g3s[r2 * sh.d3 + j3], acc);
+  return acc;
+}
+
+__device__ __forceinline__ void load_g3_slice(const TTShape &sh, const float *__restrict__ g3,
+                                              int i3, float *g3s, int tid, int nthreads) {
+  for (int e = tid; e < sh.S3; e += nthreads) {
+    const int r2 = e / sh.d3, j3 = e - r2 * sh.d3;
+    g3s[e] = g3[((size_t)r2 * sh.n3 + i3) * sh.d3 + j3];
+  }
+}
+
+// LDS layout (floats): g1s[S1] | p12[d1*d2*R2p] | g3s[rows_per_iter * S3]
+__global__ void __launch_bounds__(TT_BLOCK)
+k_fwd_prefix_rows(TTShape sh, const float *__restrict__ g1, const float *__restrict__ g2,
+                  const float *__restrict__ g3, const int32_t *__restrict__ counts,
+                  const int32_t *__restrict__ uniq_pref, const int32_t *__restrict__ pref_seg,
+                  const int32_t *__restrict__ uniq_row, float *__restrict__ rowbuf,
+                  int rows_per_iter) {
+  extern __shared__ float lds[];
+  float *g1s = lds, *p12 = g1s + sh.S1, *g3s = p12 + sh.d1 * sh.d2 * sh.R2p;
+  const int up = counts[1];
+  for (int q = blockIdx.x; q < up; q += gridDim.x) {
+    const int p = uniq_pref[q], i1 = p / sh.n2, i2 = p - i1 * sh.n2;
+    for (int e = threadIdx.x; e < sh.S1; e += blockDim.x) g1s[e] = g1[(size_t)i1 * sh.S1 + e];
+    __syncthreads();
+    prefix_product(sh, g2, i2, g1s, p12);
+    __syncthreads();
+    const int u0 = pref_seg[q], u1 = pref_seg[q + 1];
+    // rows_per_iter rows at a time: thread group `sub` owns row u + sub
+    const int sub = threadIdx.x / sh.D, tin = threadIdx.x - sub * sh.D;
+    for (int u = u0; u < u1; u += rows_per_iter) {
+      if (rows_per_iter == 1) {
+        load_g3_slice(sh, g3, uniq_row[u] % sh.n3, g3s, threadIdx.x, blockDim.x);
+      } else if (sub < rows_per_iter && u + sub < u1) {
+        load_g3_slice(sh, g3, uniq_row[u + sub] % sh.n3, g3s + sub * sh.S3, tin, sh.D);
+      }
+      __syncthreads();
+      if (rows_per_iter == 1) {
+        for (int o = threadIdx.x; o < sh.D; o += blockDim.x)
+          rowbuf[(size_t)u * sh.D + o] = row_element(sh, p12, g3s, o);
+      } else if (sub < rows_per_iter && u + sub < u1) {
+        rowbuf[(size_t)(u + sub) * sh.D + tin] = row_element(sh, p12, g3s + sub * sh.S3, tin);
+      }
+      __syncthreads();
+    }
+  }
+}
+
+// out[b][:] = sum over the lookups of bag b of rowbuf[lookup2row[l]][:].
+// A group of LANES lanes owns one bag; each lane owns VEC consecutive columns per step.
+template <int VEC>
+__global__ void __launch_bounds__(TT_BLOCK)
+k_bag_sum(int D, int lanes, const int64_t *__restrict__ offsets, int num_bags, int nnz,
+          const int32_t *__restrict__ lookup2row, const float *__restrict__ rowbuf,
+          float *__restrict__ out) {
+  const int groups_per_block = blockDim.x / lanes;
+  const int g = threadIdx.x / lanes, lane = threadIdx.x - g * lanes;
+  for (int b = blockIdx.x * groups_per_block + g; b < num_bags; b += gridDim.x * groups_per_block) {
+    // offsets are clamped to [0, nnz] so that a malformed CSR array cannot index out of bounds
+    const long long o0 = offsets[b], o1 = offsets[b + 1];
+    const int l0 = o0 < 0 ? 0 : (o0 > nnz ? nnz : (int)o0), l1 = o1 < l0 ? l0 : (o1 > nnz ? nnz : (int)o1);
+    for (int c = lane * VEC; c < D; c += lanes * VEC) {
+      float acc[VEC];
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
+      int l = l0;
+      for (; l + 4 <= l1; l += 4) {  // four independent gathers in flight, summed in order
+        int u[4];
+        float x[4][VEC];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) u[k] = lookup2row[l + k];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          if (u[k] >= 0) {
+            if (VEC == 4) {
+              const float4 t = *reinterpret_cast<const float4 *>(rowbuf + (size_t)u[k] * D + c);
+              x[k][0] = t.x; x[k][1 % VEC] = t.y; x[k][2 % VEC] = t.z; x[k][3 % VEC] = t.w;
+            } else {
+              x[k][0] = rowbuf[(size_t)u[k] * D + c];
+            }
+          } else {
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) x[k][v] = 0.f;
+          }
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+#pragma unroll
+          for (int v = 0; v < VEC; ++v) acc[v] += x[k][v];
+      }
+      for (; l < l1; ++l) {
+        const int u = lookup2row[l];
+        if (u < 0) continue;
+        if (VEC == 4) {
+          const float4 t = *reinterpret_cast<const float4 *>(rowbuf + (size_t)u * D + c);
+          acc[0] += t.x; acc[1 % VEC] += t.y; acc[2 % VEC] += t.z; acc[3 % VEC] += t.w;
+        } else {
+          acc[0] += rowbuf[(size_t)u * D + c];
+        }
+      }
+      if (VEC == 4) {
+        *reinterpret_cast<float4 *>(out + (size_t)b * D + c) =
+            make_float4(acc[0], acc[1 % VEC], acc[2 % VEC], acc[3 % VEC]);
+      } else {
+        out[(size_t)b * D + c] = acc[0];
+      }
+    }
+  }
+}
+
+// Naive arm: workgroup per bag; every lookup recomputes its prefix product and row.
+// LDS layout: g1s[S1] | p12[d1*d2*R2p] | g3s[S3]
+__global__ void __launch_bounds__(TT_BLOCK)
+k_fwd_naive(TTShape sh, const float *__restrict__ g1, const float *__restrict__ g2,
+            const float *__restrict__ g3, const int64_t *__restrict__ indices,
+            const int64_t *__restrict__ offsets, int num_bags, int nnz,
+            float *__restrict__ out) {
+  extern __shared__ float lds[];
+  float *g1s = lds, *p12 = g1s + sh.S1, *g3s = p12 + sh.d1 * sh.d2 * sh.R2p;
+  constexpr int MAXO = 4;  // D <= 1024 columns over 256 threads
+  for (int b = blockIdx.x; b < num_bags; b += gridDim.x) {
+    float acc[MAXO];
+#pragma unroll
+    for (int k = 0; k < MAXO; ++k) acc[k] = 0.f;
+    long long l0 = offsets[b], l1 = offsets[b + 1];  // clamped: malformed offsets stay in bounds
+    l0 = l0 < 0 ? 0 : (l0 > nnz ? nnz : l0);
+    l1 = l1 < l0 ? l0 : (l1 > nnz ? nnz : l1);
+    for (long long l = l0; l < l1; ++l) {
+      const long long row = indices[l];
+      if (row < 0 || row >= sh.num_rows) continue;  // uniform across the workgroup
+      const int i3 = (int)(row % sh.n3), p = (int)(row / sh.n3), i1 = p / sh.n2,
+                i2 = p - i1 * sh.n2;
+      for (int e = threadIdx.x; e < sh.S1; e += blockDim.x) g1s[e] = g1[(size_t)i1 * sh.S1 + e];
+      load_g3_slice(sh, g3, i3, g3s, threadIdx.x, blockDim.x);
+      __syncthreads();
+      prefix_product(sh, g2, i2, g1s, p12);
+      __syncthreads();
+#pragma unroll
+      for (int k = 0; k < MAXO; ++k) {
+        const int o = threadIdx.x + k * TT_BLOCK;
+        if (o < sh.D) acc[k] += row_element(sh, p12, g3s, o);
+      }
+      __syncthreads();
+    }
+#pragma unroll
+    for (int k = 0; k < MAXO; ++k) {
+      const int o = threadIdx.x + k * TT_BLOCK;
+      if (o < sh.D) out[(size_t)b * sh.D + o] = acc[k];
+    }
+  }
+}
+
+size_t fwd_lds_bytes(const TTShape &sh, int rows_per_iter) {
+  return sizeof(float) * ((size_t)sh.S1 + (size_t)sh.d1 * sh.d2 * sh.R2p +
+                          (size_t)rows_per_iter * sh.S3);
+}
+
+}  // namespace
+
+tt_status ttk_forward_plan(const TTShape &sh, const tt_table *t, const tt_plan *plan,
+                           const int64_t *offsets, int64_t num_bags, float *out, hipStream_t s) {
+  if (plan->max_prefixes > 0) {
+    int rows_per_iter = TT_BLOCK / sh.D;
+    if (rows_per_iter < 1) rows_per_iter = 1;
+    if (rows_per_iter > 8) rows_per_iter = 8;
+    long long blocks = plan->max_prefixes < 4096 ? plan->max_prefixes : 4096;
+    hipLaunchKernelGGL(k_fwd_prefix_rows, dim3((unsigned)blocks), dim3(TT_BLOCK),
+                       fwd_lds_bytes(sh, rows_per_iter), s, sh, t->core[0], t->core[1],
+                       t->core[2], plan->counts, plan->uniq_pref, plan->pref_seg, plan->uniq_row,
+                       plan->rowbuf, rows_per_iter);
+  }
+  if (num_bags > 0) {
+    const bool vec4 = (sh.D % 4) == 0 && ((uintptr_t)out % 16) == 0;
+    int lanes = 1;
+    while (lanes < TT_WAVE && lanes * (vec4 ? 4 : 1) < sh.D) lanes <<= 1;
+    const int groups = TT_BLOCK / lanes;
+    long long blocks = (num_bags + groups - 1) / groups;
+    if (blocks > 16384) blocks = 16384;
+    if (vec4)
+      hipLaunchKernelGGL(k_bag_sum<4>, dim3((unsigned)blocks), dim3(TT_BLOCK), 0, s, sh.D, lanes,
+                         offsets, (int)num_bags, (int)plan->nnz, plan->lookup2row, plan->rowbuf, out);
+    else
+      hipLaunchKernelGGL(k_bag_sum<1>, dim3((unsigned)blocks), dim3(TT_BLOCK), 0, s, sh.D, lanes,
+                         offsets, (int)num_bags, (int)plan->nnz, plan->lookup2row, plan->rowbuf, out);
+  }
+  return tt_launch_status();
+}
+
+tt_status ttk_forward_naive(const TTShape &sh, const tt_table *t, const int64_t *indices,
+                            const int64_t *offsets, int64_t nnz, int64_t num_bags, float *out,
+                            hipStream_t s) {
+  if (num_bags == 0) return TT_OK;
+  long long blocks = num_bags < 65536 ? num_bags : 65536;
+  hipLaunchKernelGGL(k_fwd_naive, dim3((unsigned)blocks), dim3(TT_BLOCK), fwd_lds_bytes(sh, 1), s,
+                     sh, t->core[0], t->core[1], t->core[2], indices, offsets, (int)num_bags, (int)nnz,
+                     out);
+  return tt_launch_status();
+}

@@ -1,0 +1,109 @@
+// Internal declarations shared by the HIP translation units of the TT embedding-bag library.
+// Nothing here is part of the C ABI (see include/tt_emb.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tt_emb.h"
+
+// Derived shape of one table, passed by value to kernels.
+struct TTShape {
+  int n1, n2, n3;
+  int d1, d2, d3;
+  int R1, R2;
+  int D;    // d1*d2*d3   columns of a row
+  int S1;   // d1*R1      floats of a core-0 slice
+  int S2;   // d2*R2      floats of one r1-chunk of a core-1 slice
+  int S3;   // R2*d3      floats of a core-2 slice
+  int P;    // d1*d2*R2   floats of a prefix product G1[i1] x G2[i2]
+  int R2p;  // padded LDS row stride for [.][R2] tiles (odd, avoids bank conflicts)
+  int sentinel;       // n1*n2*n3, sort key of an invalid lookup
+  long long num_rows;
+};
+
+#define TT_WAVE 64
+#define TT_BLOCK 256
+
+// ---- radix sort geometry ----------------------------------------------------------------
+#define TT_SORT_ITEMS 8
+#define TT_SORT_TILE (TT_BLOCK * TT_SORT_ITEMS)  // keys per workgroup per pass
+#define TT_SORT_MAX_BITS 10                      // digit width limit (1024 bins)
+
+// ---- segmented-reduction geometry -----------------------------------------------------------
+#define TT_SEG_CHUNK 64  // positions per chunk of the two-stage segmented sum
+
+static inline int tt_ceil_div(long long a, long long b) { return (int)((a + b - 1) / b); }
+
+// Launchers (host).  Each enqueues kernels on `s` and returns the launch status.
+tt_status ttk_reorder(const TTShape &sh, const int64_t *indices, const int64_t *offsets,
+                      int64_t nnz, int64_t num_bags, const int64_t *remap, const tt_plan *plan,
+                      hipStream_t s);
+tt_status ttk_forward_plan(const TTShape &sh, const tt_table *t, const tt_plan *plan,
+                           const int64_t *offsets, int64_t num_bags, float *out, hipStream_t s);
+tt_status ttk_forward_naive(const TTShape &sh, const tt_table *t, const int64_t *indices,
+                            const int64_t *offsets, int64_t nnz, int64_t num_bags, float *out,
+                            hipStream_t s);
+tt_status ttk_backward_plan(const TTShape &sh, const tt_table *t, const tt_plan *plan,
+                            const float *grad_out, float *const dcore[3], hipStream_t s);
+tt_status ttk_backward_naive(const TTShape &sh, const tt_table *t, const int64_t *indices,
+                             const int64_t *offsets, int64_t nnz, int64_t num_bags,
+                             const float *grad_out, float *const dcore[3], hipStream_t s);
+tt_status ttk_sgd(const TTShape &sh, const tt_table *t, const tt_plan *plan,
+                  const float *const dcore[3], float lr, hipStream_t s);
+
+// Sort scratch carved from plan->sort_tmp (all int32 arrays).
+struct TTSortTmp {
+  int32_t *keys_alt, *vals_alt;    // [nnz] ping-pong partner of (sorted_row, perm)
+  int32_t *bag_tmp;                // [nnz] bag of each original lookup position
+  int32_t *k3_alt, *v3_alt;        // [max_rows]
+  int32_t *k2, *k2_alt, *v2_alt;   // [max_prefixes]
+  int32_t *hist;                   // [bins][tiles] per-tile digit histograms
+  int32_t *bin_total;              // [bins]
+  int32_t *tile_sums;              // [2][tiles] head counts per tile of the unique pass
+};
+TTSortTmp tt_sort_tmp_view(const tt_plan *plan);
+size_t tt_sort_tmp_bytes(int64_t nnz, int64_t max_rows, int64_t max_prefixes);
+
+static inline tt_status tt_launch_status() {
+  return hipGetLastError() == hipSuccess ? TT_OK : TT_ERR_HIP;
+}
+
+// ---- device helpers -----------------------------------------------------------------------
+#ifdef __HIPCC__
+__device__ __forceinline__ int tt_wave_incl_scan(int v) {
+  const int lane = threadIdx.x & (TT_WAVE - 1);
+#pragma unroll
+  for (int o = 1; o < TT_WAVE; o <<= 1) {
+    int t = __shfl_up(v, o, TT_WAVE);
+    if (lane >= o) v += t;
+  }
+  return v;
+}
+
+// Exclusive scan of one int per thread over a TT_BLOCK-thread workgroup.
+// `tmp` is LDS with at least TT_BLOCK/TT_WAVE + 1 ints.  Returns the exclusive prefix;
+// *total receives the workgroup sum.  Contains two barriers.
+__device__ __forceinline__ int tt_block_excl_scan(int v, int *tmp, int *total) {
+  const int lane = threadIdx.x & (TT_WAVE - 1), wave = threadIdx.x / TT_WAVE;
+  int incl = tt_wave_incl_scan(v);
+  if (lane == TT_WAVE - 1) tmp[wave] = incl;
+  __syncthreads();
+  int base = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < TT_BLOCK / TT_WAVE; ++w) {
+    int x = tmp[w];
+    if (w < wave) base += x;
+    tot += x;
+  }
+  __syncthreads();
+  *total = tot;
+  return base + incl - v;
+}
+
+__device__ __forceinline__ float tt_wave_sum(float v) {
+#pragma unroll
+  for (int o = TT_WAVE / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, TT_WAVE);
+  return v;
+}
+#endif

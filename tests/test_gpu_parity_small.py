@@ -1,0 +1,165 @@
+"""GPU parity (through the C ABI) against the CPU oracle: small shapes, configs 1-2, edge cases."""
+import numpy as np
+import pytest
+import torch
+
+import tt_workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def g():
+    import gpu_util
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    return gpu_util
+
+
+def run_all(g, ora, shape, cores, idx, off, grad, lr=0.01, check_plan=True, remap=None):
+    import paper_2507_14668_amd as tt
+    table = g.gpu_table(shape, cores)
+    d_idx, d_off, d_grad = g.to_dev(idx, torch.int64), g.to_dev(off, torch.int64), g.to_dev(grad, torch.float32)
+    d_remap = None if remap is None else g.to_dev(remap, torch.int64)
+    o_idx = idx if remap is None else np.where((idx >= 0) & (idx < shape.num_rows), remap[np.clip(idx, 0, shape.num_rows - 1)], -1)
+    plan = tt.tt_index_reorder(table, d_idx, d_off, remap=d_remap)
+    if check_plan:
+        ref = ora.reorder_plan(shape, idx, off, remap=remap)
+        got = plan.arrays()
+        nv = ref["num_valid"]
+        assert got["num_valid"] == nv and got["U_r"] == len(ref["uniq_row"]) and got["U_p"] == len(ref["uniq_pref"])
+        for key in ("perm", "sorted_row", "bag_of_sorted"):
+            assert np.array_equal(got[key][:nv], ref[key]), key
+        for key in ("uniq_row", "row_seg", "lookup2row", "uniq_pref", "pref_seg", "row2pref"):
+            assert np.array_equal(got[key], ref[key]), key
+        # groupings: stable by i3 / i2, ranges consistent
+        i3 = ref["uniq_row"] % shape.n[2]
+        assert np.array_equal(got["rows_by_i3"], np.argsort(i3, kind="stable"))
+        assert np.array_equal(got["i3_of_sorted"], np.sort(i3))
+        assert np.array_equal(got["i3_seg"], np.searchsorted(np.sort(i3), np.arange(shape.n[2] + 1)))
+        i2 = ref["uniq_pref"] % shape.n[1]
+        assert np.array_equal(got["prefs_by_i2"], np.argsort(i2, kind="stable"))
+        assert np.array_equal(got["i2_seg"], np.searchsorted(np.sort(i2), np.arange(shape.n[1] + 1)))
+        i1 = ref["uniq_pref"] // shape.n[1]
+        assert np.array_equal(got["i1_seg"], np.searchsorted(i1, np.arange(shape.n[0] + 1)))
+    ref_out = ora.forward(shape, cores, np.where(o_idx < 0, shape.num_rows, o_idx) if remap is not None else idx, off)
+    out_plan = tt.tt_emb_bag_forward(table, plan, d_idx, d_off)
+    g.assert_close_rows(out_plan.cpu().numpy(), ref_out, g.FWD_RTOL, shape.dim, "forward(plan)")
+    if remap is None:
+        out_naive = tt.tt_emb_bag_forward(table, None, d_idx, d_off)
+        g.assert_close_rows(out_naive.cpu().numpy(), ref_out, g.FWD_RTOL, shape.dim, "forward(naive)")
+    ref_dg = ora.backward(shape, cores, np.where(o_idx < 0, shape.num_rows, o_idx) if remap is not None else idx, off, grad)
+    dg_plan = tt.tt_emb_bag_backward(table, plan, d_idx, d_off, d_grad)
+    g.assert_grads_close(shape, dg_plan, ref_dg, what="dG(plan)")
+    if remap is None:
+        dg_naive = tt.tt_emb_bag_backward(table, None, d_idx, d_off, d_grad)
+        g.assert_grads_close(shape, dg_naive, ref_dg, what="dG(naive)")
+    # determinism of the planned arm: a second run is bitwise identical
+    out2 = tt.tt_emb_bag_forward(table, plan, d_idx, d_off)
+    dg2 = tt.tt_emb_bag_backward(table, plan, d_idx, d_off, d_grad)
+    assert torch.equal(out2, out_plan)
+    for k in range(3):
+        assert torch.equal(dg2[k], dg_plan[k])
+    # update: touched-slices arm and dense arm against the oracle
+    ref_new = ora.sgd(cores, ref_dg, lr)
+    t2 = g.gpu_table(shape, cores)
+    tt.tt_core_sgd_update(table, plan, dg_plan, lr)
+    tt.tt_core_sgd_update(t2, None, dg_plan, lr)
+    torch.cuda.synchronize()
+    for k in range(3):
+        assert torch.equal(table.cores[k], t2.cores[k]), "touched-slice update differs from dense update"
+    g.assert_grads_close(shape, table.cores, ref_new, what="updated G")
+    return plan
+
+
+@pytest.mark.parametrize("seed,n,d,r,nb,ml", [
+    (1, (3, 4, 5), (2, 3, 2), (1, 3, 4, 1), 40, 6),
+    (2, (2, 2, 2), (2, 2, 2), (1, 2, 2, 1), 5, 3),
+    (3, (5, 2, 7), (1, 4, 3), (1, 5, 2, 1), 300, 9),
+    (4, (7, 6, 5), (4, 2, 4), (1, 8, 16, 1), 1000, 12),
+    (5, (1, 1, 9), (2, 2, 2), (1, 1, 1, 1), 50, 4),
+])
+def test_small_shapes(g, ora, seed, n, d, r, nb, ml):
+    print("case small_shapes seed=%d n=%s d=%s r=%s" % (seed, n, d, r), flush=True)
+    shape, cores, idx, off, grad = wl.small_random_problem(seed, n=n, d=d, r=r, num_bags=nb, max_len=ml)
+    run_all(g, ora, shape, cores, idx, off, grad)
+
+
+def test_padded_table_and_remap(g, ora):
+    print("case padded+remap", flush=True)
+    shape, cores, idx, off, grad = wl.small_random_problem(11, n=(4, 5, 6), d=(2, 2, 4), r=(1, 4, 4, 1),
+                                                          num_rows=101, num_bags=200, max_len=5)
+    run_all(g, ora, shape, cores, idx, off, grad)
+    remap = np.random.default_rng(2).permutation(shape.num_rows).astype(np.int64)
+    run_all(g, ora, shape, cores, idx, off, grad, remap=remap)
+
+
+@pytest.mark.parametrize("cfg_id", [1, 2])
+def test_config_full(g, ora, cfg_id):
+    print("case config %d" % cfg_id, flush=True)
+    cfg = wl.get_config(cfg_id)
+    shape, cores = cfg.tables[0], wl.make_cores(cfg, 0)
+    idx, off = wl.make_batch(cfg, 0)
+    run_all(g, ora, shape, cores, idx, off, wl.make_grad(cfg, 0), lr=cfg.lr)
+
+
+def test_empty_batch_and_empty_bags(g, ora):
+    print("case empty", flush=True)
+    shape, cores, *_ = wl.small_random_problem(21)
+    grad = np.random.default_rng(0).standard_normal(4 * shape.dim).astype(np.float32)
+    run_all(g, ora, shape, cores, np.zeros(0, np.int64), np.zeros(5, np.int64), grad)
+    run_all(g, ora, shape, cores, np.array([3, 3, 59], np.int64), np.array([0, 0, 2, 2, 3], np.int64), grad)
+
+
+def test_hot_row_and_long_bag_span_many_chunks(g, ora):
+    """One row repeated thousands of times (a segment spanning many reduction chunks) and one
+    very long bag; also every lookup in one prefix."""
+    print("case hot row", flush=True)
+    shape, cores, *_ = wl.small_random_problem(22, n=(3, 4, 50), d=(2, 4, 4), r=(1, 8, 8, 1))
+    rng = np.random.default_rng(1)
+    idx = np.concatenate([np.full(5000, 7), rng.integers(0, 50, 3000), rng.integers(0, shape.num_rows, 500)]).astype(np.int64)
+    rng.shuffle(idx)
+    off = np.array([0, 6000, 6001, 8500], np.int64)
+    off = np.concatenate([off[:-1], np.arange(6001, 8501, 1)[1:]]).astype(np.int64)
+    nb = len(off) - 1
+    grad = rng.standard_normal(nb * shape.dim).astype(np.float32)
+    run_all(g, ora, shape, cores, idx, off, grad)
+
+
+def test_invalid_indices_are_reported_and_skipped(g, ora):
+    import paper_2507_14668_amd as tt
+    from paper_2507_14668_amd import binding
+    print("case invalid", flush=True)
+    shape, cores, idx, off, grad = wl.small_random_problem(23, num_bags=60, max_len=5, num_rows=55)
+    idx = idx.copy()
+    idx[2], idx[17] = -3, 57  # 57 is inside the padded n1*n2*n3 range but >= num_rows
+    plan = run_all(g, ora, shape, cores, idx, off, grad)
+    assert tt.tt_plan_status(plan) == binding.TT_ERR_INDEX_RANGE
+    table = g.gpu_table(shape, cores)
+    good = np.abs(idx) % 55
+    ok = tt.tt_index_reorder(table, g.to_dev(good, torch.int64), g.to_dev(off, torch.int64))
+    assert tt.tt_plan_status(ok) == binding.TT_OK
+    # offsets that are not monotone (still inside [0, nnz]) are reported; kernels clamp them
+    bad_off = off.copy()
+    k = int(np.argmax(np.diff(off) > 0))
+    bad_off[k], bad_off[k + 1] = bad_off[k + 1], bad_off[k]
+    bad = tt.tt_index_reorder(table, g.to_dev(good, torch.int64), g.to_dev(bad_off, torch.int64))
+    counts, st = bad.counts()
+    assert st == binding.TT_ERR_INDEX_RANGE and counts[3] & 2
+    out = tt.tt_emb_bag_forward(table, bad, g.to_dev(good, torch.int64), g.to_dev(bad_off, torch.int64))
+    assert torch.isfinite(out).all()
+
+
+def test_host_side_argument_errors(g):
+    import paper_2507_14668_amd as tt
+    from paper_2507_14668_amd import binding
+    shape, cores, idx, off, grad = wl.small_random_problem(24)
+    table = g.gpu_table(shape, cores)
+    small = torch.empty(256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(tt.TTError) as e:
+        tt.tt_index_reorder(table, g.to_dev(idx, torch.int64), g.to_dev(off, torch.int64), workspace=small)
+    assert e.value.status == binding.TT_ERR_WORKSPACE
+    bad = tt.Table(shape.num_rows, shape.n, shape.d, shape.r, table.cores)
+    bad.c.r[0] = 2
+    with pytest.raises(tt.TTError) as e:
+        tt.tt_emb_bag_forward(bad, None, g.to_dev(idx, torch.int64), g.to_dev(off, torch.int64))
+    assert e.value.status == binding.TT_ERR_SHAPE
