@@ -78,6 +78,23 @@ k_fwd_prefix_rows(TTShape sh, const float *__restrict__ g1, const float *__restr
   }
 }
 
+#define TT_BAG_BLOCK 64
+
+// VEC consecutive columns of distinct row u (zeros for an invalid lookup, u < 0).
+template <int VEC>
+__device__ __forceinline__ void load_row_vec(const float *__restrict__ rowbuf, int u, int D, int c,
+                                             float (&x)[VEC]) {
+  if (u < 0) {
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) x[v] = 0.f;
+  } else if (VEC == 4) {
+    const float4 t = *reinterpret_cast<const float4 *>(rowbuf + (size_t)u * D + c);
+    x[0] = t.x; x[1 % VEC] = t.y; x[2 % VEC] = t.z; x[3 % VEC] = t.w;
+  } else {
+    x[0] = rowbuf[(size_t)u * D + c];
+  }
+}
+
 // out[b][:] = sum over the lookups of bag b of rowbuf[lookup2row[l]][:].
 // A group of LANES lanes owns one bag; each lane owns VEC consecutive columns per step.
 template <int VEC>
@@ -92,49 +109,41 @@ k_bag_sum(int D, int lanes, const int64_t *__restrict__ offsets, int num_bags, i
     const long long o0 = offsets[b], o1 = offsets[b + 1];
     const int l0 = o0 < 0 ? 0 : (o0 > nnz ? nnz : (int)o0), l1 = o1 < l0 ? l0 : (o1 > nnz ? nnz : (int)o1);
     for (int c = lane * VEC; c < D; c += lanes * VEC) {
-      float acc[VEC];
+      // two-level sum: blocks of TT_BAG_BLOCK lookups are summed first and then added to the
+      // running total, so rounding error grows with len/TT_BAG_BLOCK instead of len
+      float tot[VEC];
 #pragma unroll
-      for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
-      int l = l0;
-      for (; l + 4 <= l1; l += 4) {  // four independent gathers in flight, summed in order
-        int u[4];
-        float x[4][VEC];
+      for (int v = 0; v < VEC; ++v) tot[v] = 0.f;
+      for (int base = l0; base < l1; base += TT_BAG_BLOCK) {
+        const int stop = base + TT_BAG_BLOCK < l1 ? base + TT_BAG_BLOCK : l1;
+        float acc[VEC];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) u[k] = lookup2row[l + k];
+        for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
+        int l = base;
+        for (; l + 4 <= stop; l += 4) {  // four independent gathers in flight
+          int u[4];
+          float x[4][VEC];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          if (u[k] >= 0) {
-            if (VEC == 4) {
-              const float4 t = *reinterpret_cast<const float4 *>(rowbuf + (size_t)u[k] * D + c);
-              x[k][0] = t.x; x[k][1 % VEC] = t.y; x[k][2 % VEC] = t.z; x[k][3 % VEC] = t.w;
-            } else {
-              x[k][0] = rowbuf[(size_t)u[k] * D + c];
-            }
-          } else {
+          for (int k = 0; k < 4; ++k) u[k] = lookup2row[l + k];
 #pragma unroll
-            for (int v = 0; v < VEC; ++v) x[k][v] = 0.f;
-          }
+          for (int k = 0; k < 4; ++k) load_row_vec<VEC>(rowbuf, u[k], D, c, x[k]);
+#pragma unroll
+          for (int v = 0; v < VEC; ++v) acc[v] += (x[0][v] + x[1][v]) + (x[2][v] + x[3][v]);
+        }
+        for (; l < stop; ++l) {
+          float x[VEC];
+          load_row_vec<VEC>(rowbuf, lookup2row[l], D, c, x);
+#pragma unroll
+          for (int v = 0; v < VEC; ++v) acc[v] += x[v];
         }
 #pragma unroll
-        for (int k = 0; k < 4; ++k)
-#pragma unroll
-          for (int v = 0; v < VEC; ++v) acc[v] += x[k][v];
-      }
-      for (; l < l1; ++l) {
-        const int u = lookup2row[l];
-        if (u < 0) continue;
-        if (VEC == 4) {
-          const float4 t = *reinterpret_cast<const float4 *>(rowbuf + (size_t)u * D + c);
-          acc[0] += t.x; acc[1 % VEC] += t.y; acc[2 % VEC] += t.z; acc[3 % VEC] += t.w;
-        } else {
-          acc[0] += rowbuf[(size_t)u * D + c];
-        }
+        for (int v = 0; v < VEC; ++v) tot[v] += acc[v];
       }
       if (VEC == 4) {
         *reinterpret_cast<float4 *>(out + (size_t)b * D + c) =
-            make_float4(acc[0], acc[1 % VEC], acc[2 % VEC], acc[3 % VEC]);
+            make_float4(tot[0], tot[1 % VEC], tot[2 % VEC], tot[3 % VEC]);
       } else {
-        out[(size_t)b * D + c] = acc[0];
+        out[(size_t)b * D + c] = tot[0];
       }
     }
   }
@@ -151,14 +160,18 @@ k_fwd_naive(TTShape sh, const float *__restrict__ g1, const float *__restrict__ 
   float *g1s = lds, *p12 = g1s + sh.S1, *g3s = p12 + sh.d1 * sh.d2 * sh.R2p;
   constexpr int MAXO = 4;  // D <= 1024 columns over 256 threads
   for (int b = blockIdx.x; b < num_bags; b += gridDim.x) {
-    float acc[MAXO];
+    float acc[MAXO], tot[MAXO];
 #pragma unroll
-    for (int k = 0; k < MAXO; ++k) acc[k] = 0.f;
+    for (int k = 0; k < MAXO; ++k) acc[k] = tot[k] = 0.f;
     long long l0 = offsets[b], l1 = offsets[b + 1];  // clamped: malformed offsets stay in bounds
     l0 = l0 < 0 ? 0 : (l0 > nnz ? nnz : l0);
     l1 = l1 < l0 ? l0 : (l1 > nnz ? nnz : l1);
     for (long long l = l0; l < l1; ++l) {
       const long long row = indices[l];
+      if (((l - l0) % TT_BAG_BLOCK) == 0) {  // two-level sum as in the planned arm
+#pragma unroll
+        for (int k = 0; k < MAXO; ++k) { tot[k] += acc[k]; acc[k] = 0.f; }
+      }
       if (row < 0 || row >= sh.num_rows) continue;  // uniform across the workgroup
       const int i3 = (int)(row % sh.n3), p = (int)(row / sh.n3), i1 = p / sh.n2,
                 i2 = p - i1 * sh.n2;
@@ -177,7 +190,7 @@ k_fwd_naive(TTShape sh, const float *__restrict__ g1, const float *__restrict__ 
 #pragma unroll
     for (int k = 0; k < MAXO; ++k) {
       const int o = threadIdx.x + k * TT_BLOCK;
-      if (o < sh.D) out[(size_t)b * sh.D + o] = acc[k];
+      if (o < sh.D) out[(size_t)b * sh.D + o] = tot[k] + acc[k];
     }
   }
 }
