@@ -1,0 +1,197 @@
+#!/usr/bin/env python3
+"""Throughput of the TT embedding-bag hot path on one MI355X.
+
+One step = one pass of the whole hot path over one batch of every table of the workload:
+index reorder (for the NEXT batch, on a second stream) || forward + backward + core update
+(for the current batch).  Inputs are synthetic (tt_workloads.py), resident in HBM before the
+timed region.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0      # MI355X HBM3E, published
+PEAK_FP32_TFLOPS = 157.3   # MI355X fp32 (vector or matrix), published
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg5", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--arm", default="plan", choices=["plan", "naive"])
+    ap.add_argument("--no-overlap", action="store_true", help="reorder on the compute stream")
+    ap.add_argument("--permute", action="store_true", help="seeded random row permutation of the Zipf ranks")
+    ap.add_argument("--batches", type=int, default=8, help="distinct batches cycled through")
+    ap.add_argument("--tables", type=int, default=0, help="use only the first T tables (0 = all)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--prof-kernel", default="auto", help="kernel bracketed with HIP events for the roofline")
+    return ap.parse_args()
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    import paper_2507_14668_amd as tt
+    import tt_workloads as wl
+    from paper_2507_14668_amd import binding
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    tt.load_library()
+    cfg_id = int(args.workload[3:])
+    cfg = wl.get_config(cfg_id)
+    do_fwd = cfg_id != 4 or True
+    do_bwd = cfg_id != 3
+    ntab = len(cfg.tables) if args.tables <= 0 else min(args.tables, len(cfg.tables))
+    nbatch = max(2, args.batches + (args.batches % 2))  # even, so batch b always uses plan buffer b%2
+
+    # ---- inputs, resident in HBM ------------------------------------------------------------
+    t_gen = time.time()
+    tabs = []
+    for t in range(ntab):
+        shape = cfg.tables[t]
+        table = tt.Table.from_numpy(shape, wl.make_cores(cfg, t))
+        batches = []
+        for b in range(nbatch):
+            idx, off = wl.make_batch(cfg, t, batch=b, permute_rows=True if args.permute else None)
+            grad = wl.make_grad(cfg, t, batch=b)
+            batches.append(dict(idx=torch.from_numpy(idx).cuda(), off=torch.from_numpy(off).cuda(),
+                                grad=torch.from_numpy(grad).cuda(), nnz=len(idx)))
+        max_nnz = max(x["nnz"] for x in batches)
+        ws = [tt.alloc_workspace(table, max_nnz, cfg.batch) for _ in range(2)] if args.arm == "plan" else None
+        tabs.append(dict(shape=shape, table=table, batches=batches, ws=ws, plans=[None, None],
+                         out=torch.empty((cfg.batch, shape.dim), dtype=torch.float32, device="cuda"),
+                         dcores=table.core_grads_like()))
+    torch.cuda.synchronize()
+    t_gen = time.time() - t_gen
+
+    s1 = torch.cuda.Stream()
+    s2 = s1 if args.no_overlap else torch.cuda.Stream()
+    ready = [torch.cuda.Event(), torch.cuda.Event()]
+    free = [torch.cuda.Event(), torch.cuda.Event()]
+    planned = args.arm == "plan"
+
+    def reorder(b):
+        buf = b % 2
+        for T in tabs:
+            x = T["batches"][b % nbatch]
+            # workspace sized for the largest batch; plan is rebuilt for this batch's nnz
+            T["plans"][buf] = tt.tt_index_reorder(T["table"], x["idx"], x["off"], workspace=T["ws"][buf], stream=s2)
+        ready[buf].record(s2)
+
+    def compute(b):
+        buf = b % 2
+        if planned:
+            s1.wait_event(ready[buf])
+        for T in tabs:
+            x = T["batches"][b % nbatch]
+            plan = T["plans"][buf] if planned else None
+            if do_fwd:
+                tt.tt_emb_bag_forward(T["table"], plan, x["idx"], x["off"], out=T["out"], stream=s1)
+            if do_bwd:
+                tt.tt_emb_bag_backward(T["table"], plan, x["idx"], x["off"], x["grad"], dcores=T["dcores"], stream=s1)
+                tt.tt_core_sgd_update(T["table"], plan, T["dcores"], cfg.lr, stream=s1)
+        free[buf].record(s1)
+
+    def step(b):
+        """reorder(b+1) on s2 while batch b computes on s1; buffer (b+1)%2 was last used by b-1."""
+        if planned:
+            s2.wait_event(free[(b + 1) % 2])
+            reorder(b + 1)
+        compute(b)
+
+    # prologue: plan of batch 0, both 'free' events recorded so the first waits pass
+    free[0].record(s1)
+    free[1].record(s1)
+    if planned:
+        reorder(0)
+    b = 0
+    for _ in range(args.warmup):
+        step(b)
+        b += 1
+    torch.cuda.synchronize()
+    lookups = 0
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(b)
+        lookups += sum(T["batches"][b % nbatch]["nnz"] for T in tabs)
+        b += 1
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    status_bad = 0
+    counts = []
+    if planned:
+        for T in tabs:
+            c, st = T["plans"][(b - 1) % 2].counts()
+            status_bad |= st != 0
+            counts.append(c)
+    assert not status_bad, "a plan reported an index/offset error"
+
+    value = lookups / dt
+    phases = "reorder||fwd" if not do_bwd else "reorder||fwd+bwd+update"
+    result = {
+        "metric": "TT embedding lookups/sec fwd+bwd (1 GPU)", "value": value, "unit": "lookups/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": 1e3 * dt / args.steps, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s: %d TT tables, D=%d, ranks (1,%d,%d,1), batch %d %s bags per table, "
+                               "Zipf(alpha=%g)%s, %s, %s arm" %
+                               (args.workload, ntab, cfg.tables[0].dim, cfg.tables[0].r[1], cfg.tables[0].r[2],
+                                cfg.batch, "multi-hot" if cfg.multi_hot else "one-hot", cfg.alpha,
+                                " + row permutation" if (args.permute or cfg.permute_rows) else "",
+                                phases, args.arm),
+                   "lookups_per_step": lookups // max(1, args.steps), "tables": ntab,
+                   "overlap_second_stream": (not args.no_overlap) and planned,
+                   "input_generation_s": round(t_gen, 1)},
+        "roofline": None,
+        "cpu_baseline": None,
+    }
+    if counts:
+        result["config"]["distinct_rows_last_batch"] = int(sum(c[0] for c in counts))
+        result["config"]["distinct_prefixes_last_batch"] = int(sum(c[1] for c in counts))
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, wl, np)
+    print(json.dumps(result))
+
+
+def cpu_baseline(cfg, wl, np):
+    """The oracle (definition mode, forward + backward) timed on a bounded sample of the workload."""
+    from oracle import tt_oracle as ora
+    tab = int(np.argmax([t.num_rows for t in cfg.tables]))
+    shape, cores = cfg.tables[tab], wl.make_cores(cfg, tab)
+
+    def run(nb):
+        idx, off = wl.make_batch(cfg, tab, num_bags=nb)
+        grad = wl.make_grad(cfg, tab, num_bags=nb)
+        t0 = time.perf_counter()
+        ora.forward(shape, cores, idx, off)
+        ora.backward(shape, cores, idx, off, grad)
+        return len(idx), time.perf_counter() - t0
+
+    nb0 = min(cfg.batch, 64)
+    n0, t0 = run(nb0)
+    nb = int(min(cfg.batch, max(nb0, nb0 * 12.0 / max(t0, 1e-3))))
+    n, t = run(nb)
+    return {"value": n / t, "unit": "lookups/s", "cores": ora.max_threads(), "kind": "oracle",
+            "sample": "definition-mode forward+backward of the first %d bags (%d lookups) of table %d "
+                      "(%d rows), %.1f s" % (nb, n, tab, shape.num_rows, t)}
+
+
+if __name__ == "__main__":
+    main()

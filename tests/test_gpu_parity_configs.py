@@ -1,0 +1,198 @@
+"""GPU parity at the sizes of configs 3-5 (through the C ABI, same launch configuration as
+bench.py): full-size outputs against the oracle's dedup mode (itself pinned to definition mode
+in the CPU suite), definition mode on a reduced batch, Euler's identity on the remaining tables,
+and the two-stream pipeline against the sequential order."""
+import numpy as np
+import pytest
+import torch
+
+import tt_workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def g():
+    import gpu_util
+    assert torch.cuda.is_available()
+    return gpu_util
+
+
+def gpu_step(g, table, idx, off, grad, naive=False):
+    import paper_2507_14668_amd as tt
+    d_idx, d_off = g.to_dev(idx, torch.int64), g.to_dev(off, torch.int64)
+    plan = None if naive else tt.tt_index_reorder(table, d_idx, d_off)
+    out = tt.tt_emb_bag_forward(table, plan, d_idx, d_off)
+    dg = tt.tt_emb_bag_backward(table, plan, d_idx, d_off, g.to_dev(grad, torch.float32))
+    torch.cuda.synchronize()
+    if plan is not None:
+        assert tt.tt_plan_status(plan) == 0
+    return plan, out, dg
+
+
+def euler_check(shape, cores, out, dg, grad):
+    """<dG_k, G_k> = sum_b <out_b, g_b> for k = 1,2,3 (each row is linear in every core)."""
+    o = out.double().cpu().numpy()
+    loss = float((o * grad.reshape(o.shape).astype(np.float64)).sum())
+    scale = float(np.abs(o * grad.reshape(o.shape)).sum())
+    for k in range(3):
+        inner = float(np.dot(dg[k].double().cpu().numpy(), cores[k].astype(np.float64)))
+        assert abs(inner - loss) <= 1e-5 * scale, (k, inner, loss, scale)
+
+
+@pytest.mark.parametrize("permute", [False, True])
+def test_config3_4_reduced_batch_definition_mode(g, ora, permute):
+    print("case cfg3/4 reduced permute=%s" % permute, flush=True)
+    cfg = wl.get_config(4)
+    shape, cores = cfg.tables[0], wl.make_cores(cfg, 0)
+    idx, off = wl.make_batch(cfg, 0, permute_rows=permute, num_bags=1024)
+    grad = wl.make_grad(cfg, 0, num_bags=1024)
+    table = g.gpu_table(shape, cores)
+    ref_out = ora.forward(shape, cores, idx, off)
+    ref_dg = ora.backward(shape, cores, idx, off, grad)
+    for naive in (False, True):
+        _, out, dg = gpu_step(g, table, idx, off, grad, naive=naive)
+        g.assert_close_rows(out.cpu().numpy(), ref_out, g.FWD_RTOL, shape.dim, "cfg3 forward naive=%s" % naive)
+        g.assert_grads_close(shape, dg, ref_dg, what="cfg4 dG naive=%s" % naive)
+
+
+@pytest.mark.parametrize("tab", [0, 7])
+def test_config3_4_full_size(g, ora, tab):
+    import paper_2507_14668_amd as tt
+    print("case cfg3/4 full table %d" % tab, flush=True)
+    cfg = wl.get_config(4)
+    shape, cores = cfg.tables[tab], wl.make_cores(cfg, tab)
+    idx, off = wl.make_batch(cfg, tab)
+    grad = wl.make_grad(cfg, tab)
+    table = g.gpu_table(shape, cores)
+    plan, out, dg = gpu_step(g, table, idx, off, grad)
+    print("  nnz=%d counts=%s" % (len(idx), plan.counts()[0]), flush=True)
+    ref_out = ora.forward(shape, cores, idx, off, dedup=True)
+    g.assert_close_rows(out.cpu().numpy(), ref_out, g.FWD_RTOL, shape.dim, "cfg3 forward")
+    ref_dg = ora.backward(shape, cores, idx, off, grad, dedup=True)
+    g.assert_grads_close(shape, dg, ref_dg, what="cfg4 dG")
+    euler_check(shape, cores, out, dg, grad)
+    # naive arms at full size: forward against the oracle, backward (atomics) against the oracle
+    _, out_n, dg_n = gpu_step(g, table, idx, off, grad, naive=True)
+    g.assert_close_rows(out_n.cpu().numpy(), ref_out, g.FWD_RTOL, shape.dim, "cfg3 forward naive")
+    g.assert_grads_close(shape, dg_n, ref_dg, what="cfg4 dG naive")
+    # update with lr = 0.01
+    ref_new = ora.sgd(cores, ref_dg, cfg.lr)
+    tt.tt_core_sgd_update(table, plan, dg, cfg.lr)
+    torch.cuda.synchronize()
+    g.assert_grads_close(shape, table.cores, ref_new, what="cfg4 updated G")
+
+
+def test_config3_4_other_tables_euler_identity(g):
+    cfg = wl.get_config(4)
+    for tab in (1, 2, 3, 4, 5, 6):
+        print("case cfg3/4 euler table %d" % tab, flush=True)
+        shape, cores = cfg.tables[tab], wl.make_cores(cfg, tab)
+        idx, off = wl.make_batch(cfg, tab)
+        grad = wl.make_grad(cfg, tab)
+        _, out, dg = gpu_step(g, g.gpu_table(shape, cores), idx, off, grad)
+        euler_check(shape, cores, out, dg, grad)
+
+
+def cfg5_tables():
+    cfg = wl.get_config(5)
+    rows = [t.num_rows for t in cfg.tables]
+    order = np.argsort(rows)
+    return cfg, [int(order[0]), int(order[len(order) // 2]), int(order[-1])]
+
+
+def test_config5_full_size_small_mid_large_tables(g, ora):
+    import paper_2507_14668_amd as tt
+    cfg, tabs = cfg5_tables()
+    for tab in tabs:
+        shape, cores = cfg.tables[tab], wl.make_cores(cfg, tab)
+        print("case cfg5 table %d rows=%d n=%s" % (tab, shape.num_rows, shape.n), flush=True)
+        idx, off = wl.make_batch(cfg, tab)
+        grad = wl.make_grad(cfg, tab)
+        table = g.gpu_table(shape, cores)
+        plan, out, dg = gpu_step(g, table, idx, off, grad)
+        print("  counts=%s" % (plan.counts()[0],), flush=True)
+        ref_out = ora.forward(shape, cores, idx, off, dedup=True)
+        g.assert_close_rows(out.cpu().numpy(), ref_out, g.FWD_RTOL, shape.dim, "cfg5 forward")
+        ref_dg = ora.backward(shape, cores, idx, off, grad, dedup=True, max_threads_=8)
+        g.assert_grads_close(shape, dg, ref_dg, what="cfg5 dG")
+        euler_check(shape, cores, out, dg, grad)
+        ref_new = ora.sgd(cores, ref_dg, cfg.lr)
+        tt.tt_core_sgd_update(table, plan, dg, cfg.lr)
+        torch.cuda.synchronize()
+        g.assert_grads_close(shape, table.cores, ref_new, what="cfg5 updated G")
+
+
+def test_config5_definition_mode_sample_of_bags(g, ora):
+    """Outputs of sampled bags recomputed one by one with the definition-mode oracle."""
+    import paper_2507_14668_amd as tt
+    cfg, tabs = cfg5_tables()
+    tab = tabs[-1]
+    shape, cores = cfg.tables[tab], wl.make_cores(cfg, tab)
+    idx, off = wl.make_batch(cfg, tab)
+    table = g.gpu_table(shape, cores)
+    d_idx, d_off = g.to_dev(idx, torch.int64), g.to_dev(off, torch.int64)
+    plan = tt.tt_index_reorder(table, d_idx, d_off)
+    out = tt.tt_emb_bag_forward(table, plan, d_idx, d_off).cpu().numpy()
+    pick = np.random.default_rng(0).choice(cfg.batch, size=512, replace=False)
+    sub_idx = np.concatenate([idx[off[b]:off[b + 1]] for b in pick])
+    sub_off = np.concatenate([[0], np.cumsum([off[b + 1] - off[b] for b in pick])]).astype(np.int64)
+    ref = ora.forward(shape, cores, sub_idx, sub_off)
+    g.assert_close_rows(out[pick], ref, g.FWD_RTOL, shape.dim, "cfg5 sampled bags")
+
+
+def test_two_stream_pipeline_equals_sequential(g):
+    """Reorder of batch b+1 on a second stream while batch b runs forward/backward/update on the
+    first: results must equal the sequential order bit for bit."""
+    import paper_2507_14668_amd as tt
+    cfg, tabs = cfg5_tables()
+    tabs = tabs[:2]
+    nbatch, nb = 4, 8192
+    data = {}
+    for tab in tabs:
+        shape, cores = cfg.tables[tab], wl.make_cores(cfg, tab)
+        data[tab] = dict(shape=shape, cores=cores,
+                         batches=[wl.make_batch(cfg, tab, batch=b, num_bags=nb) for b in range(nbatch)],
+                         grads=[wl.make_grad(cfg, tab, batch=b, num_bags=nb) for b in range(nbatch)])
+
+    def run(pipelined):
+        s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+        res = {}
+        for tab in tabs:
+            d = data[tab]
+            table = g.gpu_table(d["shape"], d["cores"])
+            dev = [(g.to_dev(i, torch.int64), g.to_dev(o, torch.int64)) for i, o in d["batches"]]
+            grads = [g.to_dev(x, torch.float32) for x in d["grads"]]
+            ws = [tt.alloc_workspace(table, dev[0][0].numel(), nb) for _ in range(2)]
+            dcores = table.core_grads_like()
+            torch.cuda.synchronize()
+            ready = [torch.cuda.Event(), torch.cuda.Event()]
+            free = [torch.cuda.Event(), torch.cuda.Event()]
+            outs = []
+            rs = s2 if pipelined else s1
+            plans = [None, None]
+            plans[0] = tt.tt_index_reorder(table, dev[0][0], dev[0][1], workspace=ws[0], stream=rs)
+            ready[0].record(rs)
+            for b in range(nbatch):
+                cur, nxt = b % 2, (b + 1) % 2
+                if b + 1 < nbatch:
+                    if b >= 1:
+                        rs.wait_event(free[nxt])
+                    plans[nxt] = tt.tt_index_reorder(table, dev[b + 1][0], dev[b + 1][1], workspace=ws[nxt], stream=rs)
+                    ready[nxt].record(rs)
+                s1.wait_event(ready[cur])
+                out = tt.tt_emb_bag_forward(table, plans[cur], dev[b][0], dev[b][1], stream=s1)
+                tt.tt_emb_bag_backward(table, plans[cur], dev[b][0], dev[b][1], grads[b], dcores=dcores, stream=s1)
+                tt.tt_core_sgd_update(table, plans[cur], dcores, cfg.lr, stream=s1)
+                free[cur].record(s1)
+                outs.append(out)
+            torch.cuda.synchronize()
+            res[tab] = ([o.clone() for o in outs], [c.clone() for c in table.cores])
+        return res
+
+    seq, pipe = run(False), run(True)
+    for tab in tabs:
+        for a, b in zip(seq[tab][0], pipe[tab][0]):
+            assert torch.equal(a, b)
+        for a, b in zip(seq[tab][1], pipe[tab][1]):
+            assert torch.equal(a, b)
