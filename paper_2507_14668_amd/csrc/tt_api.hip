@@ -1,7 +1,13 @@
 // C ABI of the TT embedding-bag library: argument validation, workspace layout, dispatch.
+#include <stdlib.h>
 #include <string.h>
 
 #include "tt_internal.h"
+
+bool tt_mfma_enabled() {
+  static const bool enabled = getenv("TT_EMB_NO_MFMA") == nullptr;
+  return enabled;
+}
 
 namespace {
 
@@ -72,6 +78,7 @@ size_t layout(const TTShape &sh, int64_t nnz, int64_t num_bags, char *base, tt_p
   q.prefs_by_i2 = ints(max_pref);
   q.i2_seg = ints(sh.n2 + 1);
   q.i1_seg = ints(sh.n1 + 1);
+  q.i2_chunk_off = ints(sh.n2 + 1);
   q.counts = ints(16);
   q.rowbuf = floats((size_t)max_rows * sh.D);
   q.gagg = floats((size_t)max_rows * sh.D);

@@ -204,7 +204,10 @@ size_t fwd_lds_bytes(const TTShape &sh, int rows_per_iter) {
 
 tt_status ttk_forward_plan(const TTShape &sh, const tt_table *t, const tt_plan *plan,
                            const int64_t *offsets, int64_t num_bags, float *out, hipStream_t s) {
-  if (plan->max_prefixes > 0) {
+  if (plan->max_prefixes > 0 && tt_mfma_enabled() && ttk_forward_mfma_supported(sh)) {
+    tt_status st = ttk_forward_mfma(sh, t, plan, s);
+    if (st != TT_OK) return st;
+  } else if (plan->max_prefixes > 0) {
     int rows_per_iter = TT_BLOCK / sh.D;
     if (rows_per_iter < 1) rows_per_iter = 1;
     if (rows_per_iter > 8) rows_per_iter = 8;

@@ -30,6 +30,9 @@ struct TTShape {
 #define TT_SORT_TILE (TT_BLOCK * TT_SORT_ITEMS)  // keys per workgroup per pass
 #define TT_SORT_MAX_BITS 10                      // digit width limit (1024 bins)
 
+// ---- matrix-core kernels -------------------------------------------------------------------
+#define TT_MP 8  // distinct prefixes per chunk: two 16-row MFMA tiles of (prefix, j1) rows
+
 // ---- segmented-reduction geometry -----------------------------------------------------------
 #define TT_SEG_CHUNK 64  // positions per chunk of the two-stage segmented sum
 
@@ -41,6 +44,12 @@ tt_status ttk_reorder(const TTShape &sh, const int64_t *indices, const int64_t *
                       hipStream_t s);
 tt_status ttk_forward_plan(const TTShape &sh, const tt_table *t, const tt_plan *plan,
                            const int64_t *offsets, int64_t num_bags, float *out, hipStream_t s);
+bool ttk_forward_mfma_supported(const TTShape &sh);
+tt_status ttk_forward_mfma(const TTShape &sh, const tt_table *t, const tt_plan *plan,
+                           hipStream_t s);
+// true unless the environment variable TT_EMB_NO_MFMA is set (keeps the plain-ALU kernels
+// selectable for comparison runs)
+bool tt_mfma_enabled();
 tt_status ttk_forward_naive(const TTShape &sh, const tt_table *t, const int64_t *indices,
                             const int64_t *offsets, int64_t nnz, int64_t num_bags, float *out,
                             hipStream_t s);

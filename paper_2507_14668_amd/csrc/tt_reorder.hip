@@ -317,6 +317,26 @@ __global__ void k_seg_bounds(const int32_t *__restrict__ counts,
   if (t <= n1) i1_seg[t] = lower_bound_div(uniq_pref, up, n2, t);
 }
 
+// Running count of TT_MP-prefix chunks per i2 (single workgroup; n2 may exceed the block size).
+__global__ void __launch_bounds__(TT_BLOCK)
+k_chunk_offsets(const int32_t *__restrict__ i2_seg, int n2, int32_t *__restrict__ chunk_off,
+                int32_t *__restrict__ counts) {
+  __shared__ int tmp[TT_BLOCK / TT_WAVE + 1];
+  int carry = 0;
+  for (int base = 0; base < n2; base += TT_BLOCK) {
+    const int t = base + threadIdx.x;
+    int v = 0, total;
+    if (t < n2) v = (i2_seg[t + 1] - i2_seg[t] + TT_MP - 1) / TT_MP;
+    const int ex = tt_block_excl_scan(v, tmp, &total);
+    if (t < n2) chunk_off[t] = carry + ex;
+    carry += total;
+  }
+  if (threadIdx.x == 0) {
+    chunk_off[n2] = carry;
+    counts[5] = carry;
+  }
+}
+
 int bit_length(long long v) {
   int b = 0;
   while (v > 0) { ++b; v >>= 1; }
@@ -448,5 +468,7 @@ tt_status ttk_reorder(const TTShape &sh, const int64_t *indices, const int64_t *
   hipLaunchKernelGGL(k_seg_bounds, dim3(tt_ceil_div(nmax + 1, TT_BLOCK)), dim3(TT_BLOCK), 0, s,
                      plan->counts, plan->i3_of_sorted, sh.n3, plan->i3_seg, tmp.k2, sh.n2,
                      plan->i2_seg, plan->uniq_pref, sh.n1, plan->i1_seg);
+  hipLaunchKernelGGL(k_chunk_offsets, dim3(1), dim3(TT_BLOCK), 0, s, plan->i2_seg, sh.n2,
+                     plan->i2_chunk_off, plan->counts);
   return tt_launch_status();
 }

@@ -84,6 +84,20 @@ def test_small_shapes(g, ora, seed, n, d, r, nb, ml):
     run_all(g, ora, shape, cores, idx, off, grad)
 
 
+@pytest.mark.parametrize("seed,n,r,nb,ml", [
+    (61, (5, 7, 9), (1, 32, 32, 1), 300, 6),      # few prefixes per i2: partly filled chunks
+    (62, (40, 3, 6), (1, 32, 32, 1), 2000, 8),    # > 16 prefixes per i2: several chunks
+    (63, (3, 2, 50), (1, 64, 64, 1), 1500, 5),    # many rows per prefix, two column strips
+    (64, (37, 5, 4), (1, 64, 64, 1), 900, 3),
+])
+def test_matrix_core_shapes(g, ora, seed, n, r, nb, ml):
+    """Shapes served by the MFMA kernels (d = 4x8x4, ranks 32 or 64) on small tables."""
+    print("case mfma shapes seed=%d n=%s r=%s" % (seed, n, r), flush=True)
+    shape, cores, idx, off, grad = wl.small_random_problem(seed, n=n, d=(4, 8, 4), r=r, num_bags=nb,
+                                                          max_len=ml, sigma=0.2)
+    run_all(g, ora, shape, cores, idx, off, grad)
+
+
 def test_padded_table_and_remap(g, ora):
     print("case padded+remap", flush=True)
     shape, cores, idx, off, grad = wl.small_random_problem(11, n=(4, 5, 6), d=(2, 2, 4), r=(1, 4, 4, 1),
