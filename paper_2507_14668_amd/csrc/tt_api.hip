@@ -83,8 +83,9 @@ size_t layout(const TTShape &sh, int64_t nnz, int64_t num_bags, char *base, tt_p
   q.rowbuf = floats((size_t)max_rows * sh.D);
   q.gagg = floats((size_t)max_rows * sh.D);
   q.hbuf = floats((size_t)max_pref * sh.P);
-  q.t3buf = floats((size_t)max_rows * sh.S3);
-  q.t1buf = floats((size_t)max_pref * sh.S1);
+  const size_t strips = (size_t)ttk_mfma_strips(sh);
+  q.t3buf = floats((size_t)max_rows * sh.S3 * strips);
+  q.t1buf = floats((size_t)max_pref * sh.S1 * strips);
   size_t part = (size_t)(tt_ceil_div(nnz, TT_SEG_CHUNK) + 1) * 2 * sh.D;
   size_t part3 = (size_t)(tt_ceil_div(max_rows, TT_SEG_CHUNK) + 1) * 2 * sh.S3;
   size_t part1 = (size_t)(tt_ceil_div(max_pref, TT_SEG_CHUNK) + 1) * 2 * sh.S1;

@@ -20,6 +20,8 @@ namespace {
 // Stage 1 walks fixed chunks of TT_SEG_CHUNK positions in order; a segment that lies inside one
 // chunk is finished there, otherwise the chunk leaves a partial: slot 0 = run that began before
 // the chunk, slot 1 = run that begins in the chunk and continues past its end.
+// A position may carry `nsub` consecutive vectors (src[(gidx[pos]*nsub + t)][W], t < nsub),
+// which are added in order first.
 // Output element e of segment s goes to out[((e/out_inner)*nseg + s)*out_inner + e%out_inner]
 // (out_inner = W gives a contiguous [nseg][W] array; out_inner = d3 gives core-2 layout).
 template <int VEC>
@@ -56,7 +58,7 @@ template <int VEC>
 __global__ void __launch_bounds__(TT_BLOCK)
 k_seg_stage1(int W, int lanes, const int32_t *__restrict__ count_ptr,
              const int32_t *__restrict__ seg_src, int seg_div, const int32_t *__restrict__ gidx,
-             const int32_t *__restrict__ seg_off, const float *__restrict__ src,
+             const int32_t *__restrict__ seg_off, const float *__restrict__ src, int nsub,
              float *__restrict__ out, int out_inner, int nseg, float *__restrict__ partial) {
   const int M = *count_ptr;
   const int nchunks = (M + TT_SEG_CHUNK - 1) / TT_SEG_CHUNK;
@@ -80,7 +82,12 @@ k_seg_stage1(int W, int lanes, const int32_t *__restrict__ count_ptr,
         for (int k = 0; k < 4; ++k) {
           sg[k] = seg_src[pos + k] / seg_div;
           const int row = gidx ? gidx[pos + k] : pos + k;
-          x[k].load(src + (size_t)row * W + e);
+          x[k].load(src + (size_t)row * nsub * W + e);
+          for (int t = 1; t < nsub; ++t) {
+            Vec<VEC> y;
+            y.load(src + ((size_t)row * nsub + t) * W + e);
+            x[k].add(y);
+          }
         }
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
@@ -96,7 +103,12 @@ k_seg_stage1(int W, int lanes, const int32_t *__restrict__ count_ptr,
         const int sgk = seg_src[pos] / seg_div;
         const int row = gidx ? gidx[pos] : pos;
         Vec<VEC> x;
-        x.load(src + (size_t)row * W + e);
+        x.load(src + (size_t)row * nsub * W + e);
+        for (int t = 1; t < nsub; ++t) {
+          Vec<VEC> y;
+          y.load(src + ((size_t)row * nsub + t) * W + e);
+          x.add(y);
+        }
         if (sgk != cur) {
           if (cur >= 0) flush();
           cur = sgk;
@@ -179,6 +191,7 @@ struct SegArgs {
   const int32_t *gidx;
   const int32_t *seg_off;
   const float *src;
+  int nsub;  // vectors per position
   float *out;
   int out_inner;
   int nseg;   // number of segments for the output layout / dense zero fill
@@ -199,11 +212,11 @@ tt_status seg_sum(const SegArgs &a, hipStream_t s) {
     if (blocks > 8192) blocks = 8192;
     if (vec4)
       hipLaunchKernelGGL(k_seg_stage1<4>, dim3(blocks), dim3(TT_BLOCK), 0, s, a.W, lanes,
-                         a.count_ptr, a.seg_src, a.seg_div, a.gidx, a.seg_off, a.src, a.out,
+                         a.count_ptr, a.seg_src, a.seg_div, a.gidx, a.seg_off, a.src, a.nsub, a.out,
                          a.out_inner, a.nseg, a.partial);
     else
       hipLaunchKernelGGL(k_seg_stage1<1>, dim3(blocks), dim3(TT_BLOCK), 0, s, a.W, lanes,
-                         a.count_ptr, a.seg_src, a.seg_div, a.gidx, a.seg_off, a.src, a.out,
+                         a.count_ptr, a.seg_src, a.seg_div, a.gidx, a.seg_off, a.src, a.nsub, a.out,
                          a.out_inner, a.nseg, a.partial);
   }
   int blocks2 = nchunks;
@@ -457,10 +470,15 @@ tt_status ttk_backward_plan(const TTShape &sh, const tt_table *t, const tt_plan 
   tt_status st;
   // 1. merge output gradients per distinct row
   SegArgs a1 = {sh.D, plan->counts + 2, plan->nnz, plan->slot_of_sorted, 1, plan->bag_of_sorted,
-                plan->row_seg, grad_out, plan->gagg, sh.D, (int)plan->max_rows, 0, plan->partial};
+                plan->row_seg, grad_out, 1, plan->gagg, sh.D, (int)plan->max_rows, 0,
+                plan->partial};
   if ((st = seg_sum(a1, s)) != TT_OK) return st;
   // 2. per-prefix contractions
-  if (plan->max_prefixes > 0) {
+  const bool mfma = tt_mfma_enabled() && ttk_forward_mfma_supported(sh);
+  const int strips = mfma ? ttk_mfma_strips(sh) : 1;
+  if (mfma) {
+    if ((st = ttk_backward_mfma(sh, t, plan, dcore[1], s)) != TT_OK) return st;
+  } else if (plan->max_prefixes > 0) {
     long long blocks = plan->max_prefixes < 4096 ? plan->max_prefixes : 4096;
     hipLaunchKernelGGL(k_bwd_prefix, dim3((unsigned)blocks), dim3(TT_BLOCK), bwd_lds_bytes(sh), s,
                        sh, t->core[0], t->core[1], t->core[2], plan->counts, plan->uniq_pref,
@@ -469,14 +487,15 @@ tt_status ttk_backward_plan(const TTShape &sh, const tt_table *t, const tt_plan 
   }
   // 3a. core 2: sum the per-row contributions of all rows sharing i3
   SegArgs a3 = {sh.S3, plan->counts + 0, plan->max_rows, plan->i3_of_sorted, 1, plan->rows_by_i3,
-                plan->i3_seg, plan->t3buf, dcore[2], sh.d3, sh.n3, 1, plan->partial};
+                plan->i3_seg, plan->t3buf, strips, dcore[2], sh.d3, sh.n3, 1, plan->partial};
   if ((st = seg_sum(a3, s)) != TT_OK) return st;
   // 3b. core 0: sum the per-prefix contributions of all prefixes sharing i1 (contiguous)
   SegArgs a0 = {sh.S1, plan->counts + 1, plan->max_prefixes, plan->uniq_pref, sh.n2, nullptr,
-                plan->i1_seg, plan->t1buf, dcore[0], sh.S1, sh.n1, 1, plan->partial};
+                plan->i1_seg, plan->t1buf, strips, dcore[0], sh.S1, sh.n1, 1, plan->partial};
   if ((st = seg_sum(a0, s)) != TT_OK) return st;
-  // 3c. core 1: per-i2 accumulation over prefixes
-  hipLaunchKernelGGL(k_bwd_dg2,
+  // 3c. core 1: per-i2 accumulation over prefixes (done inside the matrix-core kernel)
+  if (!mfma)
+    hipLaunchKernelGGL(k_bwd_dg2,
                      dim3(sh.n2, tt_ceil_div(sh.S2, TT_BLOCK), tt_ceil_div(sh.R1, TT_DG2_RT)),
                      dim3(TT_BLOCK), 0, s, sh, t->core[0], plan->uniq_pref, plan->prefs_by_i2,
                      plan->i2_seg, plan->hbuf, dcore[1]);

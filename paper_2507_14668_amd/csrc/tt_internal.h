@@ -47,6 +47,11 @@ tt_status ttk_forward_plan(const TTShape &sh, const tt_table *t, const tt_plan *
 bool ttk_forward_mfma_supported(const TTShape &sh);
 tt_status ttk_forward_mfma(const TTShape &sh, const tt_table *t, const tt_plan *plan,
                            hipStream_t s);
+// number of 256-column strips a core-1 slice is cut into by the matrix-core kernels (1 when the
+// shape is served by the plain-ALU kernels); t3buf / t1buf hold one contribution per strip
+int ttk_mfma_strips(const TTShape &sh);
+tt_status ttk_backward_mfma(const TTShape &sh, const tt_table *t, const tt_plan *plan, float *dg2,
+                            hipStream_t s);
 // true unless the environment variable TT_EMB_NO_MFMA is set (keeps the plain-ALU kernels
 // selectable for comparison runs)
 bool tt_mfma_enabled();
