@@ -33,7 +33,9 @@ def parse_args():
     ap.add_argument("--batches", type=int, default=8, help="distinct batches cycled through")
     ap.add_argument("--tables", type=int, default=0, help="use only the first T tables (0 = all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--prof-kernel", default="auto", help="kernel bracketed with HIP events for the roofline")
+    ap.add_argument("--prof-kernel", default="auto",
+                    choices=["auto", "fwd_contract", "bwd_contract", "bag_sum", "grad_merge"],
+                    help="kernel bracketed with HIP events for the roofline (auto = the dominant one)")
     return ap.parse_args()
 
 
@@ -54,7 +56,7 @@ def main():
     tt.load_library()
     cfg_id = int(args.workload[3:])
     cfg = wl.get_config(cfg_id)
-    do_fwd = cfg_id != 4 or True
+    do_fwd = True
     do_bwd = cfg_id != 3
     ntab = len(cfg.tables) if args.tables <= 0 else min(args.tables, len(cfg.tables))
     nbatch = max(2, args.batches + (args.batches % 2))  # even, so batch b always uses plan buffer b%2
@@ -70,7 +72,9 @@ def main():
             idx, off = wl.make_batch(cfg, t, batch=b, permute_rows=True if args.permute else None)
             grad = wl.make_grad(cfg, t, batch=b)
             batches.append(dict(idx=torch.from_numpy(idx).cuda(), off=torch.from_numpy(off).cuda(),
-                                grad=torch.from_numpy(grad).cuda(), nnz=len(idx)))
+                                grad=torch.from_numpy(grad).cuda(), nnz=len(idx),
+                                # workload statistics used only to count algorithmic work
+                                u_r=int(np.unique(idx).size), u_p=int(np.unique(idx // shape.n[2]).size)))
         max_nnz = max(x["nnz"] for x in batches)
         ws = [tt.alloc_workspace(table, max_nnz, cfg.batch) for _ in range(2)] if args.arm == "plan" else None
         tabs.append(dict(shape=shape, table=table, batches=batches, ws=ws, plans=[None, None],
@@ -78,6 +82,11 @@ def main():
                          dcores=table.core_grads_like()))
     torch.cuda.synchronize()
     t_gen = time.time() - t_gen
+
+    prof_name = args.prof_kernel
+    if prof_name == "auto":
+        prof_name = "bwd_contract" if do_bwd else "fwd_contract"
+    prof = tt.Prof(prof_name, (args.steps + 1) * ntab * 4) if args.arm == "plan" else None
 
     s1 = torch.cuda.Stream()
     s2 = s1 if args.no_overlap else torch.cuda.Stream()
@@ -91,6 +100,8 @@ def main():
             x = T["batches"][b % nbatch]
             # workspace sized for the largest batch; plan is rebuilt for this batch's nnz
             T["plans"][buf] = tt.tt_index_reorder(T["table"], x["idx"], x["off"], workspace=T["ws"][buf], stream=s2)
+            if timing[0]:
+                prof.attach(T["plans"][buf])
         ready[buf].record(s2)
 
     def compute(b):
@@ -106,6 +117,8 @@ def main():
                 tt.tt_emb_bag_backward(T["table"], plan, x["idx"], x["off"], x["grad"], dcores=T["dcores"], stream=s1)
                 tt.tt_core_sgd_update(T["table"], plan, T["dcores"], cfg.lr, stream=s1)
         free[buf].record(s1)
+
+    timing = [False]
 
     def step(b):
         """reorder(b+1) on s2 while batch b computes on s1; buffer (b+1)%2 was last used by b-1."""
@@ -125,6 +138,10 @@ def main():
         b += 1
     torch.cuda.synchronize()
     lookups = 0
+    if planned:  # bracket the selected kernel of every launch made inside the timed region
+        timing[0] = True
+        for T in tabs:
+            prof.attach(T["plans"][b % 2])
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step(b)
@@ -132,6 +149,22 @@ def main():
         b += 1
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    roofline = None
+    if planned:
+        kernel_ms, launches = prof.collect()
+        first = b - args.steps
+        work = 0.0
+        for k in range(args.steps):
+            for T in tabs:
+                work += kernel_work(prof_name, T["shape"], T["batches"][(first + k) % nbatch], cfg.batch)
+        bound, unit, peak, scale = KERNEL_BOUND[prof_name]
+        if launches > 0 and kernel_ms > 0:
+            achieved = work / (kernel_ms * 1e-3) / scale
+            roofline = {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
+                        "frac": achieved / peak, "traffic": read_traffic(args.workload, prof_name),
+                        "kernel": prof_name, "launches": int(launches),
+                        "avg_launch_us": 1e3 * kernel_ms / launches,
+                        "algorithmic_work_per_launch": work / launches}
 
     status_bad = 0
     counts = []
@@ -158,7 +191,7 @@ def main():
                    "lookups_per_step": lookups // max(1, args.steps), "tables": ntab,
                    "overlap_second_stream": (not args.no_overlap) and planned,
                    "input_generation_s": round(t_gen, 1)},
-        "roofline": None,
+        "roofline": roofline,
         "cpu_baseline": None,
     }
     if counts:
@@ -168,6 +201,49 @@ def main():
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, wl, np)
     print(json.dumps(result))
+
+
+# kernel -> (bound, unit, published MI355X peak in that unit, divisor to that unit)
+KERNEL_BOUND = {
+    "fwd_contract": ("mfma", "TFLOP/s", PEAK_FP32_TFLOPS, 1e12),
+    "bwd_contract": ("mfma", "TFLOP/s", PEAK_FP32_TFLOPS, 1e12),
+    "bag_sum": ("hbm", "GB/s", PEAK_HBM_GBS, 1e9),
+    "grad_merge": ("hbm", "GB/s", PEAK_HBM_GBS, 1e9),
+}
+
+
+def kernel_work(kernel, shape, batch, num_bags):
+    """Algorithmic flops (contractions) or bytes (streaming kernels) of ONE launch: the work the
+    method needs after reuse and dedup, not what the implementation happens to move."""
+    d1, d2, d3 = shape.d
+    r1, r2 = shape.r[1], shape.r[2]
+    dim = d1 * d2 * d3
+    f12 = 2.0 * d1 * r1 * d2 * r2      # one prefix product G1[i1] x G2[i2]
+    f3 = 2.0 * d1 * d2 * r2 * d3       # one row P12 x G3[i3]
+    nnz, u_r, u_p = batch["nnz"], batch["u_r"], batch["u_p"]
+    if kernel == "fwd_contract":
+        return u_p * f12 + u_r * f3
+    if kernel == "bwd_contract":
+        # per prefix: P12 recomputed (cheaper than 2 x 4 x P12 bytes of traffic), H x G2^T, G1^T x H;
+        # per distinct row: P12^T x g and g x G3^T
+        return u_p * 3 * f12 + u_r * 2 * f3
+    if kernel == "bag_sum":
+        return 4.0 * nnz * dim + 4.0 * num_bags * dim + 4.0 * nnz + 8.0 * (num_bags + 1)
+    if kernel == "grad_merge":
+        return 4.0 * nnz * dim + 4.0 * u_r * dim + 8.0 * nnz
+    raise ValueError(kernel)
+
+
+def read_traffic(workload, kernel):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE), if a summary
+    for this workload and kernel has been committed under profiles/."""
+    path = os.path.join(ROOT, "profiles", "traffic_%s_%s.txt" % (workload, kernel))
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("traffic_bytes_per_launch:"):
+            return float(line.split(":", 1)[1])
+    return None
 
 
 def cpu_baseline(cfg, wl, np):
@@ -184,10 +260,14 @@ def cpu_baseline(cfg, wl, np):
         ora.backward(shape, cores, idx, off, grad)
         return len(idx), time.perf_counter() - t0
 
-    nb0 = min(cfg.batch, 64)
-    n0, t0 = run(nb0)
-    nb = int(min(cfg.batch, max(nb0, nb0 * 12.0 / max(t0, 1e-3))))
+    nb = min(cfg.batch, 256)
+    run(min(cfg.batch, 64))  # thread start-up and page faults stay out of the measurement
     n, t = run(nb)
+    for _ in range(4):  # grow the sample until it holds 10-30 s of CPU work (or the whole batch)
+        if t >= 10.0 or nb >= cfg.batch:
+            break
+        nb = int(min(cfg.batch, nb * min(16.0, max(2.0, 15.0 / max(t, 1e-3)))))
+        n, t = run(nb)
     return {"value": n / t, "unit": "lookups/s", "cores": ora.max_threads(), "kind": "oracle",
             "sample": "definition-mode forward+backward of the first %d bags (%d lookups) of table %d "
                       "(%d rows), %.1f s" % (nb, n, tab, shape.num_rows, t)}

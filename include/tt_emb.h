@@ -116,6 +116,8 @@ typedef struct {
   float *t1buf;           /* [max_prefixes][d0*r1] per-prefix contributions to core 0     */
   float *partial;         /* segmented-reduction partials                                 */
   void *sort_tmp;         /* radix-sort ping-pong buffers, histograms, scan temporaries   */
+  void *prof;             /* HOST, optional tt_prof* attached by the caller (NULL after
+                             tt_index_reorder): brackets one kernel with HIP events       */
   void *workspace;        /* the caller's workspace this plan points into                 */
   size_t workspace_bytes;
 } tt_plan;
@@ -193,6 +195,32 @@ tt_status tt_core_sgd_update(const tt_table *table, const tt_plan *plan,
 tt_status tt_plan_status(const tt_plan *plan, void *stream, int64_t counts_out[4]);
 
 const char *tt_strerror(tt_status status);
+
+/*
+ * Kernel timing helper for benchmarks (not needed by the operator itself, and the one place
+ * where the library owns anything: a host object holding HIP events).  A tt_prof selects one
+ * kernel of the planned path; while it is attached to a plan (plan->prof), every launch of that
+ * kernel made with the plan is bracketed by two HIP events recorded on the launch stream.
+ * tt_prof_collect waits for the recorded events, returns the summed duration and the number of
+ * launches since the last collect, and rearms the object.  At most `capacity` launches are
+ * recorded between two collects; later ones run untimed.
+ */
+typedef enum {
+  TT_KERNEL_FWD_CONTRACT = 0, /* prefix products + distinct rows (forward)                   */
+  TT_KERNEL_BAG_SUM = 1,      /* per-bag sum of distinct rows                                */
+  TT_KERNEL_GRAD_MERGE = 2,   /* stage 1 of merging grad_out per distinct row                */
+  TT_KERNEL_BWD_CONTRACT = 3, /* per-prefix backward contractions                            */
+  TT_KERNEL_SORT_SCATTER = 4, /* one radix-sort scatter pass of the main lookup sort         */
+  TT_KERNEL_SGD = 5,          /* core update                                                 */
+  TT_KERNEL_COUNT = 6
+} tt_kernel;
+
+typedef struct tt_prof tt_prof;
+tt_prof *tt_prof_create(int kernel, int capacity); /* NULL on failure                        */
+void tt_prof_destroy(tt_prof *prof);
+/* HOST out-params; returns TT_ERR_HIP if an event query fails */
+tt_status tt_prof_collect(tt_prof *prof, double *total_ms, int64_t *launches);
+const char *tt_kernel_name(int kernel);
 
 #ifdef __cplusplus
 }

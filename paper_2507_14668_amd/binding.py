@@ -23,7 +23,9 @@ TT_ERR_INDEX_RANGE = -4
 TT_ERR_HIP = -5
 
 EXPORTS = ("tt_workspace_bytes", "tt_index_reorder", "tt_emb_bag_forward", "tt_emb_bag_backward",
-           "tt_core_sgd_update", "tt_plan_status", "tt_strerror")
+           "tt_core_sgd_update", "tt_plan_status", "tt_strerror", "tt_prof_create", "tt_prof_destroy",
+           "tt_prof_collect", "tt_kernel_name")
+KERNELS = {"fwd_contract": 0, "bag_sum": 1, "grad_merge": 2, "bwd_contract": 3, "sort_scatter": 4, "sgd": 5}
 
 
 class TTError(RuntimeError):
@@ -50,7 +52,7 @@ class CPlan(ctypes.Structure):
                  ("r", ctypes.c_int32 * 4)]
                 + [(name, _I32P) for name in _PLAN_INT_ARRAYS]
                 + [(name, ctypes.c_void_p) for name in _PLAN_FLOAT_ARRAYS]
-                + [("sort_tmp", ctypes.c_void_p), ("workspace", ctypes.c_void_p),
+                + [("sort_tmp", ctypes.c_void_p), ("prof", ctypes.c_void_p), ("workspace", ctypes.c_void_p),
                    ("workspace_bytes", ctypes.c_size_t)])
 
 
@@ -78,6 +80,14 @@ def load_library():
         lib.tt_core_sgd_update.argtypes = [vp, vp, vp, f32, vp]
         lib.tt_plan_status.restype = ctypes.c_int
         lib.tt_plan_status.argtypes = [vp, vp, vp]
+        lib.tt_prof_create.restype = vp
+        lib.tt_prof_create.argtypes = [ctypes.c_int, ctypes.c_int]
+        lib.tt_prof_destroy.restype = None
+        lib.tt_prof_destroy.argtypes = [vp]
+        lib.tt_prof_collect.restype = ctypes.c_int
+        lib.tt_prof_collect.argtypes = [vp, vp, vp]
+        lib.tt_kernel_name.restype = ctypes.c_char_p
+        lib.tt_kernel_name.argtypes = [ctypes.c_int]
         lib.tt_strerror.restype = ctypes.c_char_p
         lib.tt_strerror.argtypes = [ctypes.c_int]
         _lib = lib
@@ -175,6 +185,30 @@ class Plan:
         out = {k: self._array(k, v, torch.int32).cpu().numpy() for k, v in lens.items()}
         out.update(U_r=ur, U_p=up, num_valid=nvalid)
         return out
+
+
+class Prof:
+    """HIP-event timing of one kernel of the planned path (benchmark helper)."""
+
+    def __init__(self, kernel: str, capacity: int):
+        self.kernel = kernel
+        self.handle = load_library().tt_prof_create(KERNELS[kernel], int(capacity))
+        if not self.handle:
+            raise TTError(TT_ERR_HIP, "tt_prof_create")
+
+    def attach(self, plan: "Plan"):
+        plan.c.prof = self.handle
+
+    def collect(self):
+        """(total milliseconds, launches) since the last collect; waits for the events."""
+        ms, n = ctypes.c_double(0.0), ctypes.c_int64(0)
+        _check(load_library().tt_prof_collect(self.handle, ctypes.byref(ms), ctypes.byref(n)), "tt_prof_collect")
+        return ms.value, n.value
+
+    def close(self):
+        if self.handle:
+            load_library().tt_prof_destroy(self.handle)
+            self.handle = None
 
 
 def tt_workspace_bytes(table: Table, nnz: int, num_bags: int) -> int:

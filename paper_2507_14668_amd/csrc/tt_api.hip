@@ -196,6 +196,58 @@ tt_status tt_plan_status(const tt_plan *plan, void *stream, int64_t counts_out[4
   return host[4] ? TT_ERR_INDEX_RANGE : TT_OK;
 }
 
+tt_prof *tt_prof_create(int kernel, int capacity) {
+  if (kernel < 0 || kernel >= TT_KERNEL_COUNT || capacity < 1) return nullptr;
+  tt_prof *p = (tt_prof *)calloc(1, sizeof(tt_prof));
+  if (!p) return nullptr;
+  p->kernel = kernel;
+  p->capacity = capacity;
+  p->ev = (hipEvent_t *)calloc((size_t)2 * capacity, sizeof(hipEvent_t));
+  if (!p->ev) { free(p); return nullptr; }
+  for (int i = 0; i < 2 * capacity; ++i)
+    if (hipEventCreate(&p->ev[i]) != hipSuccess) {
+      for (int k = 0; k < i; ++k) (void)hipEventDestroy(p->ev[k]);
+      free(p->ev); free(p);
+      return nullptr;
+    }
+  return p;
+}
+
+void tt_prof_destroy(tt_prof *p) {
+  if (!p) return;
+  for (int i = 0; i < 2 * p->capacity; ++i) (void)hipEventDestroy(p->ev[i]);
+  free(p->ev);
+  free(p);
+}
+
+tt_status tt_prof_collect(tt_prof *p, double *total_ms, int64_t *launches) {
+  if (!p || !total_ms || !launches) return TT_ERR_INVALID_ARG;
+  double sum = 0.0;
+  for (int i = 0; i < p->used; ++i) {
+    float ms = 0.f;
+    if (hipEventSynchronize(p->ev[2 * i + 1]) != hipSuccess ||
+        hipEventElapsedTime(&ms, p->ev[2 * i], p->ev[2 * i + 1]) != hipSuccess)
+      return TT_ERR_HIP;
+    sum += ms;
+  }
+  *total_ms = sum;
+  *launches = p->used;
+  p->used = 0;
+  return TT_OK;
+}
+
+const char *tt_kernel_name(int kernel) {
+  switch (kernel) {
+    case TT_KERNEL_FWD_CONTRACT: return "fwd_contract";
+    case TT_KERNEL_BAG_SUM: return "bag_sum";
+    case TT_KERNEL_GRAD_MERGE: return "grad_merge";
+    case TT_KERNEL_BWD_CONTRACT: return "bwd_contract";
+    case TT_KERNEL_SORT_SCATTER: return "sort_scatter";
+    case TT_KERNEL_SGD: return "sgd";
+  }
+  return "unknown";
+}
+
 const char *tt_strerror(tt_status status) {
   switch (status) {
     case TT_OK: return "ok";

@@ -197,6 +197,8 @@ struct SegArgs {
   int nseg;   // number of segments for the output layout / dense zero fill
   int dense;
   float *partial;
+  const tt_plan *plan;  // for the optional timing scope
+  int prof_kernel;      // kernel id of stage 1, or -1
 };
 
 tt_status seg_sum(const SegArgs &a, hipStream_t s) {
@@ -210,6 +212,7 @@ tt_status seg_sum(const SegArgs &a, hipStream_t s) {
   if (nchunks > 0) {
     int blocks = tt_ceil_div(nchunks, groups);
     if (blocks > 8192) blocks = 8192;
+    TTProfScope prof(a.plan, a.prof_kernel, s);
     if (vec4)
       hipLaunchKernelGGL(k_seg_stage1<4>, dim3(blocks), dim3(TT_BLOCK), 0, s, a.W, lanes,
                          a.count_ptr, a.seg_src, a.seg_div, a.gidx, a.seg_off, a.src, a.nsub, a.out,
@@ -471,7 +474,7 @@ tt_status ttk_backward_plan(const TTShape &sh, const tt_table *t, const tt_plan 
   // 1. merge output gradients per distinct row
   SegArgs a1 = {sh.D, plan->counts + 2, plan->nnz, plan->slot_of_sorted, 1, plan->bag_of_sorted,
                 plan->row_seg, grad_out, 1, plan->gagg, sh.D, (int)plan->max_rows, 0,
-                plan->partial};
+                plan->partial, plan, TT_KERNEL_GRAD_MERGE};
   if ((st = seg_sum(a1, s)) != TT_OK) return st;
   // 2. per-prefix contractions
   const bool mfma = tt_mfma_enabled() && ttk_forward_mfma_supported(sh);
@@ -480,6 +483,7 @@ tt_status ttk_backward_plan(const TTShape &sh, const tt_table *t, const tt_plan 
     if ((st = ttk_backward_mfma(sh, t, plan, dcore[1], s)) != TT_OK) return st;
   } else if (plan->max_prefixes > 0) {
     long long blocks = plan->max_prefixes < 4096 ? plan->max_prefixes : 4096;
+    TTProfScope prof(plan, TT_KERNEL_BWD_CONTRACT, s);
     hipLaunchKernelGGL(k_bwd_prefix, dim3((unsigned)blocks), dim3(TT_BLOCK), bwd_lds_bytes(sh), s,
                        sh, t->core[0], t->core[1], t->core[2], plan->counts, plan->uniq_pref,
                        plan->pref_seg, plan->uniq_row, plan->gagg, plan->t3buf, plan->hbuf,
@@ -487,11 +491,11 @@ tt_status ttk_backward_plan(const TTShape &sh, const tt_table *t, const tt_plan 
   }
   // 3a. core 2: sum the per-row contributions of all rows sharing i3
   SegArgs a3 = {sh.S3, plan->counts + 0, plan->max_rows, plan->i3_of_sorted, 1, plan->rows_by_i3,
-                plan->i3_seg, plan->t3buf, strips, dcore[2], sh.d3, sh.n3, 1, plan->partial};
+                plan->i3_seg, plan->t3buf, strips, dcore[2], sh.d3, sh.n3, 1, plan->partial, plan, -1};
   if ((st = seg_sum(a3, s)) != TT_OK) return st;
   // 3b. core 0: sum the per-prefix contributions of all prefixes sharing i1 (contiguous)
   SegArgs a0 = {sh.S1, plan->counts + 1, plan->max_prefixes, plan->uniq_pref, sh.n2, nullptr,
-                plan->i1_seg, plan->t1buf, strips, dcore[0], sh.S1, sh.n1, 1, plan->partial};
+                plan->i1_seg, plan->t1buf, strips, dcore[0], sh.S1, sh.n1, 1, plan->partial, plan, -1};
   if ((st = seg_sum(a0, s)) != TT_OK) return st;
   // 3c. core 1: per-i2 accumulation over prefixes (done inside the matrix-core kernel)
   if (!mfma)
@@ -523,6 +527,7 @@ tt_status ttk_backward_naive(const TTShape &sh, const tt_table *t, const int64_t
 tt_status ttk_sgd(const TTShape &sh, const tt_table *t, const tt_plan *plan,
                   const float *const dcore[3], float lr, hipStream_t s) {
   if (plan) {
+    TTProfScope prof(plan, TT_KERNEL_SGD, s);
     hipLaunchKernelGGL(k_sgd_touched, dim3(sh.n1 + sh.n2 + sh.n3), dim3(TT_BLOCK), 0, s, sh,
                        t->core[0], t->core[1], t->core[2], dcore[0], dcore[1], dcore[2],
                        plan->i1_seg, plan->i2_seg, plan->i3_seg, lr);

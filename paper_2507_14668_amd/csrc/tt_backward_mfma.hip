@@ -291,6 +291,7 @@ tt_status launch(const TTShape &sh, const tt_table *t, const tt_plan *plan, floa
       return TT_ERR_HIP;
     configured = true;
   }
+  TTProfScope prof(plan, TT_KERNEL_BWD_CONTRACT, s);
   hipLaunchKernelGGL((k_bwd_mfma<R1, R2, D2>), dim3(sh.n2 * G::NSTRIP), dim3(TT_BLOCK), lds, s, sh,
                      t->core[0], t->core[1], t->core[2], plan->uniq_pref, plan->pref_seg,
                      plan->uniq_row, plan->prefs_by_i2, plan->i2_seg, plan->gagg, plan->t3buf,

@@ -212,6 +212,7 @@ tt_status ttk_forward_plan(const TTShape &sh, const tt_table *t, const tt_plan *
     if (rows_per_iter < 1) rows_per_iter = 1;
     if (rows_per_iter > 8) rows_per_iter = 8;
     long long blocks = plan->max_prefixes < 4096 ? plan->max_prefixes : 4096;
+    TTProfScope prof(plan, TT_KERNEL_FWD_CONTRACT, s);
     hipLaunchKernelGGL(k_fwd_prefix_rows, dim3((unsigned)blocks), dim3(TT_BLOCK),
                        fwd_lds_bytes(sh, rows_per_iter), s, sh, t->core[0], t->core[1],
                        t->core[2], plan->counts, plan->uniq_pref, plan->pref_seg, plan->uniq_row,
@@ -224,6 +225,7 @@ tt_status ttk_forward_plan(const TTShape &sh, const tt_table *t, const tt_plan *
     const int groups = TT_BLOCK / lanes;
     long long blocks = (num_bags + groups - 1) / groups;
     if (blocks > 16384) blocks = 16384;
+    TTProfScope prof(plan, TT_KERNEL_BAG_SUM, s);
     if (vec4)
       hipLaunchKernelGGL(k_bag_sum<4>, dim3((unsigned)blocks), dim3(TT_BLOCK), 0, s, sh.D, lanes,
                          offsets, (int)num_bags, (int)plan->nnz, plan->lookup2row, plan->rowbuf, out);

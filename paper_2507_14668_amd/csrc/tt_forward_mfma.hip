@@ -192,6 +192,7 @@ tt_status launch(const TTShape &sh, const tt_table *t, const tt_plan *plan, hipS
   // upper bound of the chunk count: every i2 adds at most one partly filled chunk
   long long blocks = (plan->max_prefixes / TT_MP + sh.n2) * G::NSTRIP;
   if (blocks > 8192) blocks = 8192;  // grid-stride loop covers the rest
+  TTProfScope prof(plan, TT_KERNEL_FWD_CONTRACT, s);
   hipLaunchKernelGGL((k_fwd_mfma<R1, R2, D2>), dim3((unsigned)blocks), dim3(TT_BLOCK), lds, s, sh,
                      t->core[0], t->core[1], t->core[2], plan->counts, plan->uniq_pref,
                      plan->pref_seg, plan->uniq_row, plan->prefs_by_i2, plan->i2_seg,

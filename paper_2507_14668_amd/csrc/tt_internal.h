@@ -79,6 +79,32 @@ struct TTSortTmp {
 TTSortTmp tt_sort_tmp_view(const tt_plan *plan);
 size_t tt_sort_tmp_bytes(int64_t nnz, int64_t max_rows, int64_t max_prefixes);
 
+// Brackets the launches made inside its scope with HIP events when the plan carries a tt_prof
+// that selects `kernel`.
+struct tt_prof {
+  int kernel;
+  int capacity;
+  int used;
+  hipEvent_t *ev;  // [2 * capacity]: start, stop
+};
+struct TTProfScope {
+  tt_prof *p;
+  hipStream_t s;
+  TTProfScope(const tt_plan *plan, int kernel, hipStream_t stream) : p(nullptr), s(stream) {
+    tt_prof *q = plan ? (tt_prof *)plan->prof : nullptr;
+    if (q && q->kernel == kernel && q->used < q->capacity) {
+      p = q;
+      (void)hipEventRecord(p->ev[2 * p->used], s);
+    }
+  }
+  ~TTProfScope() {
+    if (p) {
+      (void)hipEventRecord(p->ev[2 * p->used + 1], s);
+      ++p->used;
+    }
+  }
+};
+
 static inline tt_status tt_launch_status() {
   return hipGetLastError() == hipSuccess ? TT_OK : TT_ERR_HIP;
 }

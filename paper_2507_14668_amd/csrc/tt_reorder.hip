@@ -355,7 +355,7 @@ RadixPlan radix_plan(int key_bits) {
 // (a) when the number of passes is even and in (b) when it is odd; the result lands in (a).
 tt_status radix_sort(int32_t *keys_a, int32_t *vals_a, int32_t *keys_b, int32_t *vals_b,
                      const int32_t *count_ptr, int64_t max_count, int key_bits,
-                     const TTSortTmp &tmp, hipStream_t s) {
+                     const TTSortTmp &tmp, hipStream_t s, const tt_plan *prof_plan = nullptr) {
   const RadixPlan rp = radix_plan(key_bits);
   const int ntiles = tt_ceil_div(max_count, TT_SORT_TILE);
   if (ntiles == 0) return TT_OK;
@@ -369,8 +369,11 @@ tt_status radix_sort(int32_t *keys_a, int32_t *vals_a, int32_t *keys_b, int32_t 
                        bits, ntiles, tmp.hist);
     hipLaunchKernelGGL(k_radix_binscan, dim3(1 << bits), dim3(TT_BLOCK), 0, s, tmp.hist, ntiles,
                        tmp.bin_total);
-    hipLaunchKernelGGL(k_radix_scatter, dim3(ntiles), dim3(TT_BLOCK), 0, s, ki, vi, ko, vo,
-                       count_ptr, shift, bits, ntiles, tmp.hist, tmp.bin_total);
+    {
+      TTProfScope prof(prof_plan, TT_KERNEL_SORT_SCATTER, s);
+      hipLaunchKernelGGL(k_radix_scatter, dim3(ntiles), dim3(TT_BLOCK), 0, s, ki, vi, ko, vo,
+                         count_ptr, shift, bits, ntiles, tmp.hist, tmp.bin_total);
+    }
     shift += bits;
     in_a = !in_a;
   }
@@ -429,7 +432,7 @@ tt_status ttk_reorder(const TTShape &sh, const int64_t *indices, const int64_t *
                      indices, offsets, remap, nnz, num_bags, sh.num_rows, sh.sentinel, k0, v0,
                      tmp.bag_tmp, plan->counts);
   tt_status st = radix_sort(plan->sorted_row, plan->perm, tmp.keys_alt, tmp.vals_alt,
-                            plan->counts + 3, nnz, key_bits, tmp, s);
+                            plan->counts + 3, nnz, key_bits, tmp, s, plan);
   if (st != TT_OK) return st;
 
   // distinct rows and prefixes
