@@ -32,6 +32,8 @@ def parse_args():
     ap.add_argument("--permute", action="store_true", help="seeded random row permutation of the Zipf ranks")
     ap.add_argument("--batches", type=int, default=8, help="distinct batches cycled through")
     ap.add_argument("--tables", type=int, default=0, help="use only the first T tables (0 = all)")
+    ap.add_argument("--streams", type=int, default=1,
+                    help="tables are dealt round-robin to this many (compute, reorder) stream pairs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--prof-kernel", default="auto",
                     choices=["auto", "fwd_contract", "bwd_contract", "bag_sum", "grad_merge"],
@@ -88,48 +90,60 @@ def main():
         prof_name = "bwd_contract" if do_bwd else "fwd_contract"
     prof = tt.Prof(prof_name, (args.steps + 1) * ntab * 4) if args.arm == "plan" else None
 
-    s1 = torch.cuda.Stream()
-    s2 = s1 if args.no_overlap else torch.cuda.Stream()
-    ready = [torch.cuda.Event(), torch.cuda.Event()]
-    free = [torch.cuda.Event(), torch.cuda.Event()]
+    # Stream pairs: table t computes on cs[t % NS] and has the NEXT batch reordered on rs[t % NS]
+    # (all default priority).  Tables on different pairs run concurrently, which fills the chip
+    # when one table's kernels are too small to do so.
+    ns = max(1, min(args.streams, ntab))
+    cs = [torch.cuda.Stream() for _ in range(ns)]
+    rs = cs if args.no_overlap else [torch.cuda.Stream() for _ in range(ns)]
+    ready = [[torch.cuda.Event(), torch.cuda.Event()] for _ in range(ns)]
+    free = [[torch.cuda.Event(), torch.cuda.Event()] for _ in range(ns)]
     planned = args.arm == "plan"
+    groups = [[T for i, T in enumerate(tabs) if i % ns == k] for k in range(ns)]
 
     def reorder(b):
         buf = b % 2
-        for T in tabs:
-            x = T["batches"][b % nbatch]
-            # workspace sized for the largest batch; plan is rebuilt for this batch's nnz
-            T["plans"][buf] = tt.tt_index_reorder(T["table"], x["idx"], x["off"], workspace=T["ws"][buf], stream=s2)
-            if timing[0]:
-                prof.attach(T["plans"][buf])
-        ready[buf].record(s2)
+        for k in range(ns):
+            for T in groups[k]:
+                x = T["batches"][b % nbatch]
+                # workspace sized for the largest batch; the plan is rebuilt for this batch's nnz
+                T["plans"][buf] = tt.tt_index_reorder(T["table"], x["idx"], x["off"], workspace=T["ws"][buf],
+                                                      stream=rs[k])
+                if timing[0]:
+                    prof.attach(T["plans"][buf])
+            ready[k][buf].record(rs[k])
 
     def compute(b):
         buf = b % 2
-        if planned:
-            s1.wait_event(ready[buf])
-        for T in tabs:
-            x = T["batches"][b % nbatch]
-            plan = T["plans"][buf] if planned else None
-            if do_fwd:
-                tt.tt_emb_bag_forward(T["table"], plan, x["idx"], x["off"], out=T["out"], stream=s1)
-            if do_bwd:
-                tt.tt_emb_bag_backward(T["table"], plan, x["idx"], x["off"], x["grad"], dcores=T["dcores"], stream=s1)
-                tt.tt_core_sgd_update(T["table"], plan, T["dcores"], cfg.lr, stream=s1)
-        free[buf].record(s1)
+        for k in range(ns):
+            if planned:
+                cs[k].wait_event(ready[k][buf])
+            for T in groups[k]:
+                x = T["batches"][b % nbatch]
+                plan = T["plans"][buf] if planned else None
+                if do_fwd:
+                    tt.tt_emb_bag_forward(T["table"], plan, x["idx"], x["off"], out=T["out"], stream=cs[k])
+                if do_bwd:
+                    tt.tt_emb_bag_backward(T["table"], plan, x["idx"], x["off"], x["grad"], dcores=T["dcores"],
+                                           stream=cs[k])
+                    tt.tt_core_sgd_update(T["table"], plan, T["dcores"], cfg.lr, stream=cs[k])
+            free[k][buf].record(cs[k])
 
     timing = [False]
 
     def step(b):
-        """reorder(b+1) on s2 while batch b computes on s1; buffer (b+1)%2 was last used by b-1."""
+        """reorder(b+1) on the reorder streams while batch b computes; plan buffer (b+1)%2 was last
+        used by the compute of batch b-1."""
         if planned:
-            s2.wait_event(free[(b + 1) % 2])
+            for k in range(ns):
+                rs[k].wait_event(free[k][(b + 1) % 2])
             reorder(b + 1)
         compute(b)
 
     # prologue: plan of batch 0, both 'free' events recorded so the first waits pass
-    free[0].record(s1)
-    free[1].record(s1)
+    for k in range(ns):
+        free[k][0].record(cs[k])
+        free[k][1].record(cs[k])
     if planned:
         reorder(0)
     b = 0
@@ -147,6 +161,7 @@ def main():
         step(b)
         lookups += sum(T["batches"][b % nbatch]["nnz"] for T in tabs)
         b += 1
+    t_enqueue = time.perf_counter() - t0  # host time spent enqueueing (GPU may still be running)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     roofline = None
@@ -189,7 +204,8 @@ def main():
                                 " + row permutation" if (args.permute or cfg.permute_rows) else "",
                                 phases, args.arm),
                    "lookups_per_step": lookups // max(1, args.steps), "tables": ntab,
-                   "overlap_second_stream": (not args.no_overlap) and planned,
+                   "overlap_second_stream": (not args.no_overlap) and planned, "stream_pairs": ns,
+                   "host_enqueue_ms_per_step": round(1e3 * t_enqueue / args.steps, 3),
                    "input_generation_s": round(t_gen, 1)},
         "roofline": roofline,
         "cpu_baseline": None,
@@ -247,12 +263,14 @@ def read_traffic(workload, kernel):
 
 
 def cpu_baseline(cfg, wl, np):
-    """The oracle (definition mode, forward + backward) timed on a bounded sample of the workload."""
+    """The oracle (definition mode, forward + backward) timed on a bounded sample of the workload:
+    whole batches of the largest tables until the sample holds at least 10 s of CPU work (about
+    30 s at most), or a prefix of one batch when a single batch already takes longer."""
     from oracle import tt_oracle as ora
-    tab = int(np.argmax([t.num_rows for t in cfg.tables]))
-    shape, cores = cfg.tables[tab], wl.make_cores(cfg, tab)
+    order = list(np.argsort([-t.num_rows for t in cfg.tables]))
 
-    def run(nb):
+    def run(tab, nb):
+        shape, cores = cfg.tables[tab], wl.make_cores(cfg, tab)
         idx, off = wl.make_batch(cfg, tab, num_bags=nb)
         grad = wl.make_grad(cfg, tab, num_bags=nb)
         t0 = time.perf_counter()
@@ -260,17 +278,25 @@ def cpu_baseline(cfg, wl, np):
         ora.backward(shape, cores, idx, off, grad)
         return len(idx), time.perf_counter() - t0
 
-    nb = min(cfg.batch, 256)
-    run(min(cfg.batch, 64))  # thread start-up and page faults stay out of the measurement
-    n, t = run(nb)
-    for _ in range(4):  # grow the sample until it holds 10-30 s of CPU work (or the whole batch)
-        if t >= 10.0 or nb >= cfg.batch:
-            break
-        nb = int(min(cfg.batch, nb * min(16.0, max(2.0, 15.0 / max(t, 1e-3)))))
-        n, t = run(nb)
-    return {"value": n / t, "unit": "lookups/s", "cores": ora.max_threads(), "kind": "oracle",
-            "sample": "definition-mode forward+backward of the first %d bags (%d lookups) of table %d "
-                      "(%d rows), %.1f s" % (nb, n, tab, shape.num_rows, t)}
+    run(order[0], min(cfg.batch, 64))  # thread start-up and page faults stay out of the measurement
+    n_probe, t_probe = run(order[0], min(cfg.batch, 512))
+    per_batch = t_probe * cfg.batch / max(1, min(cfg.batch, 512))
+    total_n, total_t, used = 0, 0.0, []
+    if per_batch > 25.0:  # one batch is already too long: time a prefix of its bags
+        nb = max(64, int(cfg.batch * 15.0 / per_batch))
+        total_n, total_t = run(order[0], nb)
+        used.append("first %d bags of table %d" % (nb, order[0]))
+    else:
+        for tab in order:
+            n, t = run(tab, cfg.batch)
+            total_n += n
+            total_t += t
+            used.append(int(tab))
+            if total_t >= 10.0:
+                break
+        used = ["whole batches of tables %s" % used]
+    return {"value": total_n / total_t, "unit": "lookups/s", "cores": ora.max_threads(), "kind": "oracle",
+            "sample": "definition-mode forward+backward, %s (%d lookups), %.1f s" % (used[0], total_n, total_t)}
 
 
 if __name__ == "__main__":
