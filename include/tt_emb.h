@@ -115,6 +115,8 @@ typedef struct {
   float *t3buf;           /* [max_rows][r2*d2] per-row contributions to core 2            */
   float *t1buf;           /* [max_prefixes][d0*r1] per-prefix contributions to core 0     */
   float *partial;         /* segmented-reduction partials                                 */
+  float *g3t;             /* [n2][r2][d2] slice-contiguous copy of core 2, refreshed by
+                             every forward / backward call that uses the matrix-core path  */
   void *sort_tmp;         /* radix-sort ping-pong buffers, histograms, scan temporaries   */
   void *prof;             /* HOST, optional tt_prof* attached by the caller (NULL after
                              tt_index_reorder): brackets one kernel with HIP events       */

@@ -86,12 +86,13 @@ size_t layout(const TTShape &sh, int64_t nnz, int64_t num_bags, char *base, tt_p
   const size_t strips = (size_t)ttk_mfma_strips(sh);
   q.t3buf = floats((size_t)max_rows * sh.S3 * strips);
   q.t1buf = floats((size_t)max_pref * sh.S1 * strips);
-  size_t part = (size_t)(tt_ceil_div(nnz, TT_SEG_CHUNK) + 1) * 2 * sh.D;
-  size_t part3 = (size_t)(tt_ceil_div(max_rows, TT_SEG_CHUNK) + 1) * 2 * sh.S3;
-  size_t part1 = (size_t)(tt_ceil_div(max_pref, TT_SEG_CHUNK) + 1) * 2 * sh.S1;
+  size_t part = (size_t)(tt_ceil_div(nnz, TT_SEG_MIN_CHUNK) + 1) * 2 * sh.D;
+  size_t part3 = (size_t)(tt_ceil_div(max_rows, TT_SEG_MIN_CHUNK) + 1) * 2 * sh.S3;
+  size_t part1 = (size_t)(tt_ceil_div(max_pref, TT_SEG_MIN_CHUNK) + 1) * 2 * sh.S1;
   if (part3 > part) part = part3;
   if (part1 > part) part = part1;
   q.partial = floats(part);
+  q.g3t = floats((size_t)sh.n3 * sh.S3);
   q.sort_tmp = take(tt_sort_tmp_bytes(nnz, max_rows, max_pref));
   if (p) *p = q;
   return off;

@@ -17,7 +17,7 @@ namespace {
 // ------------------------------------------------------------------ two-stage segmented sum
 // Positions 0..M-1 carry a vector src[gidx[pos]][W] and a non-decreasing segment id
 // seg_src[pos]/seg_div; seg_off[s]..seg_off[s+1] is the position range of segment s.
-// Stage 1 walks fixed chunks of TT_SEG_CHUNK positions in order; a segment that lies inside one
+// Stage 1 walks fixed chunks of `chunk` positions in order; a segment that lies inside one
 // chunk is finished there, otherwise the chunk leaves a partial: slot 0 = run that began before
 // the chunk, slot 1 = run that begins in the chunk and continues past its end.
 // A position may carry `nsub` consecutive vectors (src[(gidx[pos]*nsub + t)][W], t < nsub),
@@ -59,12 +59,13 @@ __global__ void __launch_bounds__(TT_BLOCK)
 k_seg_stage1(int W, int lanes, const int32_t *__restrict__ count_ptr,
              const int32_t *__restrict__ seg_src, int seg_div, const int32_t *__restrict__ gidx,
              const int32_t *__restrict__ seg_off, const float *__restrict__ src, int nsub,
-             float *__restrict__ out, int out_inner, int nseg, float *__restrict__ partial) {
+             float *__restrict__ out, int out_inner, int nseg, float *__restrict__ partial,
+             int chunk) {
   const int M = *count_ptr;
-  const int nchunks = (M + TT_SEG_CHUNK - 1) / TT_SEG_CHUNK;
+  const int nchunks = (M + chunk - 1) / chunk;
   const int groups = blockDim.x / lanes, g = threadIdx.x / lanes, lane = threadIdx.x - g * lanes;
   for (int c = blockIdx.x * groups + g; c < nchunks; c += gridDim.x * groups) {
-    const int lo = c * TT_SEG_CHUNK, hi = lo + TT_SEG_CHUNK, end = hi < M ? hi : M;
+    const int lo = c * chunk, hi = lo + chunk, end = hi < M ? hi : M;
     for (int e = lane * VEC; e < W; e += lanes * VEC) {
       Vec<VEC> acc;
       acc.zero();
@@ -75,11 +76,11 @@ k_seg_stage1(int W, int lanes, const int32_t *__restrict__ count_ptr,
         else acc.store(partial + ((size_t)c * 2 + (a < lo ? 0 : 1)) * W + e);
       };
       int pos = lo;
-      for (; pos + 4 <= end; pos += 4) {  // four independent gathers in flight, added in order
-        int sg[4];
-        Vec<VEC> x[4];
+      for (; pos + TT_SEG_UNROLL <= end; pos += TT_SEG_UNROLL) {  // independent gathers in flight,
+        int sg[TT_SEG_UNROLL];                                    // added in position order
+        Vec<VEC> x[TT_SEG_UNROLL];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
+        for (int k = 0; k < TT_SEG_UNROLL; ++k) {
           sg[k] = seg_src[pos + k] / seg_div;
           const int row = gidx ? gidx[pos + k] : pos + k;
           x[k].load(src + (size_t)row * nsub * W + e);
@@ -90,7 +91,7 @@ k_seg_stage1(int W, int lanes, const int32_t *__restrict__ count_ptr,
           }
         }
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
+        for (int k = 0; k < TT_SEG_UNROLL; ++k) {
           if (sg[k] != cur) {
             if (cur >= 0) flush();
             cur = sg[k];
@@ -130,10 +131,10 @@ __global__ void __launch_bounds__(TT_BLOCK)
 k_seg_stage2(int W, int lanes, const int32_t *__restrict__ count_ptr,
              const int32_t *__restrict__ seg_src, int seg_div,
              const int32_t *__restrict__ seg_off, float *__restrict__ out, int out_inner,
-             int nseg, const float *__restrict__ partial, int dense) {
+             int nseg, const float *__restrict__ partial, int dense, int chunk) {
   extern __shared__ float red[];
   const int M = *count_ptr;
-  const int nchunks = (M + TT_SEG_CHUNK - 1) / TT_SEG_CHUNK;
+  const int nchunks = (M + chunk - 1) / chunk;
   const int c = blockIdx.x;
   const int groups = blockDim.x / lanes, g = threadIdx.x / lanes, lane = threadIdx.x - g * lanes;
   if (dense && c < nseg && seg_off[c] == seg_off[c + 1] && g == 0) {
@@ -143,11 +144,11 @@ k_seg_stage2(int W, int lanes, const int32_t *__restrict__ count_ptr,
       z.store(out + seg_out_index(c, e, out_inner, nseg));
   }
   if (c >= nchunks) return;  // uniform
-  const int lo = c * TT_SEG_CHUNK, hi = lo + TT_SEG_CHUNK, end = hi < M ? hi : M;
+  const int lo = c * chunk, hi = lo + chunk, end = hi < M ? hi : M;
   const int s = seg_src[end - 1] / seg_div;
   const int a = seg_off[s], b = seg_off[s + 1];
   if (!(a >= lo && b > hi)) return;  // uniform: no segment starts here and runs past the chunk
-  const int c1 = (b - 1) / TT_SEG_CHUNK;
+  const int c1 = (b - 1) / chunk;
   for (int e = lane * VEC; e < W; e += lanes * VEC) {
     Vec<VEC> acc;
     acc.zero();
@@ -197,6 +198,7 @@ struct SegArgs {
   int nseg;   // number of segments for the output layout / dense zero fill
   int dense;
   float *partial;
+  int chunk;            // positions per stage-1 chunk (>= TT_SEG_MIN_CHUNK)
   const tt_plan *plan;  // for the optional timing scope
   int prof_kernel;      // kernel id of stage 1, or -1
 };
@@ -208,7 +210,7 @@ tt_status seg_sum(const SegArgs &a, hipStream_t s) {
   int lanes = 1;
   while (lanes < TT_WAVE && lanes * vec < a.W) lanes <<= 1;
   const int groups = TT_BLOCK / lanes;
-  const int nchunks = tt_ceil_div(a.max_count, TT_SEG_CHUNK);
+  const int nchunks = tt_ceil_div(a.max_count, a.chunk);
   if (nchunks > 0) {
     int blocks = tt_ceil_div(nchunks, groups);
     if (blocks > 8192) blocks = 8192;
@@ -216,11 +218,11 @@ tt_status seg_sum(const SegArgs &a, hipStream_t s) {
     if (vec4)
       hipLaunchKernelGGL(k_seg_stage1<4>, dim3(blocks), dim3(TT_BLOCK), 0, s, a.W, lanes,
                          a.count_ptr, a.seg_src, a.seg_div, a.gidx, a.seg_off, a.src, a.nsub, a.out,
-                         a.out_inner, a.nseg, a.partial);
+                         a.out_inner, a.nseg, a.partial, a.chunk);
     else
       hipLaunchKernelGGL(k_seg_stage1<1>, dim3(blocks), dim3(TT_BLOCK), 0, s, a.W, lanes,
                          a.count_ptr, a.seg_src, a.seg_div, a.gidx, a.seg_off, a.src, a.nsub, a.out,
-                         a.out_inner, a.nseg, a.partial);
+                         a.out_inner, a.nseg, a.partial, a.chunk);
   }
   int blocks2 = nchunks;
   if (a.dense && a.nseg > blocks2) blocks2 = a.nseg;
@@ -229,11 +231,11 @@ tt_status seg_sum(const SegArgs &a, hipStream_t s) {
     if (vec4)
       hipLaunchKernelGGL(k_seg_stage2<4>, dim3(blocks2), dim3(TT_BLOCK), lds, s, a.W, lanes,
                          a.count_ptr, a.seg_src, a.seg_div, a.seg_off, a.out, a.out_inner, a.nseg,
-                         a.partial, a.dense);
+                         a.partial, a.dense, a.chunk);
     else
       hipLaunchKernelGGL(k_seg_stage2<1>, dim3(blocks2), dim3(TT_BLOCK), lds, s, a.W, lanes,
                          a.count_ptr, a.seg_src, a.seg_div, a.seg_off, a.out, a.out_inner, a.nseg,
-                         a.partial, a.dense);
+                         a.partial, a.dense, a.chunk);
   }
   return tt_launch_status();
 }
@@ -474,7 +476,7 @@ tt_status ttk_backward_plan(const TTShape &sh, const tt_table *t, const tt_plan 
   // 1. merge output gradients per distinct row
   SegArgs a1 = {sh.D, plan->counts + 2, plan->nnz, plan->slot_of_sorted, 1, plan->bag_of_sorted,
                 plan->row_seg, grad_out, 1, plan->gagg, sh.D, (int)plan->max_rows, 0,
-                plan->partial, plan, TT_KERNEL_GRAD_MERGE};
+                plan->partial, 32, plan, TT_KERNEL_GRAD_MERGE};
   if ((st = seg_sum(a1, s)) != TT_OK) return st;
   // 2. per-prefix contractions
   const bool mfma = tt_mfma_enabled() && ttk_forward_mfma_supported(sh);
@@ -491,11 +493,11 @@ tt_status ttk_backward_plan(const TTShape &sh, const tt_table *t, const tt_plan 
   }
   // 3a. core 2: sum the per-row contributions of all rows sharing i3
   SegArgs a3 = {sh.S3, plan->counts + 0, plan->max_rows, plan->i3_of_sorted, 1, plan->rows_by_i3,
-                plan->i3_seg, plan->t3buf, strips, dcore[2], sh.d3, sh.n3, 1, plan->partial, plan, -1};
+                plan->i3_seg, plan->t3buf, strips, dcore[2], sh.d3, sh.n3, 1, plan->partial, TT_SEG_MIN_CHUNK, plan, -1};
   if ((st = seg_sum(a3, s)) != TT_OK) return st;
   // 3b. core 0: sum the per-prefix contributions of all prefixes sharing i1 (contiguous)
   SegArgs a0 = {sh.S1, plan->counts + 1, plan->max_prefixes, plan->uniq_pref, sh.n2, nullptr,
-                plan->i1_seg, plan->t1buf, strips, dcore[0], sh.S1, sh.n1, 1, plan->partial, plan, -1};
+                plan->i1_seg, plan->t1buf, strips, dcore[0], sh.S1, sh.n1, 1, plan->partial, TT_SEG_MIN_CHUNK, plan, -1};
   if ((st = seg_sum(a0, s)) != TT_OK) return st;
   // 3c. core 1: per-i2 accumulation over prefixes (done inside the matrix-core kernel)
   if (!mfma)

@@ -42,7 +42,7 @@ struct FwdGeom {
 template <int R1, int R2, int D2>
 __global__ void __launch_bounds__(TT_BLOCK)
 k_fwd_mfma(TTShape sh, const float *__restrict__ g1, const float *__restrict__ g2,
-           const float *__restrict__ g3, const int32_t *__restrict__ counts,
+           const float *__restrict__ g3t, const int32_t *__restrict__ counts,
            const int32_t *__restrict__ uniq_pref, const int32_t *__restrict__ pref_seg,
            const int32_t *__restrict__ uniq_row, const int32_t *__restrict__ prefs_by_i2,
            const int32_t *__restrict__ i2_seg, const int32_t *__restrict__ i2_chunk_off,
@@ -152,10 +152,10 @@ k_fwd_mfma(TTShape sh, const float *__restrict__ g1, const float *__restrict__ g
       // A operand: G3[r2][i3(row)][j3], m = (row, j3) = lm, k = r2
       const int arow = (lm >> 2) < nrow ? (lm >> 2) : nrow - 1;
       const int i3 = uniq_row[ubase + arow] % sh.n3;
-      const float *ap = g3 + ((size_t)lq * sh.n3 + i3) * 4 + (lm & 3);
+      const float *ap = g3t + (size_t)i3 * (R2 * 4) + lq * 4 + (lm & 3);
       float a[G::KS2];
 #pragma unroll
-      for (int ks = 0; ks < G::KS2; ++ks) a[ks] = ap[(size_t)(4 * ks) * sh.n3 * 4];
+      for (int ks = 0; ks < G::KS2; ++ks) a[ks] = ap[16 * ks];
       const float *bp = P12s + p * G::PS + lm * G::Rp + lq;
       f32x4 o[G::NT2];
 #pragma unroll
@@ -178,6 +178,17 @@ k_fwd_mfma(TTShape sh, const float *__restrict__ g1, const float *__restrict__ g
   }
 }
 
+// g3t[i3][r2][j3] = G3[r2][i3][j3]: a row's core-2 slice becomes one contiguous block, so the
+// MFMA operand gathers touch 2-4 cache lines per wavefront load instead of 16.
+__global__ void k_pack_g3(int n3, int R2, int d3, const float *__restrict__ g3,
+                          float *__restrict__ g3t) {
+  const int total = n3 * R2 * d3;
+  for (int e = blockIdx.x * blockDim.x + threadIdx.x; e < total; e += gridDim.x * blockDim.x) {
+    const int j3 = e % d3, r2 = (e / d3) % R2, i3 = e / (d3 * R2);
+    g3t[e] = g3[((size_t)r2 * n3 + i3) * d3 + j3];
+  }
+}
+
 template <int R1, int R2, int D2>
 tt_status launch(const TTShape &sh, const tt_table *t, const tt_plan *plan, hipStream_t s) {
   using G = FwdGeom<R1, R2, D2>;
@@ -194,13 +205,22 @@ tt_status launch(const TTShape &sh, const tt_table *t, const tt_plan *plan, hipS
   if (blocks > 8192) blocks = 8192;  // grid-stride loop covers the rest
   TTProfScope prof(plan, TT_KERNEL_FWD_CONTRACT, s);
   hipLaunchKernelGGL((k_fwd_mfma<R1, R2, D2>), dim3((unsigned)blocks), dim3(TT_BLOCK), lds, s, sh,
-                     t->core[0], t->core[1], t->core[2], plan->counts, plan->uniq_pref,
+                     t->core[0], t->core[1], plan->g3t, plan->counts, plan->uniq_pref,
                      plan->pref_seg, plan->uniq_row, plan->prefs_by_i2, plan->i2_seg,
                      plan->i2_chunk_off, plan->rowbuf);
   return tt_launch_status();
 }
 
 }  // namespace
+
+tt_status ttk_pack_g3(const TTShape &sh, const tt_table *t, const tt_plan *plan, hipStream_t s) {
+  const int total = sh.n3 * sh.S3;
+  int blocks = tt_ceil_div(total, TT_BLOCK);
+  if (blocks > 1024) blocks = 1024;
+  hipLaunchKernelGGL(k_pack_g3, dim3(blocks), dim3(TT_BLOCK), 0, s, sh.n3, sh.R2, sh.d3, t->core[2],
+                     plan->g3t);
+  return tt_launch_status();
+}
 
 bool ttk_forward_mfma_supported(const TTShape &sh) {
   if (sh.d1 != 4 || sh.d3 != 4 || sh.d2 != 8) return false;
@@ -209,6 +229,8 @@ bool ttk_forward_mfma_supported(const TTShape &sh) {
 
 tt_status ttk_forward_mfma(const TTShape &sh, const tt_table *t, const tt_plan *plan,
                            hipStream_t s) {
+  tt_status st = ttk_pack_g3(sh, t, plan, s);
+  if (st != TT_OK) return st;
   if (sh.R1 == 32) return launch<32, 32, 8>(sh, t, plan, s);
   return launch<64, 64, 8>(sh, t, plan, s);
 }

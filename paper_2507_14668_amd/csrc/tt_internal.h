@@ -26,7 +26,7 @@ struct TTShape {
 #define TT_BLOCK 256
 
 // ---- radix sort geometry ----------------------------------------------------------------
-#define TT_SORT_ITEMS 8
+#define TT_SORT_ITEMS 4
 #define TT_SORT_TILE (TT_BLOCK * TT_SORT_ITEMS)  // keys per workgroup per pass
 #define TT_SORT_MAX_BITS 10                      // digit width limit (1024 bins)
 
@@ -34,7 +34,8 @@ struct TTShape {
 #define TT_MP 8  // distinct prefixes per chunk: two 16-row MFMA tiles of (prefix, j1) rows
 
 // ---- segmented-reduction geometry -----------------------------------------------------------
-#define TT_SEG_CHUNK 64  // positions per chunk of the two-stage segmented sum
+#define TT_SEG_MIN_CHUNK 16  // smallest stage-1 chunk of the two-stage segmented sum (sizes the partials)
+#define TT_SEG_UNROLL 8      // gathers a lane group keeps in flight
 
 static inline int tt_ceil_div(long long a, long long b) { return (int)((a + b - 1) / b); }
 
@@ -47,6 +48,8 @@ tt_status ttk_forward_plan(const TTShape &sh, const tt_table *t, const tt_plan *
 bool ttk_forward_mfma_supported(const TTShape &sh);
 tt_status ttk_forward_mfma(const TTShape &sh, const tt_table *t, const tt_plan *plan,
                            hipStream_t s);
+// slice-contiguous copy of core 2 for the matrix-core kernels: g3t[i3][r2][j3] = G3[r2][i3][j3]
+tt_status ttk_pack_g3(const TTShape &sh, const tt_table *t, const tt_plan *plan, hipStream_t s);
 // number of 256-column strips a core-1 slice is cut into by the matrix-core kernels (1 when the
 // shape is served by the plain-ALU kernels); t3buf / t1buf hold one contribution per strip
 int ttk_mfma_strips(const TTShape &sh);
