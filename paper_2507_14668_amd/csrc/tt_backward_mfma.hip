@@ -40,10 +40,11 @@ struct BwdGeom {
   static constexpr int HS = 260;           // Hs   [32 (p,j1)][256 c]
   static constexpr int KS1 = R1 / 4, NT1 = R1 / 16, NTH = R2 / 16, MT2 = CC / 16, KS3 = CC / 4;
   static constexpr int D = 4 * D2 * 4, S3 = R2 * 4, S1 = 4 * R1;
-  static constexpr int OFF_AST = 32 * RS;
-  static constexpr int OFF_HS = OFF_AST + R1 * RT;
+  static constexpr int A_FLOATS = 32 * RS + R1 * RT;  // one As + AsT pair
+  static constexpr int OFF_AST = 32 * RS;             // AsT inside a pair
+  static constexpr int OFF_HS = 2 * A_FLOATS;         // two pairs: current chunk / next chunk
   static constexpr int OFF_P12 = OFF_HS + 32 * HS;
-  static constexpr int GS = D + 16;        // gs   [32 rows][D]   merged gradients of a row batch
+  static constexpr int GS = CC * 4 + 16;   // gs   [32 rows][CC*4] merged gradients of a row batch, strip columns
   static constexpr int G3S = S3 + 16;      // g3s  [32 rows][S3]  their core-2 slices
   static constexpr int OFF_GS = OFF_P12 + TT_MP * PS;
   static constexpr int OFF_G3S = OFF_GS + 32 * GS;
@@ -68,12 +69,13 @@ k_bwd_mfma(TTShape sh, const float *__restrict__ g1, const float *__restrict__ g
   constexpr int T3_SPLIT = 4 / G::NTH;       // wave groups that alternate over the row quads for T3
   static_assert(G::MT2 * G::NTH == 4, "one H tile per wavefront");
   extern __shared__ float lds[];
-  float *As = lds, *AsT = lds + G::OFF_AST, *Hs = lds + G::OFF_HS, *P12sT = lds + G::OFF_P12;
+  float *Hs = lds + G::OFF_HS, *P12sT = lds + G::OFF_P12;  // As / AsT: two pairs at lds + par*A_FLOATS
   float *T1s = P12sT;  // [4 waves][32][R1], used after the chunk's last reader of P12sT
   float *gsm = lds + G::OFF_GS, *g3sm = lds + G::OFF_G3S;
-  __shared__ int s_item_off[TT_MP + 1];
+  __shared__ int s_item_off[2][TT_MP + 1];
+  __shared__ int s_bitem[8][4];  // items of the current row batch: prefix, first row slot, rows, last
   __shared__ int s_q[TT_META], s_i1[TT_META], s_u0[TT_META], s_nr[TT_META];
-  __shared__ int s_i3[TT_MP][TT_I3_STAGE];
+  __shared__ int s_i3[2][TT_MP][TT_I3_STAGE];
 
   const int i2 = blockIdx.x / G::NSTRIP, strip = blockIdx.x - i2 * G::NSTRIP;
   const int j2base = strip * G::JW;
@@ -88,22 +90,8 @@ k_bwd_mfma(TTShape sh, const float *__restrict__ g1, const float *__restrict__ g
     return;
   }
 
-  // both register views of this wave's 64 columns of the strip
-  float breg[G::KS1][4];       // F1: B[k = r1][n = c]
-  float breg2[16][G::NT1];     // T1: B[k = c][n = r1]
-#pragma unroll
-  for (int ks = 0; ks < G::KS1; ++ks)
-#pragma unroll
-    for (int nt = 0; nt < 4; ++nt)
-      breg[ks][nt] = g2[(size_t)(4 * ks + lq) * sh.n2 * G::S2 + strip_col + 64 * wave + 16 * nt + lm];
-#pragma unroll
-  for (int ks = 0; ks < 16; ++ks)
-#pragma unroll
-    for (int nt = 0; nt < G::NT1; ++nt)
-      breg2[ks][nt] = g2[(size_t)(16 * nt + lm) * sh.n2 * G::S2 + strip_col + 64 * wave + 4 * ks + lq];
-
 #ifdef TT_DBG_TIMING
-  long long tph[6] = {0, 0, 0, 0, 0, 0}, tlast = clock64();
+  long long tph[8] = {0, 0, 0, 0, 0, 0, 0, 0}, tlast = clock64();
 #define TT_TICK(k) { long long tn = clock64(); tph[k] += tn - tlast; tlast = tn; }
 #else
 #define TT_TICK(k)
@@ -138,83 +126,133 @@ k_bwd_mfma(TTShape sh, const float *__restrict__ g1, const float *__restrict__ g
       g1n[k] = i1 >= 0 ? g1[(size_t)i1 * G::S1 + (row & 3) * R1 + r1] : 0.f;
     }
     const int p = threadIdx.x / TT_I3_STAGE, r = threadIdx.x - p * TT_I3_STAGE;
-    i3n = r < s_nr[mo + p] ? uniq_row[s_u0[mo + p] + r] % sh.n3 : 0;
+    // the row index is kept raw here; taking it modulo n3 now would wait for the load at once
+    i3n = r < s_nr[mo + p] ? uniq_row[s_u0[mo + p] + r] : 0;
   };
   static_assert(TT_MP * TT_I3_STAGE == TT_BLOCK, "one staged i3 per thread");
+
+  // registers -> LDS (buffer pair `par`) for a chunk whose operands were fetched earlier
+  auto stage_chunk = [&](int par, int mo2, int cnt2) __attribute__((always_inline)) {
+    float *As2 = lds + par * G::A_FLOATS, *AsT2 = As2 + G::OFF_AST;
+#pragma unroll
+    for (int k = 0; k < GPT; ++k) {
+      const int e = threadIdx.x + k * TT_BLOCK, row = e / R1, r1 = e - row * R1;
+      As2[row * G::RS + r1] = g1n[k];
+      AsT2[r1 * G::RT + row] = g1n[k];
+    }
+    s_i3[par][threadIdx.x / TT_I3_STAGE][threadIdx.x % TT_I3_STAGE] = i3n % sh.n3;
+    if (threadIdx.x == 0) {  // quads per prefix of the chunk, running total
+      int run = 0;
+      for (int p = 0; p < TT_MP; ++p) {
+        s_item_off[par][p] = run;
+        if (p < cnt2) run += (s_nr[mo2 + p] + 3) >> 2;
+      }
+      s_item_off[par][TT_MP] = run;
+    }
+  };
+  auto zero_unused_h = [&](int cnt2) __attribute__((always_inline)) {
+    // rows of the prefixes a partly filled chunk does not have contribute zeros to T1 / dG2
+    for (int e = 4 * cnt2 * 256 + threadIdx.x; e < 32 * 256; e += TT_BLOCK)
+      Hs[(e >> 8) * G::HS + (e & 255)] = 0.f;
+  };
 
   fetch_meta(seg0);
   __syncthreads();
   fetch_chunk(0);
 
+  // both register views of this wave's 64 columns of the strip (requested after the first chunk's
+  // plan entries so that they are in flight while the chunk is staged)
+  float breg[G::KS1][4];       // F1: B[k = r1][n = c]
+  float breg2[16][G::NT1];     // T1: B[k = c][n = r1]
+#pragma unroll
+  for (int ks = 0; ks < G::KS1; ++ks)
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt)
+      breg[ks][nt] = g2[(size_t)(4 * ks + lq) * sh.n2 * G::S2 + strip_col + 64 * wave + 16 * nt + lm];
+#pragma unroll
+  for (int ks = 0; ks < 16; ++ks)
+#pragma unroll
+    for (int nt = 0; nt < G::NT1; ++nt)
+      breg2[ks][nt] = g2[(size_t)(16 * nt + lm) * sh.n2 * G::S2 + strip_col + 64 * wave + 4 * ks + lq];
+
+
+  int bi_p = 0, bi_ubase = 0, bi_nrow = 0, bi_last = 0;  // item record written by one thread per item
+  float4 rg[G::CC / 8], r3[G::S3 / 32];
+#pragma unroll
+  for (int k = 0; k < G::CC / 8; ++k) rg[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+  for (int k = 0; k < G::S3 / 32; ++k) r3[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+  int rvalid = 0;
+  auto issue_batch = [&](int b, int par, int mo) __attribute__((always_inline)) {
+    // global -> registers for batch b of the chunk staged in buffer pair `par` (plan entries at
+    // offset `mo`); thread t serves row slot t/8
+    const int total_items = s_item_off[par][TT_MP];
+    const int rr = threadIdx.x >> 3, sub = threadIdx.x & 7;
+    const int it = 8 * b + (rr >> 2), r = rr & 3;
+    rvalid = 0;
+    if (it < total_items) {
+      int p = 0;
+#pragma unroll
+      for (int k = 1; k < TT_MP; ++k) p += (s_item_off[par][k] <= it) ? 1 : 0;
+      const int r0 = 4 * (it - s_item_off[par][p]) + r;
+      bi_p = p;
+      bi_ubase = s_u0[mo + p] + (r0 - r);
+      bi_nrow = (s_nr[mo + p] - (r0 - r)) < 4 ? (s_nr[mo + p] - (r0 - r)) : 4;
+      bi_last = (r0 - r) + 4 >= s_nr[mo + p];
+      if (r0 < s_nr[mo + p]) {
+        const int u = s_u0[mo + p] + r0;
+        const int i3 = r0 < TT_I3_STAGE ? s_i3[par][p][r0] : uniq_row[u] % sh.n3;
+        const float4 *gp = reinterpret_cast<const float4 *>(gagg + (size_t)u * G::D);
+        const float4 *g3p = reinterpret_cast<const float4 *>(g3t + (size_t)i3 * G::S3) + sub;
+#pragma unroll
+        for (int k = 0; k < G::CC / 8; ++k) {  // float4 cc = sub + 8k of the strip: (j1, j2, 0..3)
+          const int cc = sub + 8 * k;
+          rg[k] = gp[(cc / G::JW) * D2 + j2base + (cc % G::JW)];
+        }
+#pragma unroll
+        for (int k = 0; k < G::S3 / 32; ++k) r3[k] = g3p[8 * k];
+        rvalid = 1;
+      }
+    }
+  };
+  auto land_batch = [&]() __attribute__((always_inline)) {  // registers -> LDS
+    if ((threadIdx.x & 31) == 0) {
+      int *rec = s_bitem[threadIdx.x >> 5];
+      rec[0] = bi_p; rec[1] = bi_ubase; rec[2] = bi_nrow; rec[3] = bi_last;
+    }
+    if (rvalid) {
+      const int rr = threadIdx.x >> 3, sub = threadIdx.x & 7;
+      float4 *gd = reinterpret_cast<float4 *>(gsm + rr * G::GS) + sub;
+      float4 *g3d = reinterpret_cast<float4 *>(g3sm + rr * G::G3S) + sub;
+#pragma unroll
+      for (int k = 0; k < G::CC / 8; ++k) gd[8 * k] = rg[k];
+#pragma unroll
+      for (int k = 0; k < G::S3 / 32; ++k) g3d[8 * k] = r3[k];
+    }
+  };
+
+  stage_chunk(0, 0, (seg1 - seg0) < TT_MP ? (seg1 - seg0) : TT_MP);
+  zero_unused_h((seg1 - seg0) < TT_MP ? (seg1 - seg0) : TT_MP);
+  int par = 0;  // buffer pair of the current chunk
+  __syncthreads();
+  issue_batch(0, 0, 0);  // first row batch of the first chunk
+
   for (int cs = seg0; cs < seg1; cs += TT_MP) {
     const int cnt = (seg1 - cs) < TT_MP ? (seg1 - cs) : TT_MP;
     const int mo = (cs - seg0) % TT_META;  // this chunk's offset in s_q / s_i1 / s_u0 / s_nr
-    __syncthreads();  // previous chunk: T1 partials read, Hs / AsT / s_i3 consumed
-#pragma unroll
-    for (int k = 0; k < GPT; ++k) {
-      const int e = threadIdx.x + k * TT_BLOCK, row = e / R1, r1 = e - row * R1;
-      As[row * G::RS + r1] = g1n[k];
-      AsT[r1 * G::RT + row] = g1n[k];
-    }
-    s_i3[threadIdx.x / TT_I3_STAGE][threadIdx.x % TT_I3_STAGE] = i3n;
-    if (threadIdx.x == 0) {  // quads per prefix of this chunk, running total
-      int run = 0;
-      for (int p = 0; p < TT_MP; ++p) {
-        s_item_off[p] = run;
-        if (p < cnt) run += (s_nr[mo + p] + 3) >> 2;
-      }
-      s_item_off[TT_MP] = run;
-    }
-    for (int e = threadIdx.x; e < 32 * 256; e += TT_BLOCK)  // unused prefixes contribute zeros
-      if ((e >> 10) >= cnt) Hs[(e >> 8) * G::HS + (e & 255)] = 0.f;
-    __syncthreads();
+    TT_TICK(7)
+    __syncthreads();  // this chunk's staging is visible; previous chunk's T1 partials are consumed
     TT_TICK(0)
 
     // Row batches: the merged gradients and core-2 slices of up to 32 distinct rows (8 quads) are
     // brought into LDS by all 256 threads at once (one memory latency per batch instead of one
     // per quad).  The loads of the chunk's first batch are issued before F1 and land in LDS after
     // it, so F1's MFMAs hide their latency.
-    const int total_items = s_item_off[TT_MP];
-    float4 rg[4], r3[G::S3 / 32];
-#pragma unroll
-    for (int k = 0; k < 4; ++k) rg[k] = make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll
-    for (int k = 0; k < G::S3 / 32; ++k) r3[k] = make_float4(0.f, 0.f, 0.f, 0.f);
-    int rvalid = 0;
-    auto issue_batch = [&](int b) __attribute__((always_inline)) {  // global -> registers; thread t serves row slot t/8
-      const int rr = threadIdx.x >> 3, sub = threadIdx.x & 7;
-      const int it = 8 * b + (rr >> 2), r = rr & 3;
-      rvalid = 0;
-      if (it < total_items) {
-        int p = 0;
-#pragma unroll
-        for (int k = 1; k < TT_MP; ++k) p += (s_item_off[k] <= it) ? 1 : 0;
-        const int r0 = 4 * (it - s_item_off[p]) + r;
-        if (r0 < s_nr[mo + p]) {
-          const int u = s_u0[mo + p] + r0;
-          const int i3 = r0 < TT_I3_STAGE ? s_i3[p][r0] : uniq_row[u] % sh.n3;
-          const float4 *gp = reinterpret_cast<const float4 *>(gagg + (size_t)u * G::D) + sub;
-          const float4 *g3p = reinterpret_cast<const float4 *>(g3t + (size_t)i3 * G::S3) + sub;
-#pragma unroll
-          for (int k = 0; k < 4; ++k) rg[k] = gp[8 * k];
-#pragma unroll
-          for (int k = 0; k < G::S3 / 32; ++k) r3[k] = g3p[8 * k];
-          rvalid = 1;
-        }
-      }
-    };
-    auto land_batch = [&]() __attribute__((always_inline)) {  // registers -> LDS
-      if (rvalid) {
-        const int rr = threadIdx.x >> 3, sub = threadIdx.x & 7;
-        float4 *gd = reinterpret_cast<float4 *>(gsm + rr * G::GS) + sub;
-        float4 *g3d = reinterpret_cast<float4 *>(g3sm + rr * G::G3S) + sub;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) gd[8 * k] = rg[k];
-#pragma unroll
-        for (int k = 0; k < G::S3 / 32; ++k) g3d[8 * k] = r3[k];
-      }
-    };
-    issue_batch(0);
+    const float *As = lds + par * G::A_FLOATS, *AsT = As + G::OFF_AST;
+    const bool more = cs + TT_MP < seg1, refill = mo + TT_MP == TT_META;
+    const int cnt_next = (seg1 - cs - TT_MP) < TT_MP ? (seg1 - cs - TT_MP) : TT_MP;
+    const int total_items = s_item_off[par][TT_MP];
+    if (more && !refill) fetch_chunk(mo + TT_MP);  // next chunk's operands, consumed right after F1
 
     // ---- F1: P12 of the chunk -> P12sT[p][r2][cc] ---------------------------------------------
     {
@@ -246,8 +284,9 @@ k_bwd_mfma(TTShape sh, const float *__restrict__ g1, const float *__restrict__ g
       }
     }
     land_batch();
-    // next chunk's operands: requested now, consumed at the top of the next iteration
-    if (cs + TT_MP < seg1 && mo + TT_MP != TT_META) fetch_chunk(mo + TT_MP);
+    // All global loads of this chunk are consumed here, in one wait that F1 has mostly hidden; no
+    // load is waited for while the row phase's stores are in flight.
+    if (more && !refill) stage_chunk(par ^ 1, mo + TT_MP, cnt_next);
     __syncthreads();
     TT_TICK(1)
 
@@ -258,58 +297,87 @@ k_bwd_mfma(TTShape sh, const float *__restrict__ g1, const float *__restrict__ g
     // no partial sums have to be combined.
     {
       const int hmt = wave / G::NTH, hnt = wave % G::NTH;
-      const int hcol = ((16 * hmt + lm) / G::JW) * D2 + j2base + ((16 * hmt + lm) % G::JW);
+      const int hcol = 16 * hmt + lm;  // gs holds the strip's (j1, j2) columns in cc order
       f32x4 hacc = (f32x4){0.f, 0.f, 0.f, 0.f};
+      struct Info { int p, ubase, nrow, last; };
+      struct Ops { float ta[G::KS3], tb[G::KS3], ah[4], bh[4]; };
+      // LDS -> registers for the item in batch slot j (requested one item ahead of its MFMAs)
+      auto load_ops = [&](int j, bool t3, Info &ii, Ops &o) __attribute__((always_inline)) {
+        // the record is the same for every lane: move it to scalar registers
+        ii.p = __builtin_amdgcn_readfirstlane(s_bitem[j][0]);
+        ii.ubase = __builtin_amdgcn_readfirstlane(s_bitem[j][1]);
+        ii.nrow = __builtin_amdgcn_readfirstlane(s_bitem[j][2]);
+        ii.last = __builtin_amdgcn_readfirstlane(s_bitem[j][3]);
+        const float *gq = gsm + (j * 4) * G::GS;     // the quad's four gradient rows
+        const float *g3q = g3sm + (j * 4) * G::G3S;  // and core-2 slices
+        if (t3) {  // T3: M = (row, j3) = lm, N = r2 tile hnt, K = cc
+          const float *ga = gq + (lm >> 2) * G::GS + (lm & 3) + lq * 4;  // + 16*ks: cc = 4*ks + lq
+          const float *pb = P12sT + ii.p * G::PS + (16 * hnt + lm) * G::CP + lq;
+#pragma unroll
+          for (int ks = 0; ks < G::KS3; ++ks) {
+            o.ta[ks] = ga[16 * ks];
+            o.tb[ks] = pb[4 * ks];
+          }
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {  // H tile (hmt, hnt): M = cc, N = r2, K = j3
+          o.ah[r] = gq[r * G::GS + hcol * 4 + lq];
+          o.bh[r] = g3q[r * G::G3S + (16 * hnt + lm) * 4 + lq];
+        }
+      };
+      auto compute = [&](bool t3, const Info &ii, const Ops &o) __attribute__((always_inline)) {
+        if (t3) {
+          f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int ks = 0; ks < G::KS3; ++ks) acc = MFMA(o.ta[ks], o.tb[ks], acc);
+          if (lq < ii.nrow)
+            *reinterpret_cast<float4 *>(t3buf + ((size_t)(ii.ubase + lq) * G::NSTRIP + strip) * G::S3 +
+                                        (16 * hnt + lm) * 4) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r)  // one distinct row per MFMA step
+          if (r < ii.nrow) hacc = MFMA(o.ah[r], o.bh[r], hacc);
+        if (ii.last) {  // last quad of the prefix: H[cc = 16*hmt + 4*lq + v][r2 = 16*hnt + lm]
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            const int c2 = 16 * hmt + 4 * lq + v, j1 = c2 / G::JW, j2loc = c2 - j1 * G::JW;
+            Hs[(ii.p * 4 + j1) * G::HS + j2loc * R2 + 16 * hnt + lm] = hacc[v];
+          }
+          hacc = (f32x4){0.f, 0.f, 0.f, 0.f};
+        }
+      };
       const int nbatch = (total_items + 7) >> 3;
       for (int b = 0; b < nbatch; ++b) {
         if (b > 0) {  // uniform: further batches of a row-rich chunk (latency exposed)
+          TT_TICK(2)
           __syncthreads();
-          issue_batch(b);
+          issue_batch(b, par, mo);
           land_batch();
           __syncthreads();
+          TT_TICK(6)
         }
-        const int it_end = (8 * b + 8) < total_items ? (8 * b + 8) : total_items;
-        for (int it = 8 * b; it < it_end; ++it) {
-          int p = 0;
-#pragma unroll
-          for (int k = 1; k < TT_MP; ++k) p += (s_item_off[k] <= it) ? 1 : 0;
-          const int quad = it - s_item_off[p];
-          const int nr = s_nr[mo + p], ubase = s_u0[mo + p] + 4 * quad;
-          const int nrow = (nr - 4 * quad) < 4 ? (nr - 4 * quad) : 4;
-          const float *gq = gsm + ((it & 7) * 4) * G::GS;     // the quad's four gradient rows
-          const float *g3q = g3sm + ((it & 7) * 4) * G::G3S;  // and core-2 slices
-          if ((it % T3_SPLIT) == hmt) {  // T3: M = (row, j3) = lm, N = r2 tile hnt, K = cc
-            const float *ga = gq + (lm >> 2) * G::GS + (lm & 3);
-            const float *pb = P12sT + p * G::PS + (16 * hnt + lm) * G::CP + lq;
-            f32x4 t3 = (f32x4){0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int ks = 0; ks < G::KS3; ++ks) {
-              const int cc = 4 * ks + lq, col = (cc / G::JW) * D2 + j2base + (cc % G::JW);
-              t3 = MFMA(ga[col * 4], pb[4 * ks], t3);
-            }
-            if (lq < nrow)
-              *reinterpret_cast<float4 *>(t3buf + ((size_t)(ubase + lq) * G::NSTRIP + strip) * G::S3 +
-                                          (16 * hnt + lm) * 4) = make_float4(t3[0], t3[1], t3[2], t3[3]);
-          }
-          // H tile (hmt, hnt): M = cc, N = r2, K = j3 (one distinct row per MFMA step)
-#pragma unroll
-          for (int r = 0; r < 4; ++r)
-            if (r < nrow)
-              hacc = MFMA(gq[r * G::GS + hcol * 4 + lq], g3q[r * G::G3S + (16 * hnt + lm) * 4 + lq], hacc);
-          if (4 * quad + 4 >= nr) {  // last quad of the prefix: H[cc = 16*hmt + 4*lq + v][r2]
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-              const int c2 = 16 * hmt + 4 * lq + v, j1 = c2 / G::JW, j2loc = c2 - j1 * G::JW;
-              Hs[(p * 4 + j1) * G::HS + j2loc * R2 + 16 * hnt + lm] = hacc[v];
-            }
-            hacc = (f32x4){0.f, 0.f, 0.f, 0.f};
-          }
+        const int n = (total_items - 8 * b) < 8 ? (total_items - 8 * b) : 8;
+        // item 8*b + j does T3 on this wavefront when (8*b + j) % T3_SPLIT == hmt; 8 % T3_SPLIT == 0
+        Info ia, ib;
+        Ops oa, ob;
+        load_ops(0, (0 % T3_SPLIT) == hmt, ia, oa);
+        int j = 0;
+        while (true) {  // written out twice so that both operand sets stay in registers
+          if (j + 1 < n) load_ops(j + 1, ((j + 1) % T3_SPLIT) == hmt, ib, ob);
+          compute((j % T3_SPLIT) == hmt, ia, oa);
+          if (++j >= n) break;
+          if (j + 1 < n) load_ops(j + 1, ((j + 1) % T3_SPLIT) == hmt, ia, oa);
+          compute((j % T3_SPLIT) == hmt, ib, ob);
+          if (++j >= n) break;
         }
       }
     }
     TT_TICK(2)
     __syncthreads();
     TT_TICK(3)
+    // first row batch of the NEXT chunk: requested now, landed after the next F1, so that the T1 /
+    // dG2 / F1 MFMAs in between cover its latency
+    if (more && !refill) issue_batch(0, par ^ 1, mo + TT_MP);
 
     // ---- T1 (K = this wave's 64 columns) and dG2 (N = this wave's 64 columns) -----------------
     {
@@ -350,6 +418,8 @@ k_bwd_mfma(TTShape sh, const float *__restrict__ g1, const float *__restrict__ g
     }
     __syncthreads();
     TT_TICK(4)
+    if (more) zero_unused_h(cnt_next);  // Hs is free again; only the last chunk of an i2 is partial
+    TT_TICK(5)
     // fold the four K-partials of T1 in wave order and store one contribution per prefix
     for (int e = threadIdx.x; e < 32 * R1; e += TT_BLOCK) {
       const int row = e / R1, p = row >> 2;
@@ -358,19 +428,23 @@ k_bwd_mfma(TTShape sh, const float *__restrict__ g1, const float *__restrict__ g
         t1buf[((size_t)s_q[mo + p] * G::NSTRIP + strip) * G::S1 + (row & 3) * R1 + (e - row * R1)] = sum;
       }
     }
-    if (cs + TT_MP < seg1 && mo + TT_MP == TT_META) {  // uniform: refill the staged plan entries
+    if (more && refill) {  // uniform: the staged plan entries are used up, fetch the next 64
       __syncthreads();
       fetch_meta(cs + TT_MP);
       __syncthreads();
       fetch_chunk(0);
+      stage_chunk(par ^ 1, 0, cnt_next);
+      __syncthreads();
+      issue_batch(0, par ^ 1, 0);
     }
+    par ^= 1;
   }
 
 #ifdef TT_DBG_TIMING
   if (lane == 0) {
     TT_TICK(5)
-    for (int k = 0; k < 6; ++k) dbg[(blockIdx.x * 4 + wave) * 8 + k] = (float)tph[k];
-    dbg[(blockIdx.x * 4 + wave) * 8 + 6] = (float)(seg1 - seg0);
+    for (int k = 0; k < 8; ++k) dbg[(blockIdx.x * 4 + wave) * 10 + k] = (float)tph[k];
+    dbg[(blockIdx.x * 4 + wave) * 10 + 8] = (float)(seg1 - seg0);
   }
 #endif
   // dG2[r1 = 16*mt + 4*lq + v][i2][c = 64*wave + 16*nt + lm], complete for this i2 and strip
