@@ -53,7 +53,8 @@ typedef enum {
   TT_ERR_SHAPE = -2,       /* table shape violates the conventions or limits above       */
   TT_ERR_WORKSPACE = -3,   /* workspace too small or misaligned (needs 256-byte align)   */
   TT_ERR_INDEX_RANGE = -4, /* reported by tt_plan_status: bad index or bad offsets seen  */
-  TT_ERR_HIP = -5          /* a HIP runtime call or kernel launch failed                 */
+  TT_ERR_HIP = -5,         /* a HIP runtime call or kernel launch failed                 */
+  TT_ERR_UNAVAILABLE = -6  /* the entry point is switched off in this build              */
 } tt_status;
 
 /* One TT table.  HOST struct, caller-owned, read during the call only. */
@@ -187,6 +188,48 @@ tt_status tt_emb_bag_backward(const tt_table *table, const tt_plan *plan, const 
  */
 tt_status tt_core_sgd_update(const tt_table *table, const tt_plan *plan,
                              const float *const dcore[3], float lr, void *stream);
+
+/*
+ * Batched calls: the same four operations for several tables with ONE launch per kernel, so that
+ * small tables share the chip with large ones and the host enqueues dozens, not thousands, of
+ * launches per step.  All tables of a call must share d[] and r[] (n[] may differ) and must all
+ * have a plan or all lack one.  Each item names one table's arguments exactly as in the
+ * single-table calls; fields a call does not use are ignored.
+ *   items  HOST array of num_tables items (1..256); for reorder, items[t].plan is filled.
+ *   desc   DEVICE scratch of at least tt_batch_desc_bytes(num_tables) bytes, 16-byte aligned,
+ *          into which the call writes the kernels' per-table descriptors (small launches on
+ *          `stream` that carry them as arguments, so the write is ordered like any kernel).  It
+ *          is borrowed until the enqueued work has finished: consecutive calls on ONE stream may
+ *          share a buffer, calls that may overlap on different streams need different buffers.
+ * Results are bitwise identical to the single-table calls.
+ * STATUS: switched off.  Every batched call currently returns TT_ERR_UNAVAILABLE without
+ * touching the device: the first GPU run of the batched path ended in a memory fault whose cause
+ * has not been found yet, so the path stays disabled until it is.  The single-table calls are
+ * unaffected (they share the kernels but pass one descriptor by value).
+ */
+typedef struct {
+  const tt_table *table;   /* HOST                                                         */
+  tt_plan *plan;           /* HOST; out for reorder, in otherwise (NULL = naive arm)       */
+  const int64_t *indices;  /* DEVICE int64[nnz]                                            */
+  const int64_t *offsets;  /* DEVICE int64[num_bags+1]                                     */
+  int64_t nnz, num_bags;
+  const int64_t *remap;    /* DEVICE or NULL (reorder)                                     */
+  void *workspace;         /* DEVICE (reorder)                                             */
+  size_t workspace_bytes;
+  float *out;              /* DEVICE float[num_bags][D] (forward)                          */
+  const float *grad_out;   /* DEVICE float[num_bags][D] (backward)                         */
+  float *dcore[3];         /* DEVICE core-shaped (backward: written; update: read)         */
+} tt_batch_item;
+
+size_t tt_batch_desc_bytes(int num_tables);
+tt_status tt_index_reorder_batched(int num_tables, tt_batch_item *items, void *desc,
+                                   size_t desc_bytes, void *stream);
+tt_status tt_emb_bag_forward_batched(int num_tables, tt_batch_item *items, void *desc,
+                                     size_t desc_bytes, void *stream);
+tt_status tt_emb_bag_backward_batched(int num_tables, tt_batch_item *items, void *desc,
+                                      size_t desc_bytes, void *stream);
+tt_status tt_core_sgd_update_batched(int num_tables, tt_batch_item *items, float lr, void *desc,
+                                     size_t desc_bytes, void *stream);
 
 /*
  * Waits for `stream`, copies the plan's device-side counters to the host and

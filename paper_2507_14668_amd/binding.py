@@ -22,10 +22,12 @@ TT_ERR_SHAPE = -2
 TT_ERR_WORKSPACE = -3
 TT_ERR_INDEX_RANGE = -4
 TT_ERR_HIP = -5
+TT_ERR_UNAVAILABLE = -6
 
 EXPORTS = ("tt_workspace_bytes", "tt_index_reorder", "tt_emb_bag_forward", "tt_emb_bag_backward",
            "tt_core_sgd_update", "tt_plan_status", "tt_strerror", "tt_prof_create", "tt_prof_destroy",
-           "tt_prof_collect", "tt_kernel_name")
+           "tt_prof_collect", "tt_kernel_name", "tt_batch_desc_bytes", "tt_index_reorder_batched",
+           "tt_emb_bag_forward_batched", "tt_emb_bag_backward_batched", "tt_core_sgd_update_batched")
 KERNELS = {"fwd_contract": 0, "bag_sum": 1, "grad_merge": 2, "bwd_contract": 3, "sort_scatter": 4, "sgd": 5}
 
 
@@ -55,6 +57,14 @@ class CPlan(ctypes.Structure):
                 + [(name, ctypes.c_void_p) for name in _PLAN_FLOAT_ARRAYS]
                 + [("sort_tmp", ctypes.c_void_p), ("prof", ctypes.c_void_p), ("workspace", ctypes.c_void_p),
                    ("workspace_bytes", ctypes.c_size_t)])
+
+
+class CBatchItem(ctypes.Structure):
+    _fields_ = [("table", ctypes.c_void_p), ("plan", ctypes.c_void_p), ("indices", ctypes.c_void_p),
+                ("offsets", ctypes.c_void_p), ("nnz", ctypes.c_int64), ("num_bags", ctypes.c_int64),
+                ("remap", ctypes.c_void_p), ("workspace", ctypes.c_void_p),
+                ("workspace_bytes", ctypes.c_size_t), ("out", ctypes.c_void_p),
+                ("grad_out", ctypes.c_void_p), ("dcore", ctypes.c_void_p * 3)]
 
 
 _lib = None
@@ -91,6 +101,14 @@ def load_library():
         lib.tt_kernel_name.argtypes = [ctypes.c_int]
         lib.tt_strerror.restype = ctypes.c_char_p
         lib.tt_strerror.argtypes = [ctypes.c_int]
+        lib.tt_batch_desc_bytes.restype = ctypes.c_size_t
+        lib.tt_batch_desc_bytes.argtypes = [ctypes.c_int]
+        for name in ("tt_index_reorder_batched", "tt_emb_bag_forward_batched", "tt_emb_bag_backward_batched"):
+            f = getattr(lib, name)
+            f.restype = ctypes.c_int
+            f.argtypes = [ctypes.c_int, vp, vp, ctypes.c_size_t, vp]
+        lib.tt_core_sgd_update_batched.restype = ctypes.c_int
+        lib.tt_core_sgd_update_batched.argtypes = [ctypes.c_int, vp, f32, vp, ctypes.c_size_t, vp]
         _lib = lib
     return _lib
 
@@ -275,3 +293,72 @@ def tt_core_sgd_update(table: Table, plan, dcores, lr: float, stream=None):
 def tt_plan_status(plan: Plan, stream=None) -> int:
     _, st = plan.counts(stream)
     return st
+
+
+# ------------------------------------------------------------------ batched calls
+def alloc_batch_desc(num_tables: int, device="cuda"):
+    """Device scratch for the per-table kernel descriptors of ONE batched call in flight."""
+    nbytes = int(load_library().tt_batch_desc_bytes(int(num_tables)))
+    if nbytes == 0:
+        raise TTError(TT_ERR_INVALID_ARG, "tt_batch_desc_bytes")
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def _items(tables, plans=None, indices=None, offsets=None, remaps=None, workspaces=None, outs=None,
+           grads=None, dcores=None):
+    n = len(tables)
+    arr = (CBatchItem * n)()
+    for t in range(n):
+        it = arr[t]
+        it.table = ctypes.addressof(tables[t].c)
+        if plans is not None and plans[t] is not None:
+            it.plan = ctypes.addressof(plans[t].c)
+        if indices is not None:
+            it.indices = _dev_i64(indices[t], "indices").data_ptr()
+            it.nnz = indices[t].numel()
+        if offsets is not None:
+            it.offsets = _dev_i64(offsets[t], "offsets").data_ptr()
+            it.num_bags = offsets[t].numel() - 1
+        if remaps is not None and remaps[t] is not None:
+            it.remap = _dev_i64(remaps[t], "remap").data_ptr()
+        if workspaces is not None:
+            it.workspace = workspaces[t].data_ptr()
+            it.workspace_bytes = workspaces[t].numel()
+        if outs is not None:
+            it.out = _dev_f32(outs[t], "out").data_ptr()
+        if grads is not None:
+            it.grad_out = _dev_f32(grads[t], "grad_out").data_ptr()
+        if dcores is not None:
+            for k in range(3):
+                it.dcore[k] = _dev_f32(dcores[t][k], "dcore").data_ptr()
+    return arr
+
+
+def tt_index_reorder_batched(tables, indices, offsets, workspaces, desc, remaps=None, stream=None):
+    """One reorder plan per table, built with one launch per kernel for the whole batch."""
+    plans = [Plan(ws) for ws in workspaces]
+    arr = _items(tables, plans, indices, offsets, remaps, workspaces)
+    st = load_library().tt_index_reorder_batched(len(tables), arr, _ptr(desc), desc.numel(), _stream(stream))
+    _check(st, "tt_index_reorder_batched")
+    return plans
+
+
+def tt_emb_bag_forward_batched(tables, plans, indices, offsets, outs, desc, stream=None):
+    arr = _items(tables, plans, indices, offsets, outs=outs)
+    st = load_library().tt_emb_bag_forward_batched(len(tables), arr, _ptr(desc), desc.numel(), _stream(stream))
+    _check(st, "tt_emb_bag_forward_batched")
+    return outs
+
+
+def tt_emb_bag_backward_batched(tables, plans, indices, offsets, grads, dcores, desc, stream=None):
+    arr = _items(tables, plans, indices, offsets, grads=grads, dcores=dcores)
+    st = load_library().tt_emb_bag_backward_batched(len(tables), arr, _ptr(desc), desc.numel(), _stream(stream))
+    _check(st, "tt_emb_bag_backward_batched")
+    return dcores
+
+
+def tt_core_sgd_update_batched(tables, plans, dcores, lr, desc, stream=None):
+    arr = _items(tables, plans, dcores=dcores)
+    st = load_library().tt_core_sgd_update_batched(len(tables), arr, ctypes.c_float(lr), _ptr(desc),
+                                                   desc.numel(), _stream(stream))
+    _check(st, "tt_core_sgd_update_batched")

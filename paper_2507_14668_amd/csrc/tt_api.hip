@@ -111,6 +111,141 @@ bool batch_ok(int64_t nnz, int64_t num_bags) {
   return true;
 }
 
+// One table's kernel descriptor.  `plan` may be NULL (naive arms).
+void fill_dev(TTDev *d, const TTShape &sh, const tt_table *t, const tt_plan *plan,
+              const int64_t *indices, const int64_t *offsets, int64_t nnz, int64_t num_bags,
+              const int64_t *remap, float *out, const float *grad_out, float *const dcore[3],
+              float lr) {
+  memset(d, 0, sizeof(*d));
+  d->sh = sh;
+  for (int k = 0; k < 3; ++k) {
+    d->g[k] = t->core[k];
+    d->dg[k] = dcore ? dcore[k] : nullptr;
+  }
+  if (plan) {
+    d->plan = *plan;
+    d->tmp = tt_sort_tmp_view(plan);
+  }
+  d->indices = indices; d->offsets = offsets; d->remap = remap;
+  d->grad_out = grad_out; d->out = out;
+  d->nnz = (int)nnz; d->num_bags = (int)num_bags;
+  d->sort_tiles = tt_ceil_div(nnz, TT_SORT_TILE);
+  d->strips = ttk_mfma_strips(sh);
+  d->lr = lr;
+}
+
+enum BatchOp { OP_REORDER, OP_FORWARD, OP_BACKWARD, OP_SGD };
+
+// Validates one item of a call and fills its descriptor (and, for reorder, its plan).
+tt_status prepare_item(BatchOp op, const tt_batch_item *it, float lr, TTDev *d) {
+  if (!it->table) return TT_ERR_INVALID_ARG;
+  TTShape sh;
+  if (!derive_shape(it->table, &sh)) return TT_ERR_SHAPE;
+  const int64_t nnz = op == OP_SGD && it->plan ? it->plan->nnz : it->nnz;
+  const int64_t num_bags = op == OP_SGD && it->plan ? it->plan->num_bags : it->num_bags;
+  if (op != OP_SGD && !batch_ok(nnz, num_bags)) return TT_ERR_INVALID_ARG;
+  if (op == OP_REORDER) {
+    if (!it->plan || !it->workspace || !it->offsets || (nnz > 0 && !it->indices))
+      return TT_ERR_INVALID_ARG;
+    if (((uintptr_t)it->workspace & 255) != 0) return TT_ERR_WORKSPACE;
+    if (it->workspace_bytes < layout(sh, nnz, num_bags, nullptr, nullptr)) return TT_ERR_WORKSPACE;
+    layout(sh, nnz, num_bags, (char *)it->workspace, it->plan);
+    for (int k = 0; k < 3; ++k) { it->plan->n[k] = it->table->n[k]; it->plan->d[k] = it->table->d[k]; }
+    for (int k = 0; k < 4; ++k) it->plan->r[k] = it->table->r[k];
+    it->plan->workspace = it->workspace;
+    it->plan->workspace_bytes = it->workspace_bytes;
+  } else {
+    if (!cores_present(it->table)) return TT_ERR_INVALID_ARG;
+    if (it->plan && !plan_matches(it->plan, it->table, nnz, num_bags)) return TT_ERR_INVALID_ARG;
+    if (op == OP_FORWARD) {
+      if (!it->offsets || (num_bags > 0 && !it->out)) return TT_ERR_INVALID_ARG;
+      if (!it->plan && nnz > 0 && !it->indices) return TT_ERR_INVALID_ARG;
+    } else if (op == OP_BACKWARD) {
+      if (!it->offsets || !it->dcore[0] || !it->dcore[1] || !it->dcore[2]) return TT_ERR_INVALID_ARG;
+      if (num_bags > 0 && !it->grad_out) return TT_ERR_INVALID_ARG;
+      if (!it->plan && nnz > 0 && !it->indices) return TT_ERR_INVALID_ARG;
+    } else {
+      if (!it->dcore[0] || !it->dcore[1] || !it->dcore[2]) return TT_ERR_INVALID_ARG;
+    }
+  }
+  fill_dev(d, sh, it->table, it->plan, it->indices, it->offsets, nnz, num_bags, it->remap, it->out,
+           it->grad_out, it->dcore, lr);
+  return TT_OK;
+}
+
+tt_status dispatch(BatchOp op, const TTBatch &b, bool planned, hipStream_t s) {
+  switch (op) {
+    case OP_REORDER: return ttk_reorder(b, s);
+    case OP_FORWARD: return planned ? ttk_forward_plan(b, s) : ttk_forward_naive(b, s);
+    case OP_BACKWARD: return planned ? ttk_backward_plan(b, s) : ttk_backward_naive(b, s);
+    case OP_SGD: return ttk_sgd(b, planned, s);
+  }
+  return TT_ERR_INVALID_ARG;
+}
+
+#define TT_MAX_BATCH 256
+#define TT_DESC_PER_LAUNCH 6  // descriptors carried by value in one upload launch (< 4 KB of arguments)
+
+// The descriptors travel as kernel arguments, which the runtime captures at launch time: the
+// upload is ordered on the stream like any kernel and does not depend on how the runtime treats
+// asynchronous copies from pageable host memory (staging, ordering, lifetime of the source).
+struct DescChunk { TTDev d[TT_DESC_PER_LAUNCH]; };
+__global__ void k_write_desc(TTDev *__restrict__ dst, DescChunk chunk, int count) {
+  const int words = (int)(sizeof(TTDev) / sizeof(int));
+  const int *src = reinterpret_cast<const int *>(&chunk);
+  int *out = reinterpret_cast<int *>(dst);
+  for (int e = threadIdx.x; e < count * words; e += blockDim.x) out[e] = src[e];
+}
+static_assert(sizeof(TTDev) % sizeof(int) == 0 && sizeof(DescChunk) <= 3800, "descriptor upload");
+
+// Switched off: the first GPU run of a batched call ended in a memory fault whose cause has not
+// been established.  Until it is, batched calls report TT_ERR_UNAVAILABLE and launch nothing.
+constexpr bool kBatchedCallsEnabled = false;
+
+tt_status run_batched(BatchOp op, int T, tt_batch_item *items, float lr, void *desc,
+                      size_t desc_bytes, hipStream_t s) {
+  if (!kBatchedCallsEnabled) return TT_ERR_UNAVAILABLE;
+  if (T < 1 || T > TT_MAX_BATCH || !items || !desc) return TT_ERR_INVALID_ARG;
+  if (desc_bytes < (size_t)T * sizeof(TTDev) || ((uintptr_t)desc & 15) != 0) return TT_ERR_WORKSPACE;
+  TTDev *host = (TTDev *)malloc((size_t)T * sizeof(TTDev));
+  if (!host) return TT_ERR_INVALID_ARG;
+  tt_status st = TT_OK;
+  const bool planned = items[0].plan != nullptr;
+  for (int t = 0; t < T && st == TT_OK; ++t) {
+    st = prepare_item(op, &items[t], lr, &host[t]);
+    if (st != TT_OK) break;
+    // one launch serves the whole batch: same column factors, ranks and arm for every table
+    const tt_table *a = items[0].table, *c = items[t].table;
+    for (int k = 0; k < 3; ++k)
+      if (a->d[k] != c->d[k]) st = TT_ERR_SHAPE;
+    if (a->r[1] != c->r[1] || a->r[2] != c->r[2]) st = TT_ERR_SHAPE;
+    if ((items[t].plan != nullptr) != planned) st = TT_ERR_INVALID_ARG;
+  }
+  if (st == TT_OK) {
+    for (int base = 0; base < T; base += TT_DESC_PER_LAUNCH) {
+      DescChunk chunk;
+      const int count = (T - base) < TT_DESC_PER_LAUNCH ? (T - base) : TT_DESC_PER_LAUNCH;
+      memcpy(chunk.d, host + base, (size_t)count * sizeof(TTDev));
+      hipLaunchKernelGGL(k_write_desc, dim3(1), dim3(TT_BLOCK), 0, s, (TTDev *)desc + base, chunk, count);
+    }
+    st = tt_launch_status();
+  }
+  if (st == TT_OK) {
+    const TTBatch b = {T, host, (const TTDev *)desc};
+    st = dispatch(op, b, planned, s);
+  }
+  free(host);
+  return st;
+}
+
+tt_status run_single(BatchOp op, tt_batch_item *item, float lr, hipStream_t s) {
+  TTDev d;
+  tt_status st = prepare_item(op, item, lr, &d);
+  if (st != TT_OK) return st;
+  const TTBatch b = {1, &d, nullptr};
+  return dispatch(op, b, item->plan != nullptr, s);
+}
+
 }  // namespace
 
 extern "C" {
@@ -124,63 +259,69 @@ size_t tt_workspace_bytes(const tt_table *table, int64_t nnz, int64_t num_bags) 
 tt_status tt_index_reorder(const tt_table *table, const int64_t *indices, const int64_t *offsets,
                            int64_t nnz, int64_t num_bags, const int64_t *remap, void *workspace,
                            size_t workspace_bytes, tt_plan *plan_out, void *stream) {
-  if (!table || !plan_out || !workspace || !offsets || (nnz > 0 && !indices))
-    return TT_ERR_INVALID_ARG;
-  if (!batch_ok(nnz, num_bags)) return TT_ERR_INVALID_ARG;
-  TTShape sh;
-  if (!derive_shape(table, &sh)) return TT_ERR_SHAPE;
-  if (((uintptr_t)workspace & 255) != 0) return TT_ERR_WORKSPACE;
-  if (workspace_bytes < layout(sh, nnz, num_bags, nullptr, nullptr)) return TT_ERR_WORKSPACE;
-  layout(sh, nnz, num_bags, (char *)workspace, plan_out);
-  for (int k = 0; k < 3; ++k) { plan_out->n[k] = table->n[k]; plan_out->d[k] = table->d[k]; }
-  for (int k = 0; k < 4; ++k) plan_out->r[k] = table->r[k];
-  plan_out->workspace = workspace;
-  plan_out->workspace_bytes = workspace_bytes;
-  return ttk_reorder(sh, indices, offsets, nnz, num_bags, remap, plan_out, (hipStream_t)stream);
+  if (!table || !plan_out || !workspace || !offsets) return TT_ERR_INVALID_ARG;
+  tt_batch_item it;
+  memset(&it, 0, sizeof(it));
+  it.table = table; it.plan = plan_out; it.indices = indices; it.offsets = offsets;
+  it.nnz = nnz; it.num_bags = num_bags; it.remap = remap;
+  it.workspace = workspace; it.workspace_bytes = workspace_bytes;
+  return run_single(OP_REORDER, &it, 0.f, (hipStream_t)stream);
 }
 
 tt_status tt_emb_bag_forward(const tt_table *table, const tt_plan *plan, const int64_t *indices,
                              const int64_t *offsets, int64_t nnz, int64_t num_bags, float *out,
                              void *stream) {
-  if (!table || !offsets || (num_bags > 0 && !out)) return TT_ERR_INVALID_ARG;
-  if (!batch_ok(nnz, num_bags)) return TT_ERR_INVALID_ARG;
-  TTShape sh;
-  if (!derive_shape(table, &sh)) return TT_ERR_SHAPE;
-  if (!cores_present(table)) return TT_ERR_INVALID_ARG;
-  if (plan) {
-    if (!plan_matches(plan, table, nnz, num_bags)) return TT_ERR_INVALID_ARG;
-    return ttk_forward_plan(sh, table, plan, offsets, num_bags, out, (hipStream_t)stream);
-  }
-  if (nnz > 0 && !indices) return TT_ERR_INVALID_ARG;
-  return ttk_forward_naive(sh, table, indices, offsets, nnz, num_bags, out, (hipStream_t)stream);
+  tt_batch_item it;
+  memset(&it, 0, sizeof(it));
+  it.table = table; it.plan = const_cast<tt_plan *>(plan); it.indices = indices; it.offsets = offsets;
+  it.nnz = nnz; it.num_bags = num_bags; it.out = out;
+  return run_single(OP_FORWARD, &it, 0.f, (hipStream_t)stream);
 }
 
 tt_status tt_emb_bag_backward(const tt_table *table, const tt_plan *plan, const int64_t *indices,
                               const int64_t *offsets, int64_t nnz, int64_t num_bags,
                               const float *grad_out, float *const dcore[3], void *stream) {
-  if (!table || !offsets || !dcore || !dcore[0] || !dcore[1] || !dcore[2])
-    return TT_ERR_INVALID_ARG;
-  if (!batch_ok(nnz, num_bags) || (num_bags > 0 && !grad_out)) return TT_ERR_INVALID_ARG;
-  TTShape sh;
-  if (!derive_shape(table, &sh)) return TT_ERR_SHAPE;
-  if (!cores_present(table)) return TT_ERR_INVALID_ARG;
-  if (plan) {
-    if (!plan_matches(plan, table, nnz, num_bags)) return TT_ERR_INVALID_ARG;
-    return ttk_backward_plan(sh, table, plan, grad_out, dcore, (hipStream_t)stream);
-  }
-  if (nnz > 0 && !indices) return TT_ERR_INVALID_ARG;
-  return ttk_backward_naive(sh, table, indices, offsets, nnz, num_bags, grad_out, dcore,
-                            (hipStream_t)stream);
+  if (!dcore) return TT_ERR_INVALID_ARG;
+  tt_batch_item it;
+  memset(&it, 0, sizeof(it));
+  it.table = table; it.plan = const_cast<tt_plan *>(plan); it.indices = indices; it.offsets = offsets;
+  it.nnz = nnz; it.num_bags = num_bags; it.grad_out = grad_out;
+  for (int k = 0; k < 3; ++k) it.dcore[k] = dcore[k];
+  return run_single(OP_BACKWARD, &it, 0.f, (hipStream_t)stream);
 }
 
 tt_status tt_core_sgd_update(const tt_table *table, const tt_plan *plan,
                              const float *const dcore[3], float lr, void *stream) {
-  if (!table || !dcore || !dcore[0] || !dcore[1] || !dcore[2]) return TT_ERR_INVALID_ARG;
-  TTShape sh;
-  if (!derive_shape(table, &sh)) return TT_ERR_SHAPE;
-  if (!cores_present(table)) return TT_ERR_INVALID_ARG;
-  if (plan && !plan_matches(plan, table, plan->nnz, plan->num_bags)) return TT_ERR_INVALID_ARG;
-  return ttk_sgd(sh, table, plan, dcore, lr, (hipStream_t)stream);
+  if (!dcore) return TT_ERR_INVALID_ARG;
+  tt_batch_item it;
+  memset(&it, 0, sizeof(it));
+  it.table = table; it.plan = const_cast<tt_plan *>(plan);
+  for (int k = 0; k < 3; ++k) it.dcore[k] = const_cast<float *>(dcore[k]);
+  return run_single(OP_SGD, &it, lr, (hipStream_t)stream);
+}
+
+size_t tt_batch_desc_bytes(int num_tables) {
+  return num_tables < 1 || num_tables > TT_MAX_BATCH ? 0 : (size_t)num_tables * sizeof(TTDev);
+}
+
+tt_status tt_index_reorder_batched(int num_tables, tt_batch_item *items, void *desc,
+                                   size_t desc_bytes, void *stream) {
+  return run_batched(OP_REORDER, num_tables, items, 0.f, desc, desc_bytes, (hipStream_t)stream);
+}
+
+tt_status tt_emb_bag_forward_batched(int num_tables, tt_batch_item *items, void *desc,
+                                     size_t desc_bytes, void *stream) {
+  return run_batched(OP_FORWARD, num_tables, items, 0.f, desc, desc_bytes, (hipStream_t)stream);
+}
+
+tt_status tt_emb_bag_backward_batched(int num_tables, tt_batch_item *items, void *desc,
+                                      size_t desc_bytes, void *stream) {
+  return run_batched(OP_BACKWARD, num_tables, items, 0.f, desc, desc_bytes, (hipStream_t)stream);
+}
+
+tt_status tt_core_sgd_update_batched(int num_tables, tt_batch_item *items, float lr, void *desc,
+                                     size_t desc_bytes, void *stream) {
+  return run_batched(OP_SGD, num_tables, items, lr, desc, desc_bytes, (hipStream_t)stream);
 }
 
 tt_status tt_plan_status(const tt_plan *plan, void *stream, int64_t counts_out[4]) {
@@ -257,6 +398,7 @@ const char *tt_strerror(tt_status status) {
     case TT_ERR_WORKSPACE: return "workspace too small or not 256-byte aligned";
     case TT_ERR_INDEX_RANGE: return "an index was out of range or the bag offsets are not a valid CSR array";
     case TT_ERR_HIP: return "a HIP runtime call or kernel launch failed";
+    case TT_ERR_UNAVAILABLE: return "this entry point is switched off in this build";
   }
   return "unknown status";
 }

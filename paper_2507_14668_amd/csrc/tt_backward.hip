@@ -54,14 +54,52 @@ __device__ __forceinline__ size_t seg_out_index(int s, int e, int out_inner, int
   return ((size_t)hi * nseg + s) * out_inner + lo;
 }
 
-template <int VEC>
+// The three segmented sums of the backward pass, described per table on the device.
+enum { SEG_GAGG = 0, SEG_DG3 = 1, SEG_DG1 = 2 };
+struct SegView {
+  int W;                     // vector width
+  const int32_t *count_ptr;  // device: number of positions
+  const int32_t *seg_src;
+  int seg_div;
+  const int32_t *gidx;
+  const int32_t *seg_off;
+  const float *src;
+  int nsub;                  // vectors per position
+  float *out;
+  int out_inner;
+  int nseg;                  // number of segments (output layout / dense zero fill)
+  int dense;
+  float *partial;
+};
+__device__ __forceinline__ SegView seg_view(const TTDev &d, int kind) {
+  SegView v;
+  v.partial = d.plan.partial;
+  if (kind == SEG_GAGG) {  // merge grad_out over the occurrences of each distinct row
+    v.W = d.sh.D; v.count_ptr = d.plan.counts + 2; v.seg_src = d.plan.slot_of_sorted; v.seg_div = 1;
+    v.gidx = d.plan.bag_of_sorted; v.seg_off = d.plan.row_seg; v.src = d.grad_out; v.nsub = 1;
+    v.out = d.plan.gagg; v.out_inner = d.sh.D; v.nseg = (int)d.plan.max_rows; v.dense = 0;
+  } else if (kind == SEG_DG3) {  // core 2: per-row contributions of all rows sharing i3
+    v.W = d.sh.S3; v.count_ptr = d.plan.counts + 0; v.seg_src = d.plan.i3_of_sorted; v.seg_div = 1;
+    v.gidx = d.plan.rows_by_i3; v.seg_off = d.plan.i3_seg; v.src = d.plan.t3buf; v.nsub = d.strips;
+    v.out = d.dg[2]; v.out_inner = d.sh.d3; v.nseg = d.sh.n3; v.dense = 1;
+  } else {  // core 0: per-prefix contributions of all prefixes sharing i1 (contiguous)
+    v.W = d.sh.S1; v.count_ptr = d.plan.counts + 1; v.seg_src = d.plan.uniq_pref; v.seg_div = d.sh.n2;
+    v.gidx = nullptr; v.seg_off = d.plan.i1_seg; v.src = d.plan.t1buf; v.nsub = d.strips;
+    v.out = d.dg[0]; v.out_inner = d.sh.S1; v.nseg = d.sh.n1; v.dense = 1;
+  }
+  return v;
+}
+
+template <bool BATCHED, int VEC>
 __global__ void __launch_bounds__(TT_BLOCK)
-k_seg_stage1(int W, int lanes, const int32_t *__restrict__ count_ptr,
-             const int32_t *__restrict__ seg_src, int seg_div, const int32_t *__restrict__ gidx,
-             const int32_t *__restrict__ seg_off, const float *__restrict__ src, int nsub,
-             float *__restrict__ out, int out_inner, int nseg, float *__restrict__ partial,
-             int chunk) {
-  const int M = *count_ptr;
+k_seg_stage1(TTArg<BATCHED> arg, int kind, int lanes, int chunk) {
+  const SegView sv = seg_view(arg.get(), kind);
+  const int W = sv.W, seg_div = sv.seg_div, nsub = sv.nsub, out_inner = sv.out_inner, nseg = sv.nseg;
+  const int32_t *__restrict__ seg_src = sv.seg_src, *__restrict__ gidx = sv.gidx,
+                *__restrict__ seg_off = sv.seg_off;
+  const float *__restrict__ src = sv.src;
+  float *__restrict__ out = sv.out, *__restrict__ partial = sv.partial;
+  const int M = *sv.count_ptr;
   const int nchunks = (M + chunk - 1) / chunk;
   const int groups = blockDim.x / lanes, g = threadIdx.x / lanes, lane = threadIdx.x - g * lanes;
   for (int c = blockIdx.x * groups + g; c < nchunks; c += gridDim.x * groups) {
@@ -126,14 +164,16 @@ k_seg_stage1(int W, int lanes, const int32_t *__restrict__ count_ptr,
 // its own slot-1 partial and the slot-0 partials of the following chunks, in chunk order.
 // With `dense`, workgroup c also zero-fills segment c if it is empty.
 // LDS: red[groups][W]
-template <int VEC>
+template <bool BATCHED, int VEC>
 __global__ void __launch_bounds__(TT_BLOCK)
-k_seg_stage2(int W, int lanes, const int32_t *__restrict__ count_ptr,
-             const int32_t *__restrict__ seg_src, int seg_div,
-             const int32_t *__restrict__ seg_off, float *__restrict__ out, int out_inner,
-             int nseg, const float *__restrict__ partial, int dense, int chunk) {
+k_seg_stage2(TTArg<BATCHED> arg, int kind, int lanes, int chunk) {
+  const SegView sv = seg_view(arg.get(), kind);
+  const int W = sv.W, seg_div = sv.seg_div, out_inner = sv.out_inner, nseg = sv.nseg, dense = sv.dense;
+  const int32_t *__restrict__ seg_src = sv.seg_src, *__restrict__ seg_off = sv.seg_off;
+  float *__restrict__ out = sv.out;
+  const float *__restrict__ partial = sv.partial;
   extern __shared__ float red[];
-  const int M = *count_ptr;
+  const int M = *sv.count_ptr;
   const int nchunks = (M + chunk - 1) / chunk;
   const int c = blockIdx.x;
   const int groups = blockDim.x / lanes, g = threadIdx.x / lanes, lane = threadIdx.x - g * lanes;
@@ -183,59 +223,41 @@ k_seg_stage2(int W, int lanes, const int32_t *__restrict__ count_ptr,
   }
 }
 
-struct SegArgs {
-  int W;
-  const int32_t *count_ptr;  // device: number of positions
-  int64_t max_count;         // host upper bound of *count_ptr
-  const int32_t *seg_src;
-  int seg_div;
-  const int32_t *gidx;
-  const int32_t *seg_off;
-  const float *src;
-  int nsub;  // vectors per position
-  float *out;
-  int out_inner;
-  int nseg;   // number of segments for the output layout / dense zero fill
-  int dense;
-  float *partial;
-  int chunk;            // positions per stage-1 chunk (>= TT_SEG_MIN_CHUNK)
-  const tt_plan *plan;  // for the optional timing scope
-  int prof_kernel;      // kernel id of stage 1, or -1
-};
-
-tt_status seg_sum(const SegArgs &a, hipStream_t s) {
-  const bool vec4 = (a.W % 4) == 0 && (a.out_inner % 4) == 0 && ((uintptr_t)a.src % 16) == 0 &&
-                    ((uintptr_t)a.out % 16) == 0;
+// Host side of one segmented sum over every table of the batch.
+tt_status seg_sum(const TTBatch &b, int kind, int chunk, int prof_kernel, hipStream_t s) {
+  const TTShape &sh = b.host[0].sh;
+  const int W = kind == SEG_GAGG ? sh.D : (kind == SEG_DG3 ? sh.S3 : sh.S1);
+  const int out_inner = kind == SEG_DG3 ? sh.d3 : W;
+  bool vec4 = (W % 4) == 0 && (out_inner % 4) == 0;
+  long long max_count = 0, max_seg = 0;
+  for (int t = 0; t < b.T; ++t) {
+    const TTDev &d = b.host[t];
+    const float *src = kind == SEG_GAGG ? d.grad_out : (kind == SEG_DG3 ? d.plan.t3buf : d.plan.t1buf);
+    const float *out = kind == SEG_GAGG ? d.plan.gagg : (kind == SEG_DG3 ? d.dg[2] : d.dg[0]);
+    vec4 = vec4 && ((uintptr_t)src % 16) == 0 && ((uintptr_t)out % 16) == 0;
+    const long long cnt = kind == SEG_GAGG ? d.nnz : (kind == SEG_DG3 ? d.plan.max_rows : d.plan.max_prefixes);
+    const long long nseg = kind == SEG_GAGG ? 0 : (kind == SEG_DG3 ? d.sh.n3 : d.sh.n1);
+    if (cnt > max_count) max_count = cnt;
+    if (nseg > max_seg) max_seg = nseg;
+  }
   const int vec = vec4 ? 4 : 1;
   int lanes = 1;
-  while (lanes < TT_WAVE && lanes * vec < a.W) lanes <<= 1;
+  while (lanes < TT_WAVE && lanes * vec < W) lanes <<= 1;
   const int groups = TT_BLOCK / lanes;
-  const int nchunks = tt_ceil_div(a.max_count, a.chunk);
+  const int nchunks = tt_ceil_div(max_count, chunk);
   if (nchunks > 0) {
     int blocks = tt_ceil_div(nchunks, groups);
     if (blocks > 8192) blocks = 8192;
-    TTProfScope prof(a.plan, a.prof_kernel, s);
-    if (vec4)
-      hipLaunchKernelGGL(k_seg_stage1<4>, dim3(blocks), dim3(TT_BLOCK), 0, s, a.W, lanes,
-                         a.count_ptr, a.seg_src, a.seg_div, a.gidx, a.seg_off, a.src, a.nsub, a.out,
-                         a.out_inner, a.nseg, a.partial, a.chunk);
-    else
-      hipLaunchKernelGGL(k_seg_stage1<1>, dim3(blocks), dim3(TT_BLOCK), 0, s, a.W, lanes,
-                         a.count_ptr, a.seg_src, a.seg_div, a.gidx, a.seg_off, a.src, a.nsub, a.out,
-                         a.out_inner, a.nseg, a.partial, a.chunk);
+    TTProfScope prof(&b.host[0].plan, prof_kernel, s);
+    if (vec4) TT_LAUNCH_T(k_seg_stage1, 4, blocks, TT_BLOCK, 0, s, b, kind, lanes, chunk);
+    else TT_LAUNCH_T(k_seg_stage1, 1, blocks, TT_BLOCK, 0, s, b, kind, lanes, chunk);
   }
-  int blocks2 = nchunks;
-  if (a.dense && a.nseg > blocks2) blocks2 = a.nseg;
+  long long blocks2 = nchunks;
+  if (max_seg > blocks2) blocks2 = max_seg;  // dense kinds also zero-fill empty segments
   if (blocks2 > 0) {
-    const size_t lds = sizeof(float) * (size_t)groups * a.W;
-    if (vec4)
-      hipLaunchKernelGGL(k_seg_stage2<4>, dim3(blocks2), dim3(TT_BLOCK), lds, s, a.W, lanes,
-                         a.count_ptr, a.seg_src, a.seg_div, a.seg_off, a.out, a.out_inner, a.nseg,
-                         a.partial, a.dense, a.chunk);
-    else
-      hipLaunchKernelGGL(k_seg_stage2<1>, dim3(blocks2), dim3(TT_BLOCK), lds, s, a.W, lanes,
-                         a.count_ptr, a.seg_src, a.seg_div, a.seg_off, a.out, a.out_inner, a.nseg,
-                         a.partial, a.dense, a.chunk);
+    const size_t lds = sizeof(float) * (size_t)groups * W;
+    if (vec4) TT_LAUNCH_T(k_seg_stage2, 4, blocks2, TT_BLOCK, lds, s, b, kind, lanes, chunk);
+    else TT_LAUNCH_T(k_seg_stage2, 1, blocks2, TT_BLOCK, lds, s, b, kind, lanes, chunk);
   }
   return tt_launch_status();
 }
@@ -243,12 +265,17 @@ tt_status seg_sum(const SegArgs &a, hipStream_t s) {
 // ------------------------------------------------------------------ per-prefix contractions
 // Workgroup per distinct prefix q.
 // LDS (floats): g1s[S1] | p12[d1*d2*R2p] | hs[P] | gs[D] | g3s[S3]
+template <bool BATCHED>
 __global__ void __launch_bounds__(TT_BLOCK)
-k_bwd_prefix(TTShape sh, const float *__restrict__ g1, const float *__restrict__ g2,
-             const float *__restrict__ g3, const int32_t *__restrict__ counts,
-             const int32_t *__restrict__ uniq_pref, const int32_t *__restrict__ pref_seg,
-             const int32_t *__restrict__ uniq_row, const float *__restrict__ gagg,
-             float *__restrict__ t3buf, float *__restrict__ hbuf, float *__restrict__ t1buf) {
+k_bwd_prefix(TTArg<BATCHED> a) {
+  const TTDev &d = a.get();
+  const TTShape &sh = d.sh;
+  const float *__restrict__ g1 = d.g[0], *__restrict__ g2 = d.g[1], *__restrict__ g3 = d.g[2];
+  const int32_t *__restrict__ counts = d.plan.counts, *__restrict__ uniq_pref = d.plan.uniq_pref,
+                *__restrict__ pref_seg = d.plan.pref_seg, *__restrict__ uniq_row = d.plan.uniq_row;
+  const float *__restrict__ gagg = d.plan.gagg;
+  float *__restrict__ t3buf = d.plan.t3buf, *__restrict__ hbuf = d.plan.hbuf,
+        *__restrict__ t1buf = d.plan.t1buf;
   extern __shared__ float lds[];
   float *g1s = lds, *p12 = g1s + sh.S1, *hs = p12 + sh.d1 * sh.d2 * sh.R2p, *gs = hs + sh.P,
         *g3s = gs + sh.D;
@@ -315,11 +342,21 @@ k_bwd_prefix(TTShape sh, const float *__restrict__ g1, const float *__restrict__
 // sum_j1 G1[i1][j1][r1] H[(i1,i2)][j1][j2][r2].  Workgroup (i2, column tile, r1 tile); thread
 // owns one (j2,r2) column and RT values of r1; prefixes are visited in increasing i1.
 #define TT_DG2_RT 8
+template <bool BATCHED>
 __global__ void __launch_bounds__(TT_BLOCK)
-k_bwd_dg2(TTShape sh, const float *__restrict__ g1, const int32_t *__restrict__ uniq_pref,
-          const int32_t *__restrict__ prefs_by_i2, const int32_t *__restrict__ i2_seg,
-          const float *__restrict__ hbuf, float *__restrict__ dg2) {
-  const int i2 = blockIdx.x, c = blockIdx.y * TT_BLOCK + threadIdx.x, r1b = blockIdx.z * TT_DG2_RT;
+k_bwd_dg2(TTArg<BATCHED> a, int col_tiles) {
+  const TTDev &d = a.get();
+  const TTShape &sh = d.sh;
+  const float *__restrict__ g1 = d.g[0], *__restrict__ hbuf = d.plan.hbuf;
+  const int32_t *__restrict__ uniq_pref = d.plan.uniq_pref, *__restrict__ prefs_by_i2 = d.plan.prefs_by_i2,
+                *__restrict__ i2_seg = d.plan.i2_seg;
+  float *__restrict__ dg2 = d.dg[1];
+  // grid.x enumerates (i2, column tile, r1 tile); grid.y is the table in a batched launch
+  const int r1_tiles = (sh.R1 + TT_DG2_RT - 1) / TT_DG2_RT;
+  if ((int)blockIdx.x >= sh.n2 * col_tiles * r1_tiles) return;
+  const int bz = blockIdx.x % r1_tiles, by = (blockIdx.x / r1_tiles) % col_tiles,
+            bx = blockIdx.x / (r1_tiles * col_tiles);
+  const int i2 = bx, c = by * TT_BLOCK + threadIdx.x, r1b = bz * TT_DG2_RT;
   if (c >= sh.S2) return;
   float acc[TT_DG2_RT];
 #pragma unroll
@@ -341,7 +378,12 @@ k_bwd_dg2(TTShape sh, const float *__restrict__ g1, const int32_t *__restrict__ 
 }
 
 // ------------------------------------------------------------------ naive arm
-__global__ void k_fill_zero(float *__restrict__ p, size_t count) {
+template <bool BATCHED>
+__global__ void k_fill_zero_core(TTArg<BATCHED> a, int k) {
+  const TTDev &d = a.get();
+  float *__restrict__ p = d.dg[k];
+  const size_t count = k == 0 ? (size_t)d.sh.n1 * d.sh.S1
+                              : (k == 1 ? (size_t)d.sh.R1 * d.sh.n2 * d.sh.S2 : (size_t)d.sh.n3 * d.sh.S3);
   for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < count;
        e += (size_t)gridDim.x * blockDim.x)
     p[e] = 0.f;
@@ -349,12 +391,16 @@ __global__ void k_fill_zero(float *__restrict__ p, size_t count) {
 
 // Workgroup per lookup, no dedup, floating-point atomics into the core gradients.
 // LDS: g1s[S1] | p12[d1*d2*R2p] | hs[P] | gs[D] | g3s[S3]
+template <bool BATCHED>
 __global__ void __launch_bounds__(TT_BLOCK)
-k_bwd_naive(TTShape sh, const float *__restrict__ g1, const float *__restrict__ g2,
-            const float *__restrict__ g3, const int64_t *__restrict__ indices,
-            const int64_t *__restrict__ offsets, int nnz, int num_bags,
-            const float *__restrict__ grad_out, float *__restrict__ dg1, float *__restrict__ dg2,
-            float *__restrict__ dg3) {
+k_bwd_naive(TTArg<BATCHED> a) {
+  const TTDev &d = a.get();
+  const TTShape &sh = d.sh;
+  const float *__restrict__ g1 = d.g[0], *__restrict__ g2 = d.g[1], *__restrict__ g3 = d.g[2];
+  const int64_t *__restrict__ indices = d.indices, *__restrict__ offsets = d.offsets;
+  const int nnz = d.nnz, num_bags = d.num_bags;
+  const float *__restrict__ grad_out = d.grad_out;
+  float *__restrict__ dg1 = d.dg[0], *__restrict__ dg2 = d.dg[1], *__restrict__ dg3 = d.dg[2];
   extern __shared__ float lds[];
   float *g1s = lds, *p12 = g1s + sh.S1, *hs = p12 + sh.d1 * sh.d2 * sh.R2p, *gs = hs + sh.P,
         *g3s = gs + sh.D;
@@ -417,20 +463,33 @@ k_bwd_naive(TTShape sh, const float *__restrict__ g1, const float *__restrict__ 
 }
 
 // ------------------------------------------------------------------ gradient-descent update
-__global__ void k_sgd_dense(float *__restrict__ g, const float *__restrict__ dg, size_t count,
-                            float lr) {
+template <bool BATCHED>
+__global__ void k_sgd_dense(TTArg<BATCHED> a, int k) {
+  const TTDev &d = a.get();
+  float *__restrict__ g = const_cast<float *>(d.g[k]);
+  const float *__restrict__ dg = d.dg[k];
+  const float lr = d.lr;
+  const size_t count = k == 0 ? (size_t)d.sh.n1 * d.sh.S1
+                              : (k == 1 ? (size_t)d.sh.R1 * d.sh.n2 * d.sh.S2 : (size_t)d.sh.n3 * d.sh.S3);
   for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < count;
        e += (size_t)gridDim.x * blockDim.x)
     g[e] = fmaf(-lr, dg[e], g[e]);
 }
 
 // Workgroup per slice of any of the three cores; untouched slices (empty range) are skipped.
+template <bool BATCHED>
 __global__ void __launch_bounds__(TT_BLOCK)
-k_sgd_touched(TTShape sh, float *__restrict__ g1, float *__restrict__ g2, float *__restrict__ g3,
-              const float *__restrict__ dg1, const float *__restrict__ dg2,
-              const float *__restrict__ dg3, const int32_t *__restrict__ i1_seg,
-              const int32_t *__restrict__ i2_seg, const int32_t *__restrict__ i3_seg, float lr) {
+k_sgd_touched(TTArg<BATCHED> a) {
+  const TTDev &d = a.get();
+  const TTShape &sh = d.sh;
+  float *__restrict__ g1 = const_cast<float *>(d.g[0]), *__restrict__ g2 = const_cast<float *>(d.g[1]),
+        *__restrict__ g3 = const_cast<float *>(d.g[2]);
+  const float *__restrict__ dg1 = d.dg[0], *__restrict__ dg2 = d.dg[1], *__restrict__ dg3 = d.dg[2];
+  const int32_t *__restrict__ i1_seg = d.plan.i1_seg, *__restrict__ i2_seg = d.plan.i2_seg,
+                *__restrict__ i3_seg = d.plan.i3_seg;
+  const float lr = d.lr;
   int s = blockIdx.x;
+  if (s >= sh.n1 + sh.n2 + sh.n3) return;  // a narrower table of the batch
   if (s < sh.n1) {
     if (i1_seg[s] == i1_seg[s + 1]) return;
     for (int e = threadIdx.x; e < sh.S1; e += blockDim.x) {
@@ -462,84 +521,69 @@ size_t bwd_lds_bytes(const TTShape &sh) {
   return sizeof(float) * ((size_t)sh.S1 + (size_t)sh.d1 * sh.d2 * sh.R2p + sh.P + sh.D + sh.S3);
 }
 
-size_t core_len(const TTShape &sh, int k) {
-  if (k == 0) return (size_t)sh.n1 * sh.S1;
-  if (k == 1) return (size_t)sh.R1 * sh.n2 * sh.S2;
-  return (size_t)sh.n3 * sh.S3;
+long long core_len(const TTShape &sh, int k) {
+  if (k == 0) return (long long)sh.n1 * sh.S1;
+  if (k == 1) return (long long)sh.R1 * sh.n2 * sh.S2;
+  return (long long)sh.n3 * sh.S3;
 }
 
 }  // namespace
 
-tt_status ttk_backward_plan(const TTShape &sh, const tt_table *t, const tt_plan *plan,
-                            const float *grad_out, float *const dcore[3], hipStream_t s) {
+tt_status ttk_backward_plan(const TTBatch &b, hipStream_t s) {
+  const TTShape &sh = b.host[0].sh;
   tt_status st;
   // 1. merge output gradients per distinct row
-  SegArgs a1 = {sh.D, plan->counts + 2, plan->nnz, plan->slot_of_sorted, 1, plan->bag_of_sorted,
-                plan->row_seg, grad_out, 1, plan->gagg, sh.D, (int)plan->max_rows, 0,
-                plan->partial, 32, plan, TT_KERNEL_GRAD_MERGE};
-  if ((st = seg_sum(a1, s)) != TT_OK) return st;
+  if ((st = seg_sum(b, SEG_GAGG, 32, TT_KERNEL_GRAD_MERGE, s)) != TT_OK) return st;
   // 2. per-prefix contractions
   const bool mfma = tt_mfma_enabled() && ttk_forward_mfma_supported(sh);
-  const int strips = mfma ? ttk_mfma_strips(sh) : 1;
+  const long long max_pref = tt_batch_max(b, [](const TTDev &d) { return (long long)d.plan.max_prefixes; });
   if (mfma) {
-    if ((st = ttk_backward_mfma(sh, t, plan, dcore[1], s)) != TT_OK) return st;
-  } else if (plan->max_prefixes > 0) {
-    long long blocks = plan->max_prefixes < 4096 ? plan->max_prefixes : 4096;
-    TTProfScope prof(plan, TT_KERNEL_BWD_CONTRACT, s);
-    hipLaunchKernelGGL(k_bwd_prefix, dim3((unsigned)blocks), dim3(TT_BLOCK), bwd_lds_bytes(sh), s,
-                       sh, t->core[0], t->core[1], t->core[2], plan->counts, plan->uniq_pref,
-                       plan->pref_seg, plan->uniq_row, plan->gagg, plan->t3buf, plan->hbuf,
-                       plan->t1buf);
+    if ((st = ttk_backward_mfma(b, s)) != TT_OK) return st;
+  } else if (max_pref > 0) {
+    const long long blocks = max_pref < 4096 ? max_pref : 4096;
+    TTProfScope prof(&b.host[0].plan, TT_KERNEL_BWD_CONTRACT, s);
+    TT_LAUNCH(k_bwd_prefix, blocks, TT_BLOCK, bwd_lds_bytes(sh), s, b);
   }
   // 3a. core 2: sum the per-row contributions of all rows sharing i3
-  SegArgs a3 = {sh.S3, plan->counts + 0, plan->max_rows, plan->i3_of_sorted, 1, plan->rows_by_i3,
-                plan->i3_seg, plan->t3buf, strips, dcore[2], sh.d3, sh.n3, 1, plan->partial, TT_SEG_MIN_CHUNK, plan, -1};
-  if ((st = seg_sum(a3, s)) != TT_OK) return st;
+  if ((st = seg_sum(b, SEG_DG3, TT_SEG_MIN_CHUNK, -1, s)) != TT_OK) return st;
   // 3b. core 0: sum the per-prefix contributions of all prefixes sharing i1 (contiguous)
-  SegArgs a0 = {sh.S1, plan->counts + 1, plan->max_prefixes, plan->uniq_pref, sh.n2, nullptr,
-                plan->i1_seg, plan->t1buf, strips, dcore[0], sh.S1, sh.n1, 1, plan->partial, TT_SEG_MIN_CHUNK, plan, -1};
-  if ((st = seg_sum(a0, s)) != TT_OK) return st;
+  if ((st = seg_sum(b, SEG_DG1, TT_SEG_MIN_CHUNK, -1, s)) != TT_OK) return st;
   // 3c. core 1: per-i2 accumulation over prefixes (done inside the matrix-core kernel)
-  if (!mfma)
-    hipLaunchKernelGGL(k_bwd_dg2,
-                     dim3(sh.n2, tt_ceil_div(sh.S2, TT_BLOCK), tt_ceil_div(sh.R1, TT_DG2_RT)),
-                     dim3(TT_BLOCK), 0, s, sh, t->core[0], plan->uniq_pref, plan->prefs_by_i2,
-                     plan->i2_seg, plan->hbuf, dcore[1]);
+  if (!mfma) {
+    const int col_tiles = tt_ceil_div(sh.S2, TT_BLOCK), r1_tiles = tt_ceil_div(sh.R1, TT_DG2_RT);
+    const long long n2max = tt_batch_max(b, [](const TTDev &d) { return (long long)d.sh.n2; });
+    TT_LAUNCH(k_bwd_dg2, n2max * col_tiles * r1_tiles, TT_BLOCK, 0, s, b, col_tiles);
+  }
   return tt_launch_status();
 }
 
-tt_status ttk_backward_naive(const TTShape &sh, const tt_table *t, const int64_t *indices,
-                             const int64_t *offsets, int64_t nnz, int64_t num_bags,
-                             const float *grad_out, float *const dcore[3], hipStream_t s) {
+tt_status ttk_backward_naive(const TTBatch &b, hipStream_t s) {
   for (int k = 0; k < 3; ++k) {
-    const size_t len = core_len(sh, k);
-    int blocks = tt_ceil_div((long long)len, TT_BLOCK * 4);
+    const long long len = tt_batch_max(b, [k](const TTDev &d) { return core_len(d.sh, k); });
+    int blocks = tt_ceil_div(len, TT_BLOCK * 4);
     if (blocks > 4096) blocks = 4096;
-    hipLaunchKernelGGL(k_fill_zero, dim3(blocks), dim3(TT_BLOCK), 0, s, dcore[k], len);
+    TT_LAUNCH(k_fill_zero_core, blocks, TT_BLOCK, 0, s, b, k);
   }
-  if (nnz > 0) {
-    long long blocks = nnz < 65536 ? nnz : 65536;
-    hipLaunchKernelGGL(k_bwd_naive, dim3((unsigned)blocks), dim3(TT_BLOCK), bwd_lds_bytes(sh), s,
-                       sh, t->core[0], t->core[1], t->core[2], indices, offsets, (int)nnz,
-                       (int)num_bags, grad_out, dcore[0], dcore[1], dcore[2]);
+  const long long max_nnz = tt_batch_max(b, [](const TTDev &d) { return (long long)d.nnz; });
+  if (max_nnz > 0) {
+    const long long blocks = max_nnz < 65536 ? max_nnz : 65536;
+    TT_LAUNCH(k_bwd_naive, blocks, TT_BLOCK, bwd_lds_bytes(b.host[0].sh), s, b);
   }
   return tt_launch_status();
 }
 
-tt_status ttk_sgd(const TTShape &sh, const tt_table *t, const tt_plan *plan,
-                  const float *const dcore[3], float lr, hipStream_t s) {
-  if (plan) {
-    TTProfScope prof(plan, TT_KERNEL_SGD, s);
-    hipLaunchKernelGGL(k_sgd_touched, dim3(sh.n1 + sh.n2 + sh.n3), dim3(TT_BLOCK), 0, s, sh,
-                       t->core[0], t->core[1], t->core[2], dcore[0], dcore[1], dcore[2],
-                       plan->i1_seg, plan->i2_seg, plan->i3_seg, lr);
+tt_status ttk_sgd(const TTBatch &b, bool touched_only, hipStream_t s) {
+  if (touched_only) {
+    const long long slices = tt_batch_max(b, [](const TTDev &d) {
+      return (long long)d.sh.n1 + d.sh.n2 + d.sh.n3; });
+    TTProfScope prof(&b.host[0].plan, TT_KERNEL_SGD, s);
+    TT_LAUNCH(k_sgd_touched, slices, TT_BLOCK, 0, s, b);
   } else {
     for (int k = 0; k < 3; ++k) {
-      const size_t len = core_len(sh, k);
-      int blocks = tt_ceil_div((long long)len, TT_BLOCK * 4);
+      const long long len = tt_batch_max(b, [k](const TTDev &d) { return core_len(d.sh, k); });
+      int blocks = tt_ceil_div(len, TT_BLOCK * 4);
       if (blocks > 4096) blocks = 4096;
-      hipLaunchKernelGGL(k_sgd_dense, dim3(blocks), dim3(TT_BLOCK), 0, s, t->core[k], dcore[k], len,
-                         lr);
+      TT_LAUNCH(k_sgd_dense, blocks, TT_BLOCK, 0, s, b, k);
     }
   }
   return tt_launch_status();

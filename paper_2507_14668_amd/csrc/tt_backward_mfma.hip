@@ -56,14 +56,21 @@ struct BwdGeom {
 
 #define TT_META 64  // prefixes whose plan entries are fetched into LDS in one go (8 chunks)
 
-template <int R1, int R2, int D2>
+template <bool BATCHED, int R1, int R2, int D2>
 __global__ void __launch_bounds__(TT_BLOCK)
-k_bwd_mfma(TTShape sh, const float *__restrict__ g1, const float *__restrict__ g2,
-           const float *__restrict__ g3t, const int32_t *__restrict__ uniq_pref,
-           const int32_t *__restrict__ pref_seg, const int32_t *__restrict__ uniq_row,
-           const int32_t *__restrict__ prefs_by_i2, const int32_t *__restrict__ i2_seg,
-           const float *__restrict__ gagg, float *__restrict__ t3buf, float *__restrict__ t1buf,
-           float *__restrict__ dg2, float *__restrict__ dbg) {
+k_bwd_mfma(TTArg<BATCHED> a) {
+  const TTDev &d = a.get();
+  const TTShape &sh = d.sh;
+  const float *__restrict__ g1 = d.g[0], *__restrict__ g2 = d.g[1], *__restrict__ g3t = d.plan.g3t;
+  const int32_t *__restrict__ uniq_pref = d.plan.uniq_pref, *__restrict__ pref_seg = d.plan.pref_seg,
+                *__restrict__ uniq_row = d.plan.uniq_row, *__restrict__ prefs_by_i2 = d.plan.prefs_by_i2,
+                *__restrict__ i2_seg = d.plan.i2_seg;
+  const float *__restrict__ gagg = d.plan.gagg;
+  float *__restrict__ t3buf = d.plan.t3buf, *__restrict__ t1buf = d.plan.t1buf,
+        *__restrict__ dg2 = d.dg[1];
+#ifdef TT_DBG_TIMING
+  float *__restrict__ dbg = d.plan.hbuf;
+#endif
   using G = BwdGeom<R1, R2, D2>;
   constexpr int GPT = (32 * R1) / TT_BLOCK;  // core-0 tile elements per thread
   constexpr int T3_SPLIT = 4 / G::NTH;       // wave groups that alternate over the row quads for T3
@@ -77,6 +84,7 @@ k_bwd_mfma(TTShape sh, const float *__restrict__ g1, const float *__restrict__ g
   __shared__ int s_q[TT_META], s_i1[TT_META], s_u0[TT_META], s_nr[TT_META];
   __shared__ int s_i3[2][TT_MP][TT_I3_STAGE];
 
+  if ((int)blockIdx.x >= sh.n2 * G::NSTRIP) return;  // a table of the batch with fewer i2 values
   const int i2 = blockIdx.x / G::NSTRIP, strip = blockIdx.x - i2 * G::NSTRIP;
   const int j2base = strip * G::JW;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -459,22 +467,26 @@ k_bwd_mfma(TTShape sh, const float *__restrict__ g1, const float *__restrict__ g
 }
 
 template <int R1, int R2, int D2>
-tt_status launch(const TTShape &sh, const tt_table *t, const tt_plan *plan, float *dg2,
-                 hipStream_t s) {
+tt_status launch(const TTBatch &b, hipStream_t s) {
   using G = BwdGeom<R1, R2, D2>;
   const size_t lds = G::LDS_FLOATS * sizeof(float);
   static bool configured = false;
   if (!configured) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_bwd_mfma<R1, R2, D2>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_bwd_mfma<false, R1, R2, D2>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess ||
+        hipFuncSetAttribute(reinterpret_cast<const void *>(&k_bwd_mfma<true, R1, R2, D2>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
       return TT_ERR_HIP;
     configured = true;
   }
-  TTProfScope prof(plan, TT_KERNEL_BWD_CONTRACT, s);
-  hipLaunchKernelGGL((k_bwd_mfma<R1, R2, D2>), dim3(sh.n2 * G::NSTRIP), dim3(TT_BLOCK), lds, s, sh,
-                     t->core[0], t->core[1], plan->g3t, plan->uniq_pref, plan->pref_seg,
-                     plan->uniq_row, plan->prefs_by_i2, plan->i2_seg, plan->gagg, plan->t3buf,
-                     plan->t1buf, dg2, plan->hbuf);
+  const long long blocks = tt_batch_max(b, [](const TTDev &d) { return (long long)d.sh.n2 * G::NSTRIP; });
+  TTProfScope prof(&b.host[0].plan, TT_KERNEL_BWD_CONTRACT, s);
+  if (b.dev)
+    hipLaunchKernelGGL((k_bwd_mfma<true, R1, R2, D2>), dim3((unsigned)blocks, (unsigned)b.T),
+                       dim3(TT_BLOCK), lds, s, TTArg<true>{b.dev});
+  else
+    hipLaunchKernelGGL((k_bwd_mfma<false, R1, R2, D2>), dim3((unsigned)blocks), dim3(TT_BLOCK), lds, s,
+                       TTArg<false>{b.host[0]});
   return tt_launch_status();
 }
 
@@ -484,10 +496,9 @@ int ttk_mfma_strips(const TTShape &sh) {
   return ttk_forward_mfma_supported(sh) ? (sh.d2 * sh.R2) / 256 : 1;
 }
 
-tt_status ttk_backward_mfma(const TTShape &sh, const tt_table *t, const tt_plan *plan, float *dg2,
-                            hipStream_t s) {
-  tt_status st = ttk_pack_g3(sh, t, plan, s);
+tt_status ttk_backward_mfma(const TTBatch &b, hipStream_t s) {
+  tt_status st = ttk_pack_g3(b, s);
   if (st != TT_OK) return st;
-  if (sh.R1 == 32) return launch<32, 32, 8>(sh, t, plan, dg2, s);
-  return launch<64, 64, 8>(sh, t, plan, dg2, s);
+  if (b.host[0].sh.R1 == 32) return launch<32, 32, 8>(b, s);
+  return launch<64, 64, 8>(b, s);
 }

@@ -42,12 +42,15 @@ __device__ __forceinline__ void load_g3_slice(const TTShape &sh, const float *__
 }
 
 // LDS layout (floats): g1s[S1] | p12[d1*d2*R2p] | g3s[rows_per_iter * S3]
+template <bool BATCHED>
 __global__ void __launch_bounds__(TT_BLOCK)
-k_fwd_prefix_rows(TTShape sh, const float *__restrict__ g1, const float *__restrict__ g2,
-                  const float *__restrict__ g3, const int32_t *__restrict__ counts,
-                  const int32_t *__restrict__ uniq_pref, const int32_t *__restrict__ pref_seg,
-                  const int32_t *__restrict__ uniq_row, float *__restrict__ rowbuf,
-                  int rows_per_iter) {
+k_fwd_prefix_rows(TTArg<BATCHED> a, int rows_per_iter) {
+  const TTDev &d = a.get();
+  const TTShape &sh = d.sh;
+  const float *__restrict__ g1 = d.g[0], *__restrict__ g2 = d.g[1], *__restrict__ g3 = d.g[2];
+  const int32_t *__restrict__ counts = d.plan.counts, *__restrict__ uniq_pref = d.plan.uniq_pref,
+                *__restrict__ pref_seg = d.plan.pref_seg, *__restrict__ uniq_row = d.plan.uniq_row;
+  float *__restrict__ rowbuf = d.plan.rowbuf;
   extern __shared__ float lds[];
   float *g1s = lds, *p12 = g1s + sh.S1, *g3s = p12 + sh.d1 * sh.d2 * sh.R2p;
   const int up = counts[1];
@@ -97,11 +100,15 @@ __device__ __forceinline__ void load_row_vec(const float *__restrict__ rowbuf, i
 
 // out[b][:] = sum over the lookups of bag b of rowbuf[lookup2row[l]][:].
 // A group of LANES lanes owns one bag; each lane owns VEC consecutive columns per step.
-template <int VEC>
+template <bool BATCHED, int VEC>
 __global__ void __launch_bounds__(TT_BLOCK)
-k_bag_sum(int D, int lanes, const int64_t *__restrict__ offsets, int num_bags, int nnz,
-          const int32_t *__restrict__ lookup2row, const float *__restrict__ rowbuf,
-          float *__restrict__ out) {
+k_bag_sum(TTArg<BATCHED> a, int lanes) {
+  const TTDev &d = a.get();
+  const int D = d.sh.D, num_bags = d.num_bags, nnz = d.nnz;
+  const int64_t *__restrict__ offsets = d.offsets;
+  const int32_t *__restrict__ lookup2row = d.plan.lookup2row;
+  const float *__restrict__ rowbuf = d.plan.rowbuf;
+  float *__restrict__ out = d.out;
   const int groups_per_block = blockDim.x / lanes;
   const int g = threadIdx.x / lanes, lane = threadIdx.x - g * lanes;
   for (int b = blockIdx.x * groups_per_block + g; b < num_bags; b += gridDim.x * groups_per_block) {
@@ -151,11 +158,15 @@ k_bag_sum(int D, int lanes, const int64_t *__restrict__ offsets, int num_bags, i
 
 // Naive arm: workgroup per bag; every lookup recomputes its prefix product and row.
 // LDS layout: g1s[S1] | p12[d1*d2*R2p] | g3s[S3]
+template <bool BATCHED>
 __global__ void __launch_bounds__(TT_BLOCK)
-k_fwd_naive(TTShape sh, const float *__restrict__ g1, const float *__restrict__ g2,
-            const float *__restrict__ g3, const int64_t *__restrict__ indices,
-            const int64_t *__restrict__ offsets, int num_bags, int nnz,
-            float *__restrict__ out) {
+k_fwd_naive(TTArg<BATCHED> a) {
+  const TTDev &d = a.get();
+  const TTShape &sh = d.sh;
+  const float *__restrict__ g1 = d.g[0], *__restrict__ g2 = d.g[1], *__restrict__ g3 = d.g[2];
+  const int64_t *__restrict__ indices = d.indices, *__restrict__ offsets = d.offsets;
+  const int num_bags = d.num_bags, nnz = d.nnz;
+  float *__restrict__ out = d.out;
   extern __shared__ float lds[];
   float *g1s = lds, *p12 = g1s + sh.S1, *g3s = p12 + sh.d1 * sh.d2 * sh.R2p;
   constexpr int MAXO = 4;  // D <= 1024 columns over 256 threads
@@ -202,47 +213,40 @@ size_t fwd_lds_bytes(const TTShape &sh, int rows_per_iter) {
 
 }  // namespace
 
-tt_status ttk_forward_plan(const TTShape &sh, const tt_table *t, const tt_plan *plan,
-                           const int64_t *offsets, int64_t num_bags, float *out, hipStream_t s) {
-  if (plan->max_prefixes > 0 && tt_mfma_enabled() && ttk_forward_mfma_supported(sh)) {
-    tt_status st = ttk_forward_mfma(sh, t, plan, s);
+tt_status ttk_forward_plan(const TTBatch &b, hipStream_t s) {
+  const TTShape &sh = b.host[0].sh;  // d[] and r[] are common to the batch
+  const long long max_pref = tt_batch_max(b, [](const TTDev &d) { return (long long)d.plan.max_prefixes; });
+  const long long max_bags = tt_batch_max(b, [](const TTDev &d) { return (long long)d.num_bags; });
+  if (max_pref > 0 && tt_mfma_enabled() && ttk_forward_mfma_supported(sh)) {
+    tt_status st = ttk_forward_mfma(b, s);
     if (st != TT_OK) return st;
-  } else if (plan->max_prefixes > 0) {
+  } else if (max_pref > 0) {
     int rows_per_iter = TT_BLOCK / sh.D;
     if (rows_per_iter < 1) rows_per_iter = 1;
     if (rows_per_iter > 8) rows_per_iter = 8;
-    long long blocks = plan->max_prefixes < 4096 ? plan->max_prefixes : 4096;
-    TTProfScope prof(plan, TT_KERNEL_FWD_CONTRACT, s);
-    hipLaunchKernelGGL(k_fwd_prefix_rows, dim3((unsigned)blocks), dim3(TT_BLOCK),
-                       fwd_lds_bytes(sh, rows_per_iter), s, sh, t->core[0], t->core[1],
-                       t->core[2], plan->counts, plan->uniq_pref, plan->pref_seg, plan->uniq_row,
-                       plan->rowbuf, rows_per_iter);
+    const long long blocks = max_pref < 4096 ? max_pref : 4096;
+    TTProfScope prof(&b.host[0].plan, TT_KERNEL_FWD_CONTRACT, s);
+    TT_LAUNCH(k_fwd_prefix_rows, blocks, TT_BLOCK, fwd_lds_bytes(sh, rows_per_iter), s, b, rows_per_iter);
   }
-  if (num_bags > 0) {
-    const bool vec4 = (sh.D % 4) == 0 && ((uintptr_t)out % 16) == 0;
+  if (max_bags > 0) {
+    bool vec4 = (sh.D % 4) == 0;
+    for (int t = 0; t < b.T; ++t) vec4 = vec4 && ((uintptr_t)b.host[t].out % 16) == 0;
     int lanes = 1;
     while (lanes < TT_WAVE && lanes * (vec4 ? 4 : 1) < sh.D) lanes <<= 1;
     const int groups = TT_BLOCK / lanes;
-    long long blocks = (num_bags + groups - 1) / groups;
+    long long blocks = (max_bags + groups - 1) / groups;
     if (blocks > 16384) blocks = 16384;
-    TTProfScope prof(plan, TT_KERNEL_BAG_SUM, s);
-    if (vec4)
-      hipLaunchKernelGGL(k_bag_sum<4>, dim3((unsigned)blocks), dim3(TT_BLOCK), 0, s, sh.D, lanes,
-                         offsets, (int)num_bags, (int)plan->nnz, plan->lookup2row, plan->rowbuf, out);
-    else
-      hipLaunchKernelGGL(k_bag_sum<1>, dim3((unsigned)blocks), dim3(TT_BLOCK), 0, s, sh.D, lanes,
-                         offsets, (int)num_bags, (int)plan->nnz, plan->lookup2row, plan->rowbuf, out);
+    TTProfScope prof(&b.host[0].plan, TT_KERNEL_BAG_SUM, s);
+    if (vec4) TT_LAUNCH_T(k_bag_sum, 4, blocks, TT_BLOCK, 0, s, b, lanes);
+    else TT_LAUNCH_T(k_bag_sum, 1, blocks, TT_BLOCK, 0, s, b, lanes);
   }
   return tt_launch_status();
 }
 
-tt_status ttk_forward_naive(const TTShape &sh, const tt_table *t, const int64_t *indices,
-                            const int64_t *offsets, int64_t nnz, int64_t num_bags, float *out,
-                            hipStream_t s) {
-  if (num_bags == 0) return TT_OK;
-  long long blocks = num_bags < 65536 ? num_bags : 65536;
-  hipLaunchKernelGGL(k_fwd_naive, dim3((unsigned)blocks), dim3(TT_BLOCK), fwd_lds_bytes(sh, 1), s,
-                     sh, t->core[0], t->core[1], t->core[2], indices, offsets, (int)num_bags, (int)nnz,
-                     out);
+tt_status ttk_forward_naive(const TTBatch &b, hipStream_t s) {
+  const long long max_bags = tt_batch_max(b, [](const TTDev &d) { return (long long)d.num_bags; });
+  if (max_bags == 0) return TT_OK;
+  const long long blocks = max_bags < 65536 ? max_bags : 65536;
+  TT_LAUNCH(k_fwd_naive, blocks, TT_BLOCK, fwd_lds_bytes(b.host[0].sh, 1), s, b);
   return tt_launch_status();
 }

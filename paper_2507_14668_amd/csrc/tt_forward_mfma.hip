@@ -39,14 +39,17 @@ struct FwdGeom {
   static_assert(TT_MP * 4 * RS <= TT_MP * PS && TT_MP % 4 == 0, "core-0 tile must fit in the P12 area it aliases");
 };
 
-template <int R1, int R2, int D2>
+template <bool BATCHED, int R1, int R2, int D2>
 __global__ void __launch_bounds__(TT_BLOCK)
-k_fwd_mfma(TTShape sh, const float *__restrict__ g1, const float *__restrict__ g2,
-           const float *__restrict__ g3t, const int32_t *__restrict__ counts,
-           const int32_t *__restrict__ uniq_pref, const int32_t *__restrict__ pref_seg,
-           const int32_t *__restrict__ uniq_row, const int32_t *__restrict__ prefs_by_i2,
-           const int32_t *__restrict__ i2_seg, const int32_t *__restrict__ i2_chunk_off,
-           float *__restrict__ rowbuf) {
+k_fwd_mfma(TTArg<BATCHED> a) {
+  const TTDev &d = a.get();
+  const TTShape &sh = d.sh;
+  const float *__restrict__ g1 = d.g[0], *__restrict__ g2 = d.g[1], *__restrict__ g3t = d.plan.g3t;
+  const int32_t *__restrict__ counts = d.plan.counts, *__restrict__ uniq_pref = d.plan.uniq_pref,
+                *__restrict__ pref_seg = d.plan.pref_seg, *__restrict__ uniq_row = d.plan.uniq_row,
+                *__restrict__ prefs_by_i2 = d.plan.prefs_by_i2, *__restrict__ i2_seg = d.plan.i2_seg,
+                *__restrict__ i2_chunk_off = d.plan.i2_chunk_off;
+  float *__restrict__ rowbuf = d.plan.rowbuf;
   using G = FwdGeom<R1, R2, D2>;
   extern __shared__ float lds[];
   float *As = lds;    // [32][RS]  core-0 slices of the chunk (dead once F1 is done)
@@ -180,8 +183,12 @@ k_fwd_mfma(TTShape sh, const float *__restrict__ g1, const float *__restrict__ g
 
 // g3t[i3][r2][j3] = G3[r2][i3][j3]: a row's core-2 slice becomes one contiguous block, so the
 // MFMA operand gathers touch 2-4 cache lines per wavefront load instead of 16.
-__global__ void k_pack_g3(int n3, int R2, int d3, const float *__restrict__ g3,
-                          float *__restrict__ g3t) {
+template <bool BATCHED>
+__global__ void k_pack_g3(TTArg<BATCHED> a) {
+  const TTDev &d = a.get();
+  const int n3 = d.sh.n3, R2 = d.sh.R2, d3 = d.sh.d3;
+  const float *__restrict__ g3 = d.g[2];
+  float *__restrict__ g3t = d.plan.g3t;
   const int total = n3 * R2 * d3;
   for (int e = blockIdx.x * blockDim.x + threadIdx.x; e < total; e += gridDim.x * blockDim.x) {
     const int j3 = e % d3, r2 = (e / d3) % R2, i3 = e / (d3 * R2);
@@ -190,35 +197,39 @@ __global__ void k_pack_g3(int n3, int R2, int d3, const float *__restrict__ g3,
 }
 
 template <int R1, int R2, int D2>
-tt_status launch(const TTShape &sh, const tt_table *t, const tt_plan *plan, hipStream_t s) {
+tt_status launch(const TTBatch &b, hipStream_t s) {
   using G = FwdGeom<R1, R2, D2>;
   const size_t lds = G::LDS_FLOATS * sizeof(float);
   static bool configured = false;
   if (!configured) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fwd_mfma<R1, R2, D2>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fwd_mfma<false, R1, R2, D2>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess ||
+        hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fwd_mfma<true, R1, R2, D2>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
       return TT_ERR_HIP;
     configured = true;
   }
   // upper bound of the chunk count: every i2 adds at most one partly filled chunk
-  long long blocks = (plan->max_prefixes / TT_MP + sh.n2) * G::NSTRIP;
+  long long blocks = tt_batch_max(b, [](const TTDev &d) {
+    return (long long)(d.plan.max_prefixes / TT_MP + d.sh.n2) * G::NSTRIP; });
   if (blocks > 8192) blocks = 8192;  // grid-stride loop covers the rest
-  TTProfScope prof(plan, TT_KERNEL_FWD_CONTRACT, s);
-  hipLaunchKernelGGL((k_fwd_mfma<R1, R2, D2>), dim3((unsigned)blocks), dim3(TT_BLOCK), lds, s, sh,
-                     t->core[0], t->core[1], plan->g3t, plan->counts, plan->uniq_pref,
-                     plan->pref_seg, plan->uniq_row, plan->prefs_by_i2, plan->i2_seg,
-                     plan->i2_chunk_off, plan->rowbuf);
+  TTProfScope prof(&b.host[0].plan, TT_KERNEL_FWD_CONTRACT, s);
+  if (b.dev)
+    hipLaunchKernelGGL((k_fwd_mfma<true, R1, R2, D2>), dim3((unsigned)blocks, (unsigned)b.T),
+                       dim3(TT_BLOCK), lds, s, TTArg<true>{b.dev});
+  else
+    hipLaunchKernelGGL((k_fwd_mfma<false, R1, R2, D2>), dim3((unsigned)blocks), dim3(TT_BLOCK), lds, s,
+                       TTArg<false>{b.host[0]});
   return tt_launch_status();
 }
 
 }  // namespace
 
-tt_status ttk_pack_g3(const TTShape &sh, const tt_table *t, const tt_plan *plan, hipStream_t s) {
-  const int total = sh.n3 * sh.S3;
+tt_status ttk_pack_g3(const TTBatch &b, hipStream_t s) {
+  const long long total = tt_batch_max(b, [](const TTDev &d) { return (long long)d.sh.n3 * d.sh.S3; });
   int blocks = tt_ceil_div(total, TT_BLOCK);
   if (blocks > 1024) blocks = 1024;
-  hipLaunchKernelGGL(k_pack_g3, dim3(blocks), dim3(TT_BLOCK), 0, s, sh.n3, sh.R2, sh.d3, t->core[2],
-                     plan->g3t);
+  TT_LAUNCH(k_pack_g3, blocks, TT_BLOCK, 0, s, b);
   return tt_launch_status();
 }
 
@@ -227,10 +238,9 @@ bool ttk_forward_mfma_supported(const TTShape &sh) {
   return (sh.R1 == 32 && sh.R2 == 32) || (sh.R1 == 64 && sh.R2 == 64);
 }
 
-tt_status ttk_forward_mfma(const TTShape &sh, const tt_table *t, const tt_plan *plan,
-                           hipStream_t s) {
-  tt_status st = ttk_pack_g3(sh, t, plan, s);
+tt_status ttk_forward_mfma(const TTBatch &b, hipStream_t s) {
+  tt_status st = ttk_pack_g3(b, s);
   if (st != TT_OK) return st;
-  if (sh.R1 == 32) return launch<32, 32, 8>(sh, t, plan, s);
-  return launch<64, 64, 8>(sh, t, plan, s);
+  if (b.host[0].sh.R1 == 32) return launch<32, 32, 8>(b, s);
+  return launch<64, 64, 8>(b, s);
 }

@@ -39,36 +39,6 @@ struct TTShape {
 
 static inline int tt_ceil_div(long long a, long long b) { return (int)((a + b - 1) / b); }
 
-// Launchers (host).  Each enqueues kernels on `s` and returns the launch status.
-tt_status ttk_reorder(const TTShape &sh, const int64_t *indices, const int64_t *offsets,
-                      int64_t nnz, int64_t num_bags, const int64_t *remap, const tt_plan *plan,
-                      hipStream_t s);
-tt_status ttk_forward_plan(const TTShape &sh, const tt_table *t, const tt_plan *plan,
-                           const int64_t *offsets, int64_t num_bags, float *out, hipStream_t s);
-bool ttk_forward_mfma_supported(const TTShape &sh);
-tt_status ttk_forward_mfma(const TTShape &sh, const tt_table *t, const tt_plan *plan,
-                           hipStream_t s);
-// slice-contiguous copy of core 2 for the matrix-core kernels: g3t[i3][r2][j3] = G3[r2][i3][j3]
-tt_status ttk_pack_g3(const TTShape &sh, const tt_table *t, const tt_plan *plan, hipStream_t s);
-// number of 256-column strips a core-1 slice is cut into by the matrix-core kernels (1 when the
-// shape is served by the plain-ALU kernels); t3buf / t1buf hold one contribution per strip
-int ttk_mfma_strips(const TTShape &sh);
-tt_status ttk_backward_mfma(const TTShape &sh, const tt_table *t, const tt_plan *plan, float *dg2,
-                            hipStream_t s);
-// true unless the environment variable TT_EMB_NO_MFMA is set (keeps the plain-ALU kernels
-// selectable for comparison runs)
-bool tt_mfma_enabled();
-tt_status ttk_forward_naive(const TTShape &sh, const tt_table *t, const int64_t *indices,
-                            const int64_t *offsets, int64_t nnz, int64_t num_bags, float *out,
-                            hipStream_t s);
-tt_status ttk_backward_plan(const TTShape &sh, const tt_table *t, const tt_plan *plan,
-                            const float *grad_out, float *const dcore[3], hipStream_t s);
-tt_status ttk_backward_naive(const TTShape &sh, const tt_table *t, const int64_t *indices,
-                             const int64_t *offsets, int64_t nnz, int64_t num_bags,
-                             const float *grad_out, float *const dcore[3], hipStream_t s);
-tt_status ttk_sgd(const TTShape &sh, const tt_table *t, const tt_plan *plan,
-                  const float *const dcore[3], float lr, hipStream_t s);
-
 // Sort scratch carved from plan->sort_tmp (all int32 arrays).
 struct TTSortTmp {
   int32_t *keys_alt, *vals_alt;    // [nnz] ping-pong partner of (sorted_row, perm)
@@ -81,6 +51,94 @@ struct TTSortTmp {
 };
 TTSortTmp tt_sort_tmp_view(const tt_plan *plan);
 size_t tt_sort_tmp_bytes(int64_t nnz, int64_t max_rows, int64_t max_prefixes);
+
+// Everything a kernel needs to know about one table of a call.  A single-table call passes one
+// TTDev by value as a kernel argument; a batched call uploads an array of them and the kernels
+// pick theirs with blockIdx.y, so that one launch serves every table of the batch.
+struct TTDev {
+  TTShape sh;
+  const float *g[3];       // cores
+  float *dg[3];            // core gradients (backward / update)
+  tt_plan plan;            // device pointers of the plan (host-only fields unused on the device)
+  TTSortTmp tmp;           // sort scratch of the plan
+  const int64_t *indices, *offsets, *remap;
+  const float *grad_out;
+  float *out;
+  int nnz, num_bags;
+  int sort_tiles;          // radix tiles of the main lookup sort (hist row length)
+  int strips;              // 256-column strips of a core-1 slice (matrix-core path), else 1
+  float lr;
+};
+
+struct TTBatch {
+  int T;              // tables in the call
+  const TTDev *host;  // [T] host copies (grid sizing)
+  const TTDev *dev;   // [T] device copies, or nullptr: single table passed by value
+};
+
+template <bool BATCHED> struct TTArg;
+template <> struct TTArg<false> {
+  TTDev one;
+#ifdef __HIPCC__
+  __device__ __forceinline__ const TTDev &get() const { return one; }
+#endif
+};
+template <> struct TTArg<true> {
+  const TTDev *arr;
+#ifdef __HIPCC__
+  __device__ __forceinline__ const TTDev &get() const { return arr[blockIdx.y]; }
+#endif
+};
+
+// K is a kernel template whose first template parameter is `bool BATCHED` and whose first
+// argument is TTArg<BATCHED>; TARGS are its remaining template arguments (may be empty).
+#define TT_LAUNCH(K, gx, bs, lds, s, batch, ...)                                                  \
+  do {                                                                                            \
+    if ((batch).dev)                                                                              \
+      hipLaunchKernelGGL((K<true>), dim3((unsigned)(gx), (unsigned)(batch).T), dim3(bs), lds, s,  \
+                         TTArg<true>{(batch).dev}, ##__VA_ARGS__);                                \
+    else                                                                                          \
+      hipLaunchKernelGGL((K<false>), dim3((unsigned)(gx)), dim3(bs), lds, s,                      \
+                         TTArg<false>{(batch).host[0]}, ##__VA_ARGS__);                           \
+  } while (0)
+#define TT_LAUNCH_T(K, TARGS, gx, bs, lds, s, batch, ...)                                         \
+  do {                                                                                            \
+    if ((batch).dev)                                                                              \
+      hipLaunchKernelGGL((K<true, TARGS>), dim3((unsigned)(gx), (unsigned)(batch).T), dim3(bs),   \
+                         lds, s, TTArg<true>{(batch).dev}, ##__VA_ARGS__);                        \
+    else                                                                                          \
+      hipLaunchKernelGGL((K<false, TARGS>), dim3((unsigned)(gx)), dim3(bs), lds, s,               \
+                         TTArg<false>{(batch).host[0]}, ##__VA_ARGS__);                           \
+  } while (0)
+
+// Launchers (host).  Each enqueues kernels on `s` for every table of the batch and returns the
+// launch status.  All tables of a batch share d[] and r[] (checked by the caller).
+tt_status ttk_reorder(const TTBatch &b, hipStream_t s);
+tt_status ttk_forward_plan(const TTBatch &b, hipStream_t s);
+bool ttk_forward_mfma_supported(const TTShape &sh);
+tt_status ttk_forward_mfma(const TTBatch &b, hipStream_t s);
+// slice-contiguous copy of core 2 for the matrix-core kernels: g3t[i3][r2][j3] = G3[r2][i3][j3]
+tt_status ttk_pack_g3(const TTBatch &b, hipStream_t s);
+// number of 256-column strips a core-1 slice is cut into by the matrix-core kernels (1 when the
+// shape is served by the plain-ALU kernels); t3buf / t1buf hold one contribution per strip
+int ttk_mfma_strips(const TTShape &sh);
+tt_status ttk_backward_mfma(const TTBatch &b, hipStream_t s);
+// true unless the environment variable TT_EMB_NO_MFMA is set (keeps the plain-ALU kernels
+// selectable for comparison runs)
+bool tt_mfma_enabled();
+tt_status ttk_forward_naive(const TTBatch &b, hipStream_t s);
+tt_status ttk_backward_plan(const TTBatch &b, hipStream_t s);
+tt_status ttk_backward_naive(const TTBatch &b, hipStream_t s);
+tt_status ttk_sgd(const TTBatch &b, bool touched_only, hipStream_t s);
+
+template <class F> static inline long long tt_batch_max(const TTBatch &b, F f) {
+  long long m = 0;
+  for (int t = 0; t < b.T; ++t) {
+    const long long v = f(b.host[t]);
+    if (v > m) m = v;
+  }
+  return m;
+}
 
 // Brackets the launches made inside its scope with HIP events when the plan carries a tt_prof
 // that selects `kernel`.

@@ -14,18 +14,24 @@
 namespace {
 
 // ------------------------------------------------------------------ key extraction
-__global__ void k_init_counts(int32_t *counts, int nnz) {
-  if (threadIdx.x < 16) counts[threadIdx.x] = (threadIdx.x == 3) ? nnz : 0;
+template <bool BATCHED>
+__global__ void k_init_counts(TTArg<BATCHED> a) {
+  const TTDev &d = a.get();
+  if (threadIdx.x < 16) d.plan.counts[threadIdx.x] = (threadIdx.x == 3) ? d.nnz : 0;
 }
 
 // One thread per lookup: validate, apply the optional bijection, emit (row, position) and the
 // bag holding the position.  Threads b <= num_bags also validate the CSR offsets.
-__global__ void k_extract_keys(const int64_t *__restrict__ indices,
-                               const int64_t *__restrict__ offsets,
-                               const int64_t *__restrict__ remap, int nnz, int num_bags,
-                               long long num_rows, int sentinel, int32_t *__restrict__ keys,
-                               int32_t *__restrict__ vals, int32_t *__restrict__ bag_tmp,
-                               int32_t *__restrict__ counts) {
+template <bool BATCHED>
+__global__ void k_extract_keys(TTArg<BATCHED> a, int in_a) {
+  const TTDev &d = a.get();
+  const int64_t *__restrict__ indices = d.indices, *__restrict__ offsets = d.offsets,
+                *__restrict__ remap = d.remap;
+  const int nnz = d.nnz, num_bags = d.num_bags, sentinel = d.sh.sentinel;
+  const long long num_rows = d.sh.num_rows;
+  int32_t *__restrict__ keys = in_a ? d.plan.sorted_row : d.tmp.keys_alt;
+  int32_t *__restrict__ vals = in_a ? d.plan.perm : d.tmp.vals_alt;
+  int32_t *__restrict__ bag_tmp = d.tmp.bag_tmp, *__restrict__ counts = d.plan.counts;
   const int l = blockIdx.x * blockDim.x + threadIdx.x;
   if (l <= num_bags) {
     bool bad;
@@ -53,11 +59,41 @@ __global__ void k_extract_keys(const int64_t *__restrict__ indices,
 }
 
 // ------------------------------------------------------------------ LSD radix pass
+// The three sorts of a plan: 0 = lookups by row, 1 = distinct rows by i3, 2 = distinct prefixes
+// by i2.  (a) buffers hold the final result, (b) buffers are their ping-pong partners.
+struct SortBufs {
+  int32_t *ka, *va, *kb, *vb;
+  const int32_t *count_ptr;
+  int ntiles;
+};
+__device__ __forceinline__ SortBufs sort_bufs(const TTDev &d, int which) {
+  SortBufs b;
+  if (which == 0) {
+    b.ka = d.plan.sorted_row; b.va = d.plan.perm; b.kb = d.tmp.keys_alt; b.vb = d.tmp.vals_alt;
+    b.count_ptr = d.plan.counts + 3; b.ntiles = d.sort_tiles;
+  } else if (which == 1) {
+    b.ka = d.plan.i3_of_sorted; b.va = d.plan.rows_by_i3; b.kb = d.tmp.k3_alt; b.vb = d.tmp.v3_alt;
+    b.count_ptr = d.plan.counts + 0;
+    b.ntiles = (int)((d.plan.max_rows + TT_SORT_TILE - 1) / TT_SORT_TILE);
+  } else {
+    b.ka = d.tmp.k2; b.va = d.plan.prefs_by_i2; b.kb = d.tmp.k2_alt; b.vb = d.tmp.v2_alt;
+    b.count_ptr = d.plan.counts + 1;
+    b.ntiles = (int)((d.plan.max_prefixes + TT_SORT_TILE - 1) / TT_SORT_TILE);
+  }
+  return b;
+}
+
+template <bool BATCHED>
 __global__ void __launch_bounds__(TT_BLOCK)
-k_radix_hist(const int32_t *__restrict__ keys, const int32_t *__restrict__ count_ptr, int shift,
-             int bits, int ntiles, int32_t *__restrict__ hist) {
+k_radix_hist(TTArg<BATCHED> a, int which, int in_a, int shift, int bits) {
+  const TTDev &d = a.get();
+  const SortBufs sb = sort_bufs(d, which);
+  const int ntiles = sb.ntiles;
+  if ((int)blockIdx.x >= ntiles) return;  // uniform: this table has fewer tiles than the widest
+  const int32_t *__restrict__ keys = in_a ? sb.ka : sb.kb;
+  int32_t *__restrict__ hist = d.tmp.hist;
   __shared__ int h[1 << TT_SORT_MAX_BITS];
-  const int nbins = 1 << bits, tile = blockIdx.x, count = *count_ptr;
+  const int nbins = 1 << bits, tile = blockIdx.x, count = *sb.count_ptr;
   for (int b = threadIdx.x; b < nbins; b += TT_BLOCK) h[b] = 0;
   __syncthreads();
   const int base = tile * TT_SORT_TILE;
@@ -73,10 +109,14 @@ k_radix_hist(const int32_t *__restrict__ keys, const int32_t *__restrict__ count
 }
 
 // One workgroup per bin: exclusive scan of that bin's per-tile counts, in place.
+template <bool BATCHED>
 __global__ void __launch_bounds__(TT_BLOCK)
-k_radix_binscan(int32_t *__restrict__ hist, int ntiles, int32_t *__restrict__ bin_total) {
+k_radix_binscan(TTArg<BATCHED> a, int which) {
+  const TTDev &d = a.get();
+  const int ntiles = sort_bufs(d, which).ntiles;
+  int32_t *__restrict__ bin_total = d.tmp.bin_total;
   __shared__ int tmp[TT_BLOCK / TT_WAVE + 1];
-  int32_t *row = hist + (size_t)blockIdx.x * ntiles;
+  int32_t *row = d.tmp.hist + (size_t)blockIdx.x * ntiles;
   int carry = 0;
   for (int base = 0; base < ntiles; base += TT_BLOCK) {
     int t = base + threadIdx.x;
@@ -90,11 +130,17 @@ k_radix_binscan(int32_t *__restrict__ hist, int ntiles, int32_t *__restrict__ bi
 
 // Stable scatter: elements of a tile are ranked in tile order (round i, thread t) so that equal
 // digits keep their relative order.
+template <bool BATCHED>
 __global__ void __launch_bounds__(TT_BLOCK)
-k_radix_scatter(const int32_t *__restrict__ keys_in, const int32_t *__restrict__ vals_in,
-                int32_t *__restrict__ keys_out, int32_t *__restrict__ vals_out,
-                const int32_t *__restrict__ count_ptr, int shift, int bits, int ntiles,
-                const int32_t *__restrict__ hist, const int32_t *__restrict__ bin_total) {
+k_radix_scatter(TTArg<BATCHED> a, int which, int in_a, int shift, int bits) {
+  const TTDev &d = a.get();
+  const SortBufs sb = sort_bufs(d, which);
+  const int ntiles = sb.ntiles;
+  if ((int)blockIdx.x >= ntiles) return;  // uniform
+  const int32_t *__restrict__ keys_in = in_a ? sb.ka : sb.kb, *__restrict__ vals_in = in_a ? sb.va : sb.vb;
+  int32_t *__restrict__ keys_out = in_a ? sb.kb : sb.ka, *__restrict__ vals_out = in_a ? sb.vb : sb.va;
+  const int32_t *__restrict__ count_ptr = sb.count_ptr, *__restrict__ hist = d.tmp.hist,
+                *__restrict__ bin_total = d.tmp.bin_total;
   constexpr int MAXB = 1 << TT_SORT_MAX_BITS;
   constexpr int NW = TT_BLOCK / TT_WAVE;
   __shared__ int gofs[MAXB];
@@ -187,9 +233,15 @@ __device__ __forceinline__ void head_flags(const int32_t *__restrict__ keys, int
   hp = (kp / n3) != (k / n3);
 }
 
+template <bool BATCHED>
 __global__ void __launch_bounds__(TT_BLOCK)
-k_uniq_reduce(const int32_t *__restrict__ keys, int nnz, int sentinel, int n3, int ntiles,
-              int32_t *__restrict__ tile_sums, int32_t *__restrict__ counts) {
+k_uniq_reduce(TTArg<BATCHED> a) {
+  const TTDev &d = a.get();
+  const int nnz = d.nnz, sentinel = d.sh.sentinel, n3 = d.sh.n3;
+  const int ntiles = (nnz + TT_UNIQ_TILE - 1) / TT_UNIQ_TILE;
+  if ((int)blockIdx.x >= ntiles) return;  // uniform
+  const int32_t *__restrict__ keys = d.plan.sorted_row;
+  int32_t *__restrict__ tile_sums = d.tmp.tile_sums, *__restrict__ counts = d.plan.counts;
   __shared__ int tmp[TT_BLOCK / TT_WAVE + 1];
   int sr = 0, sp = 0;
   const int s0 = blockIdx.x * TT_UNIQ_TILE + threadIdx.x * TT_UNIQ_ITEMS;
@@ -212,9 +264,13 @@ k_uniq_reduce(const int32_t *__restrict__ keys, int nnz, int sentinel, int n3, i
   }
 }
 
+template <bool BATCHED>
 __global__ void __launch_bounds__(TT_BLOCK)
-k_uniq_scan(int32_t *__restrict__ tile_sums, int ntiles, int32_t *__restrict__ counts,
-            int32_t *__restrict__ row_seg, int32_t *__restrict__ pref_seg) {
+k_uniq_scan(TTArg<BATCHED> a) {
+  const TTDev &d = a.get();
+  const int ntiles = (d.nnz + TT_UNIQ_TILE - 1) / TT_UNIQ_TILE;
+  int32_t *__restrict__ tile_sums = d.tmp.tile_sums, *__restrict__ counts = d.plan.counts,
+          *__restrict__ row_seg = d.plan.row_seg, *__restrict__ pref_seg = d.plan.pref_seg;
   __shared__ int tmp[TT_BLOCK / TT_WAVE + 1];
   int carry[2] = {0, 0};
   for (int c = 0; c < 2; ++c) {
@@ -235,14 +291,20 @@ k_uniq_scan(int32_t *__restrict__ tile_sums, int ntiles, int32_t *__restrict__ c
   }
 }
 
+template <bool BATCHED>
 __global__ void __launch_bounds__(TT_BLOCK)
-k_uniq_emit(const int32_t *__restrict__ keys, const int32_t *__restrict__ perm,
-            const int32_t *__restrict__ bag_tmp, int nnz, int sentinel, int n3, int ntiles,
-            const int32_t *__restrict__ tile_sums, int32_t *__restrict__ bag_of_sorted,
-            int32_t *__restrict__ slot_of_sorted, int32_t *__restrict__ lookup2row,
-            int32_t *__restrict__ uniq_row, int32_t *__restrict__ row_seg,
-            int32_t *__restrict__ row2pref, int32_t *__restrict__ uniq_pref,
-            int32_t *__restrict__ pref_seg) {
+k_uniq_emit(TTArg<BATCHED> a) {
+  const TTDev &d = a.get();
+  const int nnz = d.nnz, sentinel = d.sh.sentinel, n3 = d.sh.n3;
+  const int ntiles = (nnz + TT_UNIQ_TILE - 1) / TT_UNIQ_TILE;
+  if ((int)blockIdx.x >= ntiles) return;  // uniform
+  const int32_t *__restrict__ keys = d.plan.sorted_row, *__restrict__ perm = d.plan.perm,
+                *__restrict__ bag_tmp = d.tmp.bag_tmp, *__restrict__ tile_sums = d.tmp.tile_sums;
+  int32_t *__restrict__ bag_of_sorted = d.plan.bag_of_sorted,
+          *__restrict__ slot_of_sorted = d.plan.slot_of_sorted,
+          *__restrict__ lookup2row = d.plan.lookup2row, *__restrict__ uniq_row = d.plan.uniq_row,
+          *__restrict__ row_seg = d.plan.row_seg, *__restrict__ row2pref = d.plan.row2pref,
+          *__restrict__ uniq_pref = d.plan.uniq_pref, *__restrict__ pref_seg = d.plan.pref_seg;
   __shared__ int tmp[TT_BLOCK / TT_WAVE + 1];
   const int s0 = blockIdx.x * TT_UNIQ_TILE + threadIdx.x * TT_UNIQ_ITEMS;
   int hr[TT_UNIQ_ITEMS], hp[TT_UNIQ_ITEMS], sr = 0, sp = 0;
@@ -278,11 +340,16 @@ k_uniq_emit(const int32_t *__restrict__ keys, const int32_t *__restrict__ perm,
 }
 
 // ------------------------------------------------------------------ groupings by i3 / i2 / i1
-__global__ void k_group_keys(const int32_t *__restrict__ counts,
-                             const int32_t *__restrict__ uniq_row, int n3,
-                             int32_t *__restrict__ k3, int32_t *__restrict__ v3,
-                             const int32_t *__restrict__ uniq_pref, int n2,
-                             int32_t *__restrict__ k2, int32_t *__restrict__ v2) {
+template <bool BATCHED>
+__global__ void k_group_keys(TTArg<BATCHED> a, int a3, int a2) {
+  const TTDev &d = a.get();
+  const int32_t *__restrict__ counts = d.plan.counts, *__restrict__ uniq_row = d.plan.uniq_row,
+                *__restrict__ uniq_pref = d.plan.uniq_pref;
+  const int n3 = d.sh.n3, n2 = d.sh.n2;
+  int32_t *__restrict__ k3 = a3 ? d.plan.i3_of_sorted : d.tmp.k3_alt;
+  int32_t *__restrict__ v3 = a3 ? d.plan.rows_by_i3 : d.tmp.v3_alt;
+  int32_t *__restrict__ k2 = a2 ? d.tmp.k2 : d.tmp.k2_alt;
+  int32_t *__restrict__ v2 = a2 ? d.plan.prefs_by_i2 : d.tmp.v2_alt;
   const int ur = counts[0], up = counts[1];
   for (int u = blockIdx.x * blockDim.x + threadIdx.x; u < ur; u += gridDim.x * blockDim.x) {
     k3[u] = uniq_row[u] % n3;
@@ -304,12 +371,14 @@ __device__ __forceinline__ int lower_bound_div(const int32_t *__restrict__ a, in
   return lo;
 }
 
-__global__ void k_seg_bounds(const int32_t *__restrict__ counts,
-                             const int32_t *__restrict__ k3_sorted, int n3,
-                             int32_t *__restrict__ i3_seg, const int32_t *__restrict__ k2_sorted,
-                             int n2, int32_t *__restrict__ i2_seg,
-                             const int32_t *__restrict__ uniq_pref, int n1,
-                             int32_t *__restrict__ i1_seg) {
+template <bool BATCHED>
+__global__ void k_seg_bounds(TTArg<BATCHED> a) {
+  const TTDev &d = a.get();
+  const int32_t *__restrict__ counts = d.plan.counts, *__restrict__ k3_sorted = d.plan.i3_of_sorted,
+                *__restrict__ k2_sorted = d.tmp.k2, *__restrict__ uniq_pref = d.plan.uniq_pref;
+  int32_t *__restrict__ i3_seg = d.plan.i3_seg, *__restrict__ i2_seg = d.plan.i2_seg,
+          *__restrict__ i1_seg = d.plan.i1_seg;
+  const int n1 = d.sh.n1, n2 = d.sh.n2, n3 = d.sh.n3;
   const int ur = counts[0], up = counts[1];
   const int t = blockIdx.x * blockDim.x + threadIdx.x;
   if (t <= n3) i3_seg[t] = lower_bound_div(k3_sorted, ur, 1, t);
@@ -318,9 +387,13 @@ __global__ void k_seg_bounds(const int32_t *__restrict__ counts,
 }
 
 // Running count of TT_MP-prefix chunks per i2 (single workgroup; n2 may exceed the block size).
+template <bool BATCHED>
 __global__ void __launch_bounds__(TT_BLOCK)
-k_chunk_offsets(const int32_t *__restrict__ i2_seg, int n2, int32_t *__restrict__ chunk_off,
-                int32_t *__restrict__ counts) {
+k_chunk_offsets(TTArg<BATCHED> a) {
+  const TTDev &d = a.get();
+  const int32_t *__restrict__ i2_seg = d.plan.i2_seg;
+  const int n2 = d.sh.n2;
+  int32_t *__restrict__ chunk_off = d.plan.i2_chunk_off, *__restrict__ counts = d.plan.counts;
   __shared__ int tmp[TT_BLOCK / TT_WAVE + 1];
   int carry = 0;
   for (int base = 0; base < n2; base += TT_BLOCK) {
@@ -351,28 +424,21 @@ RadixPlan radix_plan(int key_bits) {
   return p;
 }
 
-// Sort (keys, vals) of *count_ptr (<= max_count) elements.  The input must sit in
-// (a) when the number of passes is even and in (b) when it is odd; the result lands in (a).
-tt_status radix_sort(int32_t *keys_a, int32_t *vals_a, int32_t *keys_b, int32_t *vals_b,
-                     const int32_t *count_ptr, int64_t max_count, int key_bits,
-                     const TTSortTmp &tmp, hipStream_t s, const tt_plan *prof_plan = nullptr) {
+// One of the three sorts, for every table of the batch, with the same pass structure (so that a
+// pass is one launch): key_bits is the widest key of the batch.  The input must sit in the (a)
+// buffers when the number of passes is even and in (b) when it is odd; the result lands in (a).
+tt_status radix_sort(const TTBatch &b, int which, int max_tiles, int key_bits, hipStream_t s) {
   const RadixPlan rp = radix_plan(key_bits);
-  const int ntiles = tt_ceil_div(max_count, TT_SORT_TILE);
-  if (ntiles == 0) return TT_OK;
-  bool in_a = (rp.passes % 2) == 0;
+  if (max_tiles == 0) return TT_OK;
+  int in_a = (rp.passes % 2) == 0;
   int shift = 0;
   for (int p = 0; p < rp.passes; ++p) {
     const int bits = (key_bits - shift) < rp.bits_per_pass ? (key_bits - shift) : rp.bits_per_pass;
-    int32_t *ki = in_a ? keys_a : keys_b, *vi = in_a ? vals_a : vals_b;
-    int32_t *ko = in_a ? keys_b : keys_a, *vo = in_a ? vals_b : vals_a;
-    hipLaunchKernelGGL(k_radix_hist, dim3(ntiles), dim3(TT_BLOCK), 0, s, ki, count_ptr, shift,
-                       bits, ntiles, tmp.hist);
-    hipLaunchKernelGGL(k_radix_binscan, dim3(1 << bits), dim3(TT_BLOCK), 0, s, tmp.hist, ntiles,
-                       tmp.bin_total);
+    TT_LAUNCH(k_radix_hist, max_tiles, TT_BLOCK, 0, s, b, which, in_a, shift, bits);
+    TT_LAUNCH(k_radix_binscan, 1 << bits, TT_BLOCK, 0, s, b, which);
     {
-      TTProfScope prof(prof_plan, TT_KERNEL_SORT_SCATTER, s);
-      hipLaunchKernelGGL(k_radix_scatter, dim3(ntiles), dim3(TT_BLOCK), 0, s, ki, vi, ko, vo,
-                         count_ptr, shift, bits, ntiles, tmp.hist, tmp.bin_total);
+      TTProfScope prof(which == 0 ? &b.host[0].plan : nullptr, TT_KERNEL_SORT_SCATTER, s);
+      TT_LAUNCH(k_radix_scatter, max_tiles, TT_BLOCK, 0, s, b, which, in_a, shift, bits);
     }
     shift += bits;
     in_a = !in_a;
@@ -416,62 +482,45 @@ TTSortTmp tt_sort_tmp_view(const tt_plan *plan) {
   return t;
 }
 
-tt_status ttk_reorder(const TTShape &sh, const int64_t *indices, const int64_t *offsets,
-                      int64_t nnz64, int64_t num_bags64, const int64_t *remap,
-                      const tt_plan *plan, hipStream_t s) {
-  const int nnz = (int)nnz64, num_bags = (int)num_bags64;
-  const TTSortTmp tmp = tt_sort_tmp_view(plan);
-  hipLaunchKernelGGL(k_init_counts, dim3(1), dim3(64), 0, s, plan->counts, nnz);
+tt_status ttk_reorder(const TTBatch &b, hipStream_t s) {
+  TT_LAUNCH(k_init_counts, 1, 64, 0, s, b);
 
   // main sort: keys in [0, sentinel]
-  const int key_bits = bit_length(sh.sentinel);
-  const bool in_a = (radix_plan(key_bits).passes % 2) == 0;
-  int32_t *k0 = in_a ? plan->sorted_row : tmp.keys_alt, *v0 = in_a ? plan->perm : tmp.vals_alt;
-  const int cover = (nnz > num_bags + 1 ? nnz : num_bags + 1);
-  hipLaunchKernelGGL(k_extract_keys, dim3(tt_ceil_div(cover, TT_BLOCK)), dim3(TT_BLOCK), 0, s,
-                     indices, offsets, remap, nnz, num_bags, sh.num_rows, sh.sentinel, k0, v0,
-                     tmp.bag_tmp, plan->counts);
-  tt_status st = radix_sort(plan->sorted_row, plan->perm, tmp.keys_alt, tmp.vals_alt,
-                            plan->counts + 3, nnz, key_bits, tmp, s, plan);
+  const int key_bits = bit_length(tt_batch_max(b, [](const TTDev &d) { return (long long)d.sh.sentinel; }));
+  const int in_a = (radix_plan(key_bits).passes % 2) == 0;
+  const long long cover = tt_batch_max(b, [](const TTDev &d) {
+    return (long long)(d.nnz > d.num_bags + 1 ? d.nnz : d.num_bags + 1); });
+  TT_LAUNCH(k_extract_keys, tt_ceil_div(cover, TT_BLOCK), TT_BLOCK, 0, s, b, in_a);
+  const int tiles0 = (int)tt_batch_max(b, [](const TTDev &d) { return (long long)d.sort_tiles; });
+  tt_status st = radix_sort(b, 0, tiles0, key_bits, s);
   if (st != TT_OK) return st;
 
   // distinct rows and prefixes
-  const int utiles = tt_ceil_div(nnz, TT_UNIQ_TILE);
-  if (utiles > 0)
-    hipLaunchKernelGGL(k_uniq_reduce, dim3(utiles), dim3(TT_BLOCK), 0, s, plan->sorted_row, nnz,
-                       sh.sentinel, sh.n3, utiles, tmp.tile_sums, plan->counts);
-  hipLaunchKernelGGL(k_uniq_scan, dim3(1), dim3(TT_BLOCK), 0, s, tmp.tile_sums, utiles,
-                     plan->counts, plan->row_seg, plan->pref_seg);
-  if (utiles > 0)
-    hipLaunchKernelGGL(k_uniq_emit, dim3(utiles), dim3(TT_BLOCK), 0, s, plan->sorted_row,
-                       plan->perm, tmp.bag_tmp, nnz, sh.sentinel, sh.n3, utiles, tmp.tile_sums,
-                       plan->bag_of_sorted, plan->slot_of_sorted, plan->lookup2row,
-                       plan->uniq_row, plan->row_seg, plan->row2pref, plan->uniq_pref,
-                       plan->pref_seg);
+  const int utiles = (int)tt_batch_max(b, [](const TTDev &d) {
+    return (long long)tt_ceil_div(d.nnz, TT_UNIQ_TILE); });
+  if (utiles > 0) TT_LAUNCH(k_uniq_reduce, utiles, TT_BLOCK, 0, s, b);
+  TT_LAUNCH(k_uniq_scan, 1, TT_BLOCK, 0, s, b);
+  if (utiles > 0) TT_LAUNCH(k_uniq_emit, utiles, TT_BLOCK, 0, s, b);
 
   // groupings: distinct rows by i3, distinct prefixes by i2 (stable), i1 ranges
-  const int bits3 = bit_length(sh.n3 - 1), bits2 = bit_length(sh.n2 - 1);
-  const bool a3 = (radix_plan(bits3).passes % 2) == 0, a2 = (radix_plan(bits2).passes % 2) == 0;
-  int32_t *k3in = a3 ? plan->i3_of_sorted : tmp.k3_alt, *v3in = a3 ? plan->rows_by_i3 : tmp.v3_alt;
-  int32_t *k2in = a2 ? tmp.k2 : tmp.k2_alt, *v2in = a2 ? plan->prefs_by_i2 : tmp.v2_alt;
-  if (plan->max_rows > 0) {
-    int blocks = tt_ceil_div(plan->max_rows, TT_BLOCK);
+  const int bits3 = bit_length(tt_batch_max(b, [](const TTDev &d) { return (long long)d.sh.n3 - 1; }));
+  const int bits2 = bit_length(tt_batch_max(b, [](const TTDev &d) { return (long long)d.sh.n2 - 1; }));
+  const int a3 = (radix_plan(bits3).passes % 2) == 0, a2 = (radix_plan(bits2).passes % 2) == 0;
+  const long long max_rows = tt_batch_max(b, [](const TTDev &d) { return (long long)d.plan.max_rows; });
+  const long long max_pref = tt_batch_max(b, [](const TTDev &d) { return (long long)d.plan.max_prefixes; });
+  if (max_rows > 0) {
+    int blocks = tt_ceil_div(max_rows, TT_BLOCK);
     if (blocks > 2048) blocks = 2048;
-    hipLaunchKernelGGL(k_group_keys, dim3(blocks), dim3(TT_BLOCK), 0, s, plan->counts,
-                       plan->uniq_row, sh.n3, k3in, v3in, plan->uniq_pref, sh.n2, k2in, v2in);
-    st = radix_sort(plan->i3_of_sorted, plan->rows_by_i3, tmp.k3_alt, tmp.v3_alt, plan->counts + 0,
-                    plan->max_rows, bits3, tmp, s);
+    TT_LAUNCH(k_group_keys, blocks, TT_BLOCK, 0, s, b, a3, a2);
+    st = radix_sort(b, 1, tt_ceil_div(max_rows, TT_SORT_TILE), bits3, s);
     if (st != TT_OK) return st;
-    st = radix_sort(tmp.k2, plan->prefs_by_i2, tmp.k2_alt, tmp.v2_alt, plan->counts + 1,
-                    plan->max_prefixes, bits2, tmp, s);
+    st = radix_sort(b, 2, tt_ceil_div(max_pref, TT_SORT_TILE), bits2, s);
     if (st != TT_OK) return st;
   }
-  int nmax = sh.n1 > sh.n2 ? sh.n1 : sh.n2;
-  if (sh.n3 > nmax) nmax = sh.n3;
-  hipLaunchKernelGGL(k_seg_bounds, dim3(tt_ceil_div(nmax + 1, TT_BLOCK)), dim3(TT_BLOCK), 0, s,
-                     plan->counts, plan->i3_of_sorted, sh.n3, plan->i3_seg, tmp.k2, sh.n2,
-                     plan->i2_seg, plan->uniq_pref, sh.n1, plan->i1_seg);
-  hipLaunchKernelGGL(k_chunk_offsets, dim3(1), dim3(TT_BLOCK), 0, s, plan->i2_seg, sh.n2,
-                     plan->i2_chunk_off, plan->counts);
+  const long long nmax = tt_batch_max(b, [](const TTDev &d) {
+    long long m = d.sh.n1 > d.sh.n2 ? d.sh.n1 : d.sh.n2;
+    return m > d.sh.n3 ? m : (long long)d.sh.n3; });
+  TT_LAUNCH(k_seg_bounds, tt_ceil_div(nmax + 1, TT_BLOCK), TT_BLOCK, 0, s, b);
+  TT_LAUNCH(k_chunk_offsets, 1, TT_BLOCK, 0, s, b);
   return tt_launch_status();
 }

@@ -56,3 +56,14 @@ def test_workspace_query_and_host_validation_without_gpu():
     assert st == binding.TT_ERR_INVALID_ARG
     st = lib.tt_emb_bag_forward(None, None, None, None, 0, 0, None, None)
     assert st == binding.TT_ERR_INVALID_ARG
+
+
+def test_batched_entry_points_are_switched_off():
+    """They report TT_ERR_UNAVAILABLE and launch nothing (see the header for the reason)."""
+    from paper_2507_14668_amd import binding
+    lib = binding.load_library()
+    items = (binding.CBatchItem * 1)()
+    for name in ("tt_index_reorder_batched", "tt_emb_bag_forward_batched", "tt_emb_bag_backward_batched"):
+        assert getattr(lib, name)(1, items, None, 0, None) == binding.TT_ERR_UNAVAILABLE
+    assert lib.tt_core_sgd_update_batched(1, items, 0.1, None, 0, None) == binding.TT_ERR_UNAVAILABLE
+    assert lib.tt_batch_desc_bytes(4) > 0

@@ -196,3 +196,63 @@ def test_two_stream_pipeline_equals_sequential(g):
             assert torch.equal(a, b)
         for a, b in zip(seq[tab][1], pipe[tab][1]):
             assert torch.equal(a, b)
+
+
+@pytest.mark.skip(reason="batched entry points are switched off (TT_ERR_UNAVAILABLE): their first GPU run "
+                         "ended in a memory fault whose cause has not been found; the case must not run on "
+                         "the GPU again until it is")
+@pytest.mark.parametrize("kind", ["mfma", "plain"])
+def test_batched_calls_equal_single_table_calls(g, kind):
+    """One launch per kernel for several tables (different row factors, same d and ranks) must give
+    bit-for-bit the results of the single-table calls, for the planned and the naive arms."""
+    import paper_2507_14668_amd as tt
+    if kind == "mfma":
+        cfg, tabs = cfg5_tables()
+        tabs = tabs + [3]
+        nb = 4096
+        specs = [(cfg.tables[t], wl.make_cores(cfg, t), wl.make_batch(cfg, t, num_bags=nb),
+                  wl.make_grad(cfg, t, num_bags=nb)) for t in tabs]
+    else:
+        specs = []
+        for seed, n in [(71, (5, 7, 9)), (72, (11, 3, 4)), (73, (2, 13, 6))]:
+            shape, cores, idx, off, grad = wl.small_random_problem(seed, n=n, d=(2, 3, 4), r=(1, 5, 6, 1),
+                                                                  num_bags=300, max_len=7)
+            specs.append((shape, cores, (idx, off), grad))
+    lr = 0.01
+    for planned in (True, False):
+        print("case batched kind=%s planned=%s" % (kind, planned), flush=True)
+        singles, tables_b, idxs, offs, grads = [], [], [], [], []
+        for shape, cores, (idx, off), grad in specs:
+            table = g.gpu_table(shape, cores)
+            d_idx, d_off, d_g = g.to_dev(idx, torch.int64), g.to_dev(off, torch.int64), g.to_dev(grad, torch.float32)
+            plan = tt.tt_index_reorder(table, d_idx, d_off) if planned else None
+            out = tt.tt_emb_bag_forward(table, plan, d_idx, d_off)
+            dg = tt.tt_emb_bag_backward(table, plan, d_idx, d_off, d_g)
+            tt.tt_core_sgd_update(table, plan, dg, lr)
+            singles.append((out, dg, table.cores))
+            tables_b.append(g.gpu_table(shape, cores))
+            idxs.append(d_idx); offs.append(d_off); grads.append(d_g)
+        T = len(specs)
+        desc = tt.alloc_batch_desc(T)
+        plans = [None] * T
+        if planned:
+            ws = [tt.alloc_workspace(tables_b[t], idxs[t].numel(), offs[t].numel() - 1) for t in range(T)]
+            plans = tt.tt_index_reorder_batched(tables_b, idxs, offs, ws, desc)
+        outs = [torch.empty((offs[t].numel() - 1, tables_b[t].dim), dtype=torch.float32, device="cuda") for t in range(T)]
+        dcs = [tables_b[t].core_grads_like() for t in range(T)]
+        tt.tt_emb_bag_forward_batched(tables_b, plans, idxs, offs, outs, desc)
+        tt.tt_emb_bag_backward_batched(tables_b, plans, idxs, offs, grads, dcs, desc)
+        tt.tt_core_sgd_update_batched(tables_b, plans, dcs, lr, desc)
+        torch.cuda.synchronize()
+        for t in range(T):
+            if planned:
+                assert tt.tt_plan_status(plans[t]) == 0
+                assert torch.equal(outs[t], singles[t][0]), "forward differs for table %d" % t
+                for k in range(3):
+                    assert torch.equal(dcs[t][k], singles[t][1][k]), "dG%d differs for table %d" % (k + 1, t)
+                    assert torch.equal(tables_b[t].cores[k], singles[t][2][k])
+            else:  # naive backward uses float atomics: compare to tolerance
+                assert torch.equal(outs[t], singles[t][0])
+                for k in range(3):
+                    ref = singles[t][1][k]
+                    assert (dcs[t][k] - ref).abs().max() <= 1e-4 * ref.abs().max() + 1e-30
