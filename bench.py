@@ -34,6 +34,9 @@ def parse_args():
     ap.add_argument("--tables", type=int, default=0, help="use only the first T tables (0 = all)")
     ap.add_argument("--streams", type=int, default=1,
                     help="tables are dealt round-robin to this many (compute, reorder) stream pairs")
+    ap.add_argument("--separate-update", action="store_true",
+                    help="backward writes the core gradients and a separate call applies them "
+                         "(default: the fused backward+update call)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--prof-kernel", default="auto",
                     choices=["auto", "fwd_contract", "bwd_contract", "bag_sum", "grad_merge"],
@@ -123,7 +126,10 @@ def main():
                 plan = T["plans"][buf] if planned else None
                 if do_fwd:
                     tt.tt_emb_bag_forward(T["table"], plan, x["idx"], x["off"], out=T["out"], stream=cs[k])
-                if do_bwd:
+                if do_bwd and planned and not args.separate_update:
+                    tt.tt_emb_bag_backward_sgd(T["table"], plan, x["idx"], x["off"], x["grad"], cfg.lr,
+                                               stream=cs[k])
+                elif do_bwd:
                     tt.tt_emb_bag_backward(T["table"], plan, x["idx"], x["off"], x["grad"], dcores=T["dcores"],
                                            stream=cs[k])
                     tt.tt_core_sgd_update(T["table"], plan, T["dcores"], cfg.lr, stream=cs[k])
@@ -192,6 +198,8 @@ def main():
 
     value = lookups / dt
     phases = "reorder||fwd" if not do_bwd else "reorder||fwd+bwd+update"
+    if do_bwd and planned and not args.separate_update:
+        phases += " (update fused into bwd)"
     result = {
         "metric": "TT embedding lookups/sec fwd+bwd (1 GPU)", "value": value, "unit": "lookups/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -264,8 +272,8 @@ def read_traffic(workload, kernel):
 
 def cpu_baseline(cfg, wl, np):
     """The oracle (definition mode, forward + backward) timed on a bounded sample of the workload:
-    whole batches of the largest tables until the sample holds at least 10 s of CPU work (about
-    30 s at most), or a prefix of one batch when a single batch already takes longer."""
+    batches of the largest tables, one after the other, until the sample holds at least 10 s of CPU
+    work; a batch that would not fit into a budget of about 25 s is cut to a prefix of its bags."""
     from oracle import tt_oracle as ora
     order = list(np.argsort([-t.num_rows for t in cfg.tables]))
 
@@ -279,22 +287,22 @@ def cpu_baseline(cfg, wl, np):
         return len(idx), time.perf_counter() - t0
 
     run(order[0], min(cfg.batch, 64))  # thread start-up and page faults stay out of the measurement
-    n_probe, t_probe = run(order[0], min(cfg.batch, 512))
-    per_batch = t_probe * cfg.batch / max(1, min(cfg.batch, 512))
+    probe_bags = min(cfg.batch, 2048)
+    n, t = run(order[0], probe_bags)
+    rate, mean_len = n / t, n / probe_bags   # lookups/s of the last run; lookups per bag
     total_n, total_t, used = 0, 0.0, []
-    if per_batch > 25.0:  # one batch is already too long: time a prefix of its bags
-        nb = max(64, int(cfg.batch * 15.0 / per_batch))
-        total_n, total_t = run(order[0], nb)
-        used.append("first %d bags of table %d" % (nb, order[0]))
-    else:
-        for tab in order:
-            n, t = run(tab, cfg.batch)
-            total_n += n
-            total_t += t
-            used.append(int(tab))
-            if total_t >= 10.0:
-                break
-        used = ["whole batches of tables %s" % used]
+    for tab in order:
+        if total_t >= 10.0:
+            break
+        # whole batch if it fits into what is left of a ~25 s budget at the last measured rate
+        fit = int(rate * (25.0 - total_t) / mean_len)
+        nb = min(cfg.batch, max(64, fit))
+        n, t = run(tab, nb)
+        total_n += n
+        total_t += t
+        rate = n / t
+        used.append("table %d: %s" % (tab, "whole batch" if nb == cfg.batch else "first %d bags" % nb))
+    used = ["; ".join(used)]
     return {"value": total_n / total_t, "unit": "lookups/s", "cores": ora.max_threads(), "kind": "oracle",
             "sample": "definition-mode forward+backward, %s (%d lookups), %.1f s" % (used[0], total_n, total_t)}
 

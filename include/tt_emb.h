@@ -190,6 +190,21 @@ tt_status tt_core_sgd_update(const tt_table *table, const tt_plan *plan,
                              const float *const dcore[3], float lr, void *stream);
 
 /*
+ * Backward with the core update fused in (Section III-F, fused TT-core update): the same
+ * gradients as tt_emb_bag_backward with a plan, but every gradient slice is applied as
+ * G_k <- G_k - lr * dG_k at the point where its reduction completes (the workgroup that holds the
+ * finished core-1 strip in registers, the final step of the segmented sums for cores 0 and 2), so
+ * no core-shaped gradient is written to or re-read from memory and the separate update launch
+ * disappears.  The cores end up bitwise equal to tt_emb_bag_backward followed by
+ * tt_core_sgd_update on the same plan; all contractions use the pre-update cores.
+ *   plan     required (the naive arm accumulates with atomics and has no completion point);
+ *   table->core[k] are updated IN PLACE; no gradient is returned.
+ */
+tt_status tt_emb_bag_backward_sgd(const tt_table *table, const tt_plan *plan, const int64_t *indices,
+                                  const int64_t *offsets, int64_t nnz, int64_t num_bags,
+                                  const float *grad_out, float lr, void *stream);
+
+/*
  * Batched calls: the same four operations for several tables with ONE launch per kernel, so that
  * small tables share the chip with large ones and the host enqueues dozens, not thousands, of
  * launches per step.  All tables of a call must share d[] and r[] (n[] may differ) and must all

@@ -115,7 +115,7 @@ bool batch_ok(int64_t nnz, int64_t num_bags) {
 void fill_dev(TTDev *d, const TTShape &sh, const tt_table *t, const tt_plan *plan,
               const int64_t *indices, const int64_t *offsets, int64_t nnz, int64_t num_bags,
               const int64_t *remap, float *out, const float *grad_out, float *const dcore[3],
-              float lr) {
+              float lr, bool fused) {
   memset(d, 0, sizeof(*d));
   d->sh = sh;
   for (int k = 0; k < 3; ++k) {
@@ -132,9 +132,10 @@ void fill_dev(TTDev *d, const TTShape &sh, const tt_table *t, const tt_plan *pla
   d->sort_tiles = tt_ceil_div(nnz, TT_SORT_TILE);
   d->strips = ttk_mfma_strips(sh);
   d->lr = lr;
+  d->fused = fused ? 1 : 0;
 }
 
-enum BatchOp { OP_REORDER, OP_FORWARD, OP_BACKWARD, OP_SGD };
+enum BatchOp { OP_REORDER, OP_FORWARD, OP_BACKWARD, OP_SGD, OP_BACKWARD_SGD };
 
 // Validates one item of a call and fills its descriptor (and, for reorder, its plan).
 tt_status prepare_item(BatchOp op, const tt_batch_item *it, float lr, TTDev *d) {
@@ -164,12 +165,15 @@ tt_status prepare_item(BatchOp op, const tt_batch_item *it, float lr, TTDev *d) 
       if (!it->offsets || !it->dcore[0] || !it->dcore[1] || !it->dcore[2]) return TT_ERR_INVALID_ARG;
       if (num_bags > 0 && !it->grad_out) return TT_ERR_INVALID_ARG;
       if (!it->plan && nnz > 0 && !it->indices) return TT_ERR_INVALID_ARG;
+    } else if (op == OP_BACKWARD_SGD) {
+      // the fused update lives in the sorted reductions, which only the planned arm has
+      if (!it->plan || !it->offsets || (num_bags > 0 && !it->grad_out)) return TT_ERR_INVALID_ARG;
     } else {
       if (!it->dcore[0] || !it->dcore[1] || !it->dcore[2]) return TT_ERR_INVALID_ARG;
     }
   }
   fill_dev(d, sh, it->table, it->plan, it->indices, it->offsets, nnz, num_bags, it->remap, it->out,
-           it->grad_out, it->dcore, lr);
+           it->grad_out, op == OP_BACKWARD_SGD ? nullptr : it->dcore, lr, op == OP_BACKWARD_SGD);
   return TT_OK;
 }
 
@@ -178,6 +182,7 @@ tt_status dispatch(BatchOp op, const TTBatch &b, bool planned, hipStream_t s) {
     case OP_REORDER: return ttk_reorder(b, s);
     case OP_FORWARD: return planned ? ttk_forward_plan(b, s) : ttk_forward_naive(b, s);
     case OP_BACKWARD: return planned ? ttk_backward_plan(b, s) : ttk_backward_naive(b, s);
+    case OP_BACKWARD_SGD: return ttk_backward_plan(b, s);
     case OP_SGD: return ttk_sgd(b, planned, s);
   }
   return TT_ERR_INVALID_ARG;
@@ -288,6 +293,16 @@ tt_status tt_emb_bag_backward(const tt_table *table, const tt_plan *plan, const 
   it.nnz = nnz; it.num_bags = num_bags; it.grad_out = grad_out;
   for (int k = 0; k < 3; ++k) it.dcore[k] = dcore[k];
   return run_single(OP_BACKWARD, &it, 0.f, (hipStream_t)stream);
+}
+
+tt_status tt_emb_bag_backward_sgd(const tt_table *table, const tt_plan *plan, const int64_t *indices,
+                                  const int64_t *offsets, int64_t nnz, int64_t num_bags,
+                                  const float *grad_out, float lr, void *stream) {
+  tt_batch_item it;
+  memset(&it, 0, sizeof(it));
+  it.table = table; it.plan = const_cast<tt_plan *>(plan); it.indices = indices; it.offsets = offsets;
+  it.nnz = nnz; it.num_bags = num_bags; it.grad_out = grad_out;
+  return run_single(OP_BACKWARD_SGD, &it, lr, (hipStream_t)stream);
 }
 
 tt_status tt_core_sgd_update(const tt_table *table, const tt_plan *plan,

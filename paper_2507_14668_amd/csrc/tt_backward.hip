@@ -43,6 +43,14 @@ struct Vec {
     if (VEC == 4) *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1 % VEC], v[2 % VEC], v[3 % VEC]);
     else *p = v[0];
   }
+  // p <- p - lr * v   (the fused core update: the finished gradient slice is never stored)
+  __device__ __forceinline__ void store_sgd(float *p, float lr) const {
+    Vec old;
+    old.load(p);
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) old.v[k] = fmaf(-lr, v[k], old.v[k]);
+    old.store(p);
+  }
   __device__ __forceinline__ void add(const Vec &o) {
 #pragma unroll
     for (int k = 0; k < VEC; ++k) v[k] += o.v[k];
@@ -70,10 +78,13 @@ struct SegView {
   int nseg;                  // number of segments (output layout / dense zero fill)
   int dense;
   float *partial;
+  int fused;                 // out is the core itself: finished sums are applied as out -= lr * sum
+  float lr;
 };
 __device__ __forceinline__ SegView seg_view(const TTDev &d, int kind) {
   SegView v;
   v.partial = d.plan.partial;
+  v.fused = 0; v.lr = d.lr;
   if (kind == SEG_GAGG) {  // merge grad_out over the occurrences of each distinct row
     v.W = d.sh.D; v.count_ptr = d.plan.counts + 2; v.seg_src = d.plan.slot_of_sorted; v.seg_div = 1;
     v.gidx = d.plan.bag_of_sorted; v.seg_off = d.plan.row_seg; v.src = d.grad_out; v.nsub = 1;
@@ -82,10 +93,12 @@ __device__ __forceinline__ SegView seg_view(const TTDev &d, int kind) {
     v.W = d.sh.S3; v.count_ptr = d.plan.counts + 0; v.seg_src = d.plan.i3_of_sorted; v.seg_div = 1;
     v.gidx = d.plan.rows_by_i3; v.seg_off = d.plan.i3_seg; v.src = d.plan.t3buf; v.nsub = d.strips;
     v.out = d.dg[2]; v.out_inner = d.sh.d3; v.nseg = d.sh.n3; v.dense = 1;
+    if (d.fused) { v.out = const_cast<float *>(d.g[2]); v.dense = 0; v.fused = 1; }
   } else {  // core 0: per-prefix contributions of all prefixes sharing i1 (contiguous)
     v.W = d.sh.S1; v.count_ptr = d.plan.counts + 1; v.seg_src = d.plan.uniq_pref; v.seg_div = d.sh.n2;
     v.gidx = nullptr; v.seg_off = d.plan.i1_seg; v.src = d.plan.t1buf; v.nsub = d.strips;
     v.out = d.dg[0]; v.out_inner = d.sh.S1; v.nseg = d.sh.n1; v.dense = 1;
+    if (d.fused) { v.out = const_cast<float *>(d.g[0]); v.dense = 0; v.fused = 1; }
   }
   return v;
 }
@@ -101,6 +114,8 @@ k_seg_stage1(TTArg<BATCHED> arg, int kind, int lanes, int chunk) {
   float *__restrict__ out = sv.out, *__restrict__ partial = sv.partial;
   const int M = *sv.count_ptr;
   const int nchunks = (M + chunk - 1) / chunk;
+  const int fused = sv.fused;
+  const float lr = sv.lr;
   const int groups = blockDim.x / lanes, g = threadIdx.x / lanes, lane = threadIdx.x - g * lanes;
   for (int c = blockIdx.x * groups + g; c < nchunks; c += gridDim.x * groups) {
     const int lo = c * chunk, hi = lo + chunk, end = hi < M ? hi : M;
@@ -110,8 +125,10 @@ k_seg_stage1(TTArg<BATCHED> arg, int kind, int lanes, int chunk) {
       int cur = -1;
       auto flush = [&]() {
         const int a = seg_off[cur], b = seg_off[cur + 1];
-        if (a >= lo && b <= hi) acc.store(out + seg_out_index(cur, e, out_inner, nseg));
-        else acc.store(partial + ((size_t)c * 2 + (a < lo ? 0 : 1)) * W + e);
+        if (a >= lo && b <= hi) {
+          float *dst = out + seg_out_index(cur, e, out_inner, nseg);
+          if (fused) acc.store_sgd(dst, lr); else acc.store(dst);
+        } else acc.store(partial + ((size_t)c * 2 + (a < lo ? 0 : 1)) * W + e);
       };
       int pos = lo;
       for (; pos + TT_SEG_UNROLL <= end; pos += TT_SEG_UNROLL) {  // independent gathers in flight,
@@ -218,7 +235,8 @@ k_seg_stage2(TTArg<BATCHED> arg, int kind, int lanes, int chunk) {
         x.load(red + (size_t)k * W + e);
         acc.add(x);
       }
-      acc.store(out + seg_out_index(s, e, out_inner, nseg));
+      float *dst = out + seg_out_index(s, e, out_inner, nseg);
+      if (sv.fused) acc.store_sgd(dst, sv.lr); else acc.store(dst);
     }
   }
 }
@@ -236,7 +254,7 @@ tt_status seg_sum(const TTBatch &b, int kind, int chunk, int prof_kernel, hipStr
     const float *out = kind == SEG_GAGG ? d.plan.gagg : (kind == SEG_DG3 ? d.dg[2] : d.dg[0]);
     vec4 = vec4 && ((uintptr_t)src % 16) == 0 && ((uintptr_t)out % 16) == 0;
     const long long cnt = kind == SEG_GAGG ? d.nnz : (kind == SEG_DG3 ? d.plan.max_rows : d.plan.max_prefixes);
-    const long long nseg = kind == SEG_GAGG ? 0 : (kind == SEG_DG3 ? d.sh.n3 : d.sh.n1);
+    const long long nseg = (kind == SEG_GAGG || d.fused) ? 0 : (kind == SEG_DG3 ? d.sh.n3 : d.sh.n1);
     if (cnt > max_count) max_count = cnt;
     if (nseg > max_seg) max_seg = nseg;
   }
@@ -350,7 +368,9 @@ k_bwd_dg2(TTArg<BATCHED> a, int col_tiles) {
   const float *__restrict__ g1 = d.g[0], *__restrict__ hbuf = d.plan.hbuf;
   const int32_t *__restrict__ uniq_pref = d.plan.uniq_pref, *__restrict__ prefs_by_i2 = d.plan.prefs_by_i2,
                 *__restrict__ i2_seg = d.plan.i2_seg;
-  float *__restrict__ dg2 = d.dg[1];
+  float *__restrict__ dg2 = d.fused ? const_cast<float *>(d.g[1]) : d.dg[1];
+  const int fused = d.fused;
+  const float lr = d.lr;
   // grid.x enumerates (i2, column tile, r1 tile); grid.y is the table in a batched launch
   const int r1_tiles = (sh.R1 + TT_DG2_RT - 1) / TT_DG2_RT;
   if ((int)blockIdx.x >= sh.n2 * col_tiles * r1_tiles) return;
@@ -362,6 +382,7 @@ k_bwd_dg2(TTArg<BATCHED> a, int col_tiles) {
 #pragma unroll
   for (int k = 0; k < TT_DG2_RT; ++k) acc[k] = 0.f;
   const int s0 = i2_seg[i2], s1 = i2_seg[i2 + 1];
+  if (fused && s0 == s1) return;  // untouched slice: nothing to apply
   for (int s = s0; s < s1; ++s) {
     const int q = prefs_by_i2[s], i1 = uniq_pref[q] / sh.n2;
     for (int j1 = 0; j1 < sh.d1; ++j1) {
@@ -374,7 +395,10 @@ k_bwd_dg2(TTArg<BATCHED> a, int col_tiles) {
   }
 #pragma unroll
   for (int k = 0; k < TT_DG2_RT; ++k)
-    if (r1b + k < sh.R1) dg2[((size_t)(r1b + k) * sh.n2 + i2) * sh.S2 + c] = acc[k];
+    if (r1b + k < sh.R1) {
+      float *dst = dg2 + ((size_t)(r1b + k) * sh.n2 + i2) * sh.S2 + c;
+      *dst = fused ? fmaf(-lr, acc[k], *dst) : acc[k];
+    }
 }
 
 // ------------------------------------------------------------------ naive arm
@@ -544,16 +568,17 @@ tt_status ttk_backward_plan(const TTBatch &b, hipStream_t s) {
     TTProfScope prof(&b.host[0].plan, TT_KERNEL_BWD_CONTRACT, s);
     TT_LAUNCH(k_bwd_prefix, blocks, TT_BLOCK, bwd_lds_bytes(sh), s, b);
   }
-  // 3a. core 2: sum the per-row contributions of all rows sharing i3
-  if ((st = seg_sum(b, SEG_DG3, TT_SEG_MIN_CHUNK, -1, s)) != TT_OK) return st;
-  // 3b. core 0: sum the per-prefix contributions of all prefixes sharing i1 (contiguous)
-  if ((st = seg_sum(b, SEG_DG1, TT_SEG_MIN_CHUNK, -1, s)) != TT_OK) return st;
-  // 3c. core 1: per-i2 accumulation over prefixes (done inside the matrix-core kernel)
+  // 3. core 1: per-i2 accumulation over prefixes (inside the matrix-core kernel, else here).  It
+  //    reads core 0, so with the fused update it has to run before the core-0 reduction below.
   if (!mfma) {
     const int col_tiles = tt_ceil_div(sh.S2, TT_BLOCK), r1_tiles = tt_ceil_div(sh.R1, TT_DG2_RT);
     const long long n2max = tt_batch_max(b, [](const TTDev &d) { return (long long)d.sh.n2; });
     TT_LAUNCH(k_bwd_dg2, n2max * col_tiles * r1_tiles, TT_BLOCK, 0, s, b, col_tiles);
   }
+  // 4a. core 2: sum the per-row contributions of all rows sharing i3
+  if ((st = seg_sum(b, SEG_DG3, TT_SEG_MIN_CHUNK, -1, s)) != TT_OK) return st;
+  // 4b. core 0: sum the per-prefix contributions of all prefixes sharing i1 (contiguous)
+  if ((st = seg_sum(b, SEG_DG1, TT_SEG_MIN_CHUNK, -1, s)) != TT_OK) return st;
   return tt_launch_status();
 }
 

@@ -61,13 +61,17 @@ __global__ void __launch_bounds__(TT_BLOCK)
 k_bwd_mfma(TTArg<BATCHED> a) {
   const TTDev &d = a.get();
   const TTShape &sh = d.sh;
-  const float *__restrict__ g1 = d.g[0], *__restrict__ g2 = d.g[1], *__restrict__ g3t = d.plan.g3t;
+  // with the fused update the strip of core 1 this workgroup reads is also the one it rewrites at
+  // the end (no other workgroup touches it), so g2 / dg2 may alias and carry no __restrict__
+  const float *__restrict__ g1 = d.g[0], *g2 = d.g[1], *__restrict__ g3t = d.plan.g3t;
   const int32_t *__restrict__ uniq_pref = d.plan.uniq_pref, *__restrict__ pref_seg = d.plan.pref_seg,
                 *__restrict__ uniq_row = d.plan.uniq_row, *__restrict__ prefs_by_i2 = d.plan.prefs_by_i2,
                 *__restrict__ i2_seg = d.plan.i2_seg;
   const float *__restrict__ gagg = d.plan.gagg;
-  float *__restrict__ t3buf = d.plan.t3buf, *__restrict__ t1buf = d.plan.t1buf,
-        *__restrict__ dg2 = d.dg[1];
+  float *__restrict__ t3buf = d.plan.t3buf, *__restrict__ t1buf = d.plan.t1buf;
+  const int fused = d.fused;
+  const float lr = d.lr;
+  float *dg2 = fused ? const_cast<float *>(d.g[1]) : d.dg[1];
 #ifdef TT_DBG_TIMING
   float *__restrict__ dbg = d.plan.hbuf;
 #endif
@@ -93,6 +97,7 @@ k_bwd_mfma(TTArg<BATCHED> a) {
   const size_t strip_col = (size_t)i2 * G::S2 + strip * 256;  // + r1*n2*S2 + c
 
   if (seg0 == seg1) {  // uniform: no lookup touches this i2, its gradient strip is zero
+    if (fused) return;
     for (int e = threadIdx.x; e < R1 * 256; e += TT_BLOCK)
       dg2[(size_t)(e >> 8) * sh.n2 * G::S2 + strip_col + (e & 255)] = 0.f;
     return;
@@ -461,9 +466,10 @@ k_bwd_mfma(TTArg<BATCHED> a) {
 #pragma unroll
     for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
-      for (int v = 0; v < 4; ++v)
-        dg2[(size_t)(16 * mt + 4 * lq + v) * sh.n2 * G::S2 + strip_col + 64 * wave + 16 * nt + lm] =
-            acc2[mt][nt][v];
+      for (int v = 0; v < 4; ++v) {
+        float *dst = dg2 + (size_t)(16 * mt + 4 * lq + v) * sh.n2 * G::S2 + strip_col + 64 * wave + 16 * nt + lm;
+        *dst = fused ? fmaf(-lr, acc2[mt][nt][v], *dst) : acc2[mt][nt][v];
+      }
 }
 
 template <int R1, int R2, int D2>

@@ -68,6 +68,7 @@ struct TTDev {
   int sort_tiles;          // radix tiles of the main lookup sort (hist row length)
   int strips;              // 256-column strips of a core-1 slice (matrix-core path), else 1
   float lr;
+  int fused;               // backward applies G <- G - lr*dG where each gradient slice is completed
 };
 
 struct TTBatch {

@@ -30,6 +30,19 @@ def gpu_step(g, table, idx, off, grad, naive=False):
     return plan, out, dg
 
 
+def fused_update_check(g, shape, cores, plan, idx, off, grad, lr, updated_table, ref_new, what):
+    """Fused backward + update (Section III-F) on fresh cores: against the oracle's updated cores
+    and bitwise against backward followed by update."""
+    import paper_2507_14668_amd as tt
+    fresh = g.gpu_table(shape, cores)
+    tt.tt_emb_bag_backward_sgd(fresh, plan, g.to_dev(idx, torch.int64), g.to_dev(off, torch.int64),
+                               g.to_dev(grad, torch.float32), lr)
+    torch.cuda.synchronize()
+    g.assert_grads_close(shape, fresh.cores, ref_new, what="%s fused updated G" % what)
+    for k in range(3):
+        assert torch.equal(fresh.cores[k], updated_table.cores[k]), "%s: fused update differs (core %d)" % (what, k)
+
+
 def euler_check(shape, cores, out, dg, grad):
     """<dG_k, G_k> = sum_b <out_b, g_b> for k = 1,2,3 (each row is linear in every core)."""
     o = out.double().cpu().numpy()
@@ -81,6 +94,7 @@ def test_config3_4_full_size(g, ora, tab):
     tt.tt_core_sgd_update(table, plan, dg, cfg.lr)
     torch.cuda.synchronize()
     g.assert_grads_close(shape, table.cores, ref_new, what="cfg4 updated G")
+    fused_update_check(g, shape, cores, plan, idx, off, grad, cfg.lr, table, ref_new, "cfg4")
 
 
 def test_config3_4_other_tables_euler_identity(g):
@@ -121,6 +135,7 @@ def test_config5_full_size_small_mid_large_tables(g, ora):
         tt.tt_core_sgd_update(table, plan, dg, cfg.lr)
         torch.cuda.synchronize()
         g.assert_grads_close(shape, table.cores, ref_new, what="cfg5 updated G")
+        fused_update_check(g, shape, cores, plan, idx, off, grad, cfg.lr, table, ref_new, "cfg5")
 
 
 def test_config5_definition_mode_sample_of_bags(g, ora):

@@ -68,6 +68,12 @@ def run_all(g, ora, shape, cores, idx, off, grad, lr=0.01, check_plan=True, rema
     for k in range(3):
         assert torch.equal(table.cores[k], t2.cores[k]), "touched-slice update differs from dense update"
     g.assert_grads_close(shape, table.cores, ref_new, what="updated G")
+    # fused backward + update (Section III-F): bitwise the same cores as backward followed by update
+    t3 = g.gpu_table(shape, cores)
+    tt.tt_emb_bag_backward_sgd(t3, plan, d_idx, d_off, d_grad, lr)
+    torch.cuda.synchronize()
+    for k in range(3):
+        assert torch.equal(t3.cores[k], table.cores[k]), "fused update differs from backward + update (core %d)" % k
     return plan
 
 
