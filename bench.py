@@ -32,12 +32,18 @@ def parse_args():
     ap.add_argument("--permute", action="store_true", help="seeded random row permutation of the Zipf ranks")
     ap.add_argument("--batches", type=int, default=8, help="distinct batches cycled through")
     ap.add_argument("--tables", type=int, default=0, help="use only the first T tables (0 = all)")
-    ap.add_argument("--streams", type=int, default=1,
+    ap.add_argument("--streams", type=int, default=8,
                     help="tables are dealt round-robin to this many (compute, reorder) stream pairs")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture each step of the timed region (all tables, all stream pairs) in a HIP "
+                         "graph and replay it, so that the host enqueues one graph instead of ~1000 kernels")
     ap.add_argument("--separate-update", action="store_true",
                     help="backward writes the core gradients and a separate call applies them "
                          "(default: the fused backward+update call)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run only a plain device copy of known size (256 MiB read + 256 MiB written, five "
+                         "times): the reference that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     ap.add_argument("--prof-kernel", default="auto",
                     choices=["auto", "fwd_contract", "bwd_contract", "bag_sum", "grad_merge"],
                     help="kernel bracketed with HIP events for the roofline (auto = the dominant one)")
@@ -58,6 +64,17 @@ def main():
     from paper_2507_14668_amd import binding
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.copy_calibration:
+        n = 64 * 1024 * 1024
+        src = torch.arange(n, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": True, "launches": 5, "bytes_read_per_launch": 4 * n,
+                          "bytes_written_per_launch": 4 * n}))
+        return
     tt.load_library()
     cfg_id = int(args.workload[3:])
     cfg = wl.get_config(cfg_id)
@@ -93,105 +110,165 @@ def main():
         prof_name = "bwd_contract" if do_bwd else "fwd_contract"
     prof = tt.Prof(prof_name, (args.steps + 1) * ntab * 4) if args.arm == "plan" else None
 
-    # Stream pairs: table t computes on cs[t % NS] and has the NEXT batch reordered on rs[t % NS]
-    # (all default priority).  Tables on different pairs run concurrently, which fills the chip
-    # when one table's kernels are too small to do so.
-    ns = max(1, min(args.streams, ntab))
-    cs = [torch.cuda.Stream() for _ in range(ns)]
-    rs = cs if args.no_overlap else [torch.cuda.Stream() for _ in range(ns)]
-    ready = [[torch.cuda.Event(), torch.cuda.Event()] for _ in range(ns)]
-    free = [[torch.cuda.Event(), torch.cuda.Event()] for _ in range(ns)]
     planned = args.arm == "plan"
-    groups = [[T for i, T in enumerate(tabs) if i % ns == k] for k in range(ns)]
 
-    def reorder(b):
-        buf = b % 2
-        for k in range(ns):
-            for T in groups[k]:
-                x = T["batches"][b % nbatch]
-                # workspace sized for the largest batch; the plan is rebuilt for this batch's nnz
-                T["plans"][buf] = tt.tt_index_reorder(T["table"], x["idx"], x["off"], workspace=T["ws"][buf],
-                                                      stream=rs[k])
-                if timing[0]:
-                    prof.attach(T["plans"][buf])
-            ready[k][buf].record(rs[k])
+    def run_region(ns, warmup, steps, bracket, use_graph=False):
+        """`warmup` untimed and `steps` timed steps with `ns` stream pairs: table t computes on
+        cs[t % ns] and has the NEXT batch reordered on rs[t % ns] (all default priority).  Tables
+        on different pairs run concurrently, which fills the chip when one table's kernels are too
+        small to do so.  With `bracket`, the selected kernel of every launch in the timed steps is
+        bracketed with HIP events on its launch stream."""
+        cs = [torch.cuda.Stream() for _ in range(ns)]
+        rs = cs if args.no_overlap else [torch.cuda.Stream() for _ in range(ns)]
+        ready = [[torch.cuda.Event(), torch.cuda.Event()] for _ in range(ns)]
+        free = [[torch.cuda.Event(), torch.cuda.Event()] for _ in range(ns)]
+        groups = [[T for i, T in enumerate(tabs) if i % ns == k] for k in range(ns)]
+        timing = [False]
 
-    def compute(b):
-        buf = b % 2
-        for k in range(ns):
-            if planned:
-                cs[k].wait_event(ready[k][buf])
-            for T in groups[k]:
-                x = T["batches"][b % nbatch]
-                plan = T["plans"][buf] if planned else None
-                if do_fwd:
-                    tt.tt_emb_bag_forward(T["table"], plan, x["idx"], x["off"], out=T["out"], stream=cs[k])
-                if do_bwd and planned and not args.separate_update:
-                    tt.tt_emb_bag_backward_sgd(T["table"], plan, x["idx"], x["off"], x["grad"], cfg.lr,
-                                               stream=cs[k])
-                elif do_bwd:
-                    tt.tt_emb_bag_backward(T["table"], plan, x["idx"], x["off"], x["grad"], dcores=T["dcores"],
-                                           stream=cs[k])
-                    tt.tt_core_sgd_update(T["table"], plan, T["dcores"], cfg.lr, stream=cs[k])
-            free[k][buf].record(cs[k])
-
-    timing = [False]
-
-    def step(b):
-        """reorder(b+1) on the reorder streams while batch b computes; plan buffer (b+1)%2 was last
-        used by the compute of batch b-1."""
-        if planned:
+        def reorder(b, events=True):
+            buf = b % 2
             for k in range(ns):
-                rs[k].wait_event(free[k][(b + 1) % 2])
-            reorder(b + 1)
-        compute(b)
+                for T in groups[k]:
+                    x = T["batches"][b % nbatch]
+                    # workspace sized for the largest batch; the plan is rebuilt for this batch's nnz
+                    T["plans"][buf] = tt.tt_index_reorder(T["table"], x["idx"], x["off"], workspace=T["ws"][buf],
+                                                          stream=rs[k])
+                    if timing[0]:
+                        prof.attach(T["plans"][buf])
+                if events:
+                    ready[k][buf].record(rs[k])
 
-    # prologue: plan of batch 0, both 'free' events recorded so the first waits pass
-    for k in range(ns):
-        free[k][0].record(cs[k])
-        free[k][1].record(cs[k])
-    if planned:
-        reorder(0)
-    b = 0
-    for _ in range(args.warmup):
-        step(b)
-        b += 1
-    torch.cuda.synchronize()
-    lookups = 0
-    if planned:  # bracket the selected kernel of every launch made inside the timed region
-        timing[0] = True
-        for T in tabs:
-            prof.attach(T["plans"][b % 2])
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step(b)
-        lookups += sum(T["batches"][b % nbatch]["nnz"] for T in tabs)
-        b += 1
-    t_enqueue = time.perf_counter() - t0  # host time spent enqueueing (GPU may still be running)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    roofline = None
-    if planned:
-        kernel_ms, launches = prof.collect()
-        first = b - args.steps
-        work = 0.0
-        for k in range(args.steps):
+        def compute(b, events=True):
+            buf = b % 2
+            for k in range(ns):
+                if planned and events:
+                    cs[k].wait_event(ready[k][buf])
+                for T in groups[k]:
+                    x = T["batches"][b % nbatch]
+                    plan = T["plans"][buf] if planned else None
+                    if do_fwd:
+                        tt.tt_emb_bag_forward(T["table"], plan, x["idx"], x["off"], out=T["out"], stream=cs[k])
+                    if do_bwd and planned and not args.separate_update:
+                        tt.tt_emb_bag_backward_sgd(T["table"], plan, x["idx"], x["off"], x["grad"], cfg.lr,
+                                                   stream=cs[k])
+                    elif do_bwd:
+                        tt.tt_emb_bag_backward(T["table"], plan, x["idx"], x["off"], x["grad"], dcores=T["dcores"],
+                                               stream=cs[k])
+                        tt.tt_core_sgd_update(T["table"], plan, T["dcores"], cfg.lr, stream=cs[k])
+                if events:
+                    free[k][buf].record(cs[k])
+
+        def step(b):
+            """reorder(b+1) on the reorder streams while batch b computes; plan buffer (b+1)%2 was
+            last used by the compute of batch b-1."""
+            if planned:
+                for k in range(ns):
+                    rs[k].wait_event(free[k][(b + 1) % 2])
+                reorder(b + 1)
+            compute(b)
+
+        def capture(b):
+            """One step as a HIP graph: the capture stream forks into every stream pair, reorder(b+1)
+            and compute(b) are recorded without cross-step events (consecutive replays on one stream
+            are ordered as a whole, and inside a step the two do not depend on each other), and all
+            streams join again.  The library allocates nothing and records no memset."""
+            g = torch.cuda.CUDAGraph()
+            cap = torch.cuda.Stream()
+            with torch.cuda.graph(g, stream=cap):
+                for st in set(cs) | set(rs):
+                    st.wait_stream(cap)
+                if planned:
+                    reorder(b + 1, events=False)
+                compute(b, events=False)
+                for st in set(cs) | set(rs):
+                    cap.wait_stream(st)
+            return g
+
+        graphs = None
+        if use_graph:
+            assert not bracket, "kernel brackets are HIP events and cannot be replayed from a graph"
+            if planned:
+                reorder(0)  # one eager step first: module load and launch attributes precede any capture
+            step(0)
+            torch.cuda.synchronize()
+            if planned:
+                reorder(0, events=False)
+            torch.cuda.synchronize()
+            graphs = [capture(i) for i in range(nbatch)]
+            replay_stream = torch.cuda.Stream()
+
+            def step(b):  # noqa: F811 - the captured step replaces the eager one
+                with torch.cuda.stream(replay_stream):
+                    graphs[b % nbatch].replay()
+
+        # prologue: plan of batch 0, both 'free' events recorded so the first waits pass
+        torch.cuda.synchronize()
+        for k in range(ns):
+            free[k][0].record(cs[k])
+            free[k][1].record(cs[k])
+        if planned and not use_graph:
+            reorder(0)
+        b = 0
+        for _ in range(warmup):
+            step(b)
+            b += 1
+        torch.cuda.synchronize()
+        lookups = 0
+        if planned and bracket:
+            timing[0] = True
             for T in tabs:
-                work += kernel_work(prof_name, T["shape"], T["batches"][(first + k) % nbatch], cfg.batch)
-        bound, unit, peak, scale = KERNEL_BOUND[prof_name]
-        if launches > 0 and kernel_ms > 0:
-            achieved = work / (kernel_ms * 1e-3) / scale
-            roofline = {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
-                        "frac": achieved / peak, "traffic": read_traffic(args.workload, prof_name),
-                        "kernel": prof_name, "launches": int(launches),
-                        "avg_launch_us": 1e3 * kernel_ms / launches,
-                        "algorithmic_work_per_launch": work / launches}
+                prof.attach(T["plans"][b % 2])
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step(b)
+            lookups += sum(T["batches"][b % nbatch]["nnz"] for T in tabs)
+            b += 1
+        t_enqueue = time.perf_counter() - t0  # host time spent enqueueing (GPU may still be running)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        res = dict(dt=dt, t_enqueue=t_enqueue, lookups=lookups, last_b=b, roofline=None)
+        if planned and bracket:
+            kernel_ms, launches = prof.collect()
+            for T in tabs:  # later regions must not record into the same event pool
+                for pl in T["plans"]:
+                    if pl is not None:
+                        pl.c.prof = None
+            first = b - steps
+            work = 0.0
+            for k in range(steps):
+                for T in tabs:
+                    work += kernel_work(prof_name, T["shape"], T["batches"][(first + k) % nbatch], cfg.batch)
+            bound, unit, peak, scale = KERNEL_BOUND[prof_name]
+            if launches > 0 and kernel_ms > 0:
+                achieved = work / (kernel_ms * 1e-3) / scale
+                res["roofline"] = {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
+                                   "frac": achieved / peak, "traffic": read_traffic(args.workload, prof_name),
+                                   "kernel": prof_name, "launches": int(launches),
+                                   "avg_launch_us": 1e3 * kernel_ms / launches,
+                                   "algorithmic_work_per_launch": work / launches,
+                                   "stream_pairs": ns}
+        return res
+
+    # Timed region: K steps of the whole job on `--streams` stream pairs -> value.  With more than
+    # one pair the kernels of different tables overlap and a bracketed kernel's duration includes
+    # contention, so the roofline of the dominant kernel is then taken from a second timed pass of
+    # the same K steps on ONE pair, where the bracketed kernel has the chip to itself (this is also
+    # the condition under which a rocprofv3 kernel trace, which serialises dispatches, sees it).
+    ns = max(1, min(args.streams, ntab))
+    solo_main = ns == 1 and not args.graph
+    main_region = run_region(ns, args.warmup, args.steps, bracket=solo_main, use_graph=args.graph)
+    solo_region = main_region if solo_main else (run_region(1, 1, args.steps, bracket=True) if planned else None)
+    dt, t_enqueue, lookups, b = main_region["dt"], main_region["t_enqueue"], main_region["lookups"], main_region["last_b"]
+    roofline = solo_region["roofline"] if solo_region else None
+    if roofline is not None and not solo_main:
+        roofline["measured_in"] = "second timed pass of the same %d steps on 1 stream pair (%.3f ms/step)" % (
+            args.steps, 1e3 * solo_region["dt"] / args.steps)
 
     status_bad = 0
     counts = []
     if planned:
         for T in tabs:
-            c, st = T["plans"][(b - 1) % 2].counts()
+            c, st = T["plans"][((solo_region or main_region)["last_b"] - 1) % 2].counts()
             status_bad |= st != 0
             counts.append(c)
     assert not status_bad, "a plan reported an index/offset error"
@@ -213,6 +290,7 @@ def main():
                                 phases, args.arm),
                    "lookups_per_step": lookups // max(1, args.steps), "tables": ntab,
                    "overlap_second_stream": (not args.no_overlap) and planned, "stream_pairs": ns,
+                   "hip_graph_replay": bool(args.graph),
                    "host_enqueue_ms_per_step": round(1e3 * t_enqueue / args.steps, 3),
                    "input_generation_s": round(t_gen, 1)},
         "roofline": roofline,
