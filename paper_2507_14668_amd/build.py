@@ -11,7 +11,8 @@ LIB = os.path.join(PKG, "libtt_emb.so")
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared", "-munsafe-fp-atomics",
-    # keep the compiler from forming packed-fp32 instructions (build flags)
+    # keep the compiler from forming packed-fp32 instructions (some of their forms have given wrong
+    # results on this hardware); hipcc's host pass warns that it does not know the feature, harmlessly
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function",
 ]

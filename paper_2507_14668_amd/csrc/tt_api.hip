@@ -130,7 +130,8 @@ void fill_dev(TTDev *d, const TTShape &sh, const tt_table *t, const tt_plan *pla
   d->grad_out = grad_out; d->out = out;
   d->nnz = (int)nnz; d->num_bags = (int)num_bags;
   d->sort_tiles = tt_ceil_div(nnz, TT_SORT_TILE);
-  d->strips = ttk_mfma_strips(sh);
+  d->mfma = ttk_mfma_selected(sh, t->core[1]) ? 1 : 0;
+  d->strips = d->mfma ? ttk_mfma_strips(sh) : 1;
   d->lr = lr;
   d->fused = fused ? 1 : 0;
 }

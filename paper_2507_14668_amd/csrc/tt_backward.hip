@@ -559,7 +559,7 @@ tt_status ttk_backward_plan(const TTBatch &b, hipStream_t s) {
   // 1. merge output gradients per distinct row
   if ((st = seg_sum(b, SEG_GAGG, 32, TT_KERNEL_GRAD_MERGE, s)) != TT_OK) return st;
   // 2. per-prefix contractions
-  const bool mfma = tt_mfma_enabled() && ttk_forward_mfma_supported(sh);
+  const bool mfma = ttk_batch_mfma(b);
   const long long max_pref = tt_batch_max(b, [](const TTDev &d) { return (long long)d.plan.max_prefixes; });
   if (mfma) {
     if ((st = ttk_backward_mfma(b, s)) != TT_OK) return st;

@@ -50,6 +50,8 @@ struct BwdGeom {
   static constexpr int OFF_G3S = OFF_GS + 32 * GS;
   static constexpr size_t LDS_FLOATS = (size_t)OFF_G3S + 32 * G3S;
   static_assert(256 % R2 == 0 && D2 % JW == 0 && R1 % 16 == 0 && R2 % 16 == 0 && CC % 16 == 0, "shape");
+  static constexpr int SW = 68;            // row stride of the strip staging tile [R1][64 columns] of a wavefront
+  static_assert(4 * R1 * SW <= 32 * HS + TT_MP * PS, "the strip staging tiles alias the H and P12 areas");
   static_assert(4 * 32 * R1 <= TT_MP * PS, "T1 partials alias the P12 area");
   static_assert(TT_MP == 8, "chunk geometry: two 16-row tiles of (prefix, j1) rows");
 };
@@ -173,21 +175,30 @@ k_bwd_mfma(TTArg<BATCHED> a) {
   __syncthreads();
   fetch_chunk(0);
 
-  // both register views of this wave's 64 columns of the strip (requested after the first chunk's
-  // plan entries so that they are in flight while the chunk is staged)
+  // Both register views of this wave's 64 columns of the strip.  The strip is read from memory
+  // once, as whole 256-byte rows (float4 per lane), into a staging tile that aliases the H / P12
+  // areas (not yet in use), and the two operand layouts are then picked out of LDS.
   float breg[G::KS1][4];       // F1: B[k = r1][n = c]
   float breg2[16][G::NT1];     // T1: B[k = c][n = r1]
+  {
+    float *stg = lds + G::OFF_HS + wave * (R1 * G::SW);
 #pragma unroll
-  for (int ks = 0; ks < G::KS1; ++ks)
+    for (int i = 0; i < R1 / 4; ++i) {
+      const int r1 = 4 * i + lq;
+      const float4 v = *reinterpret_cast<const float4 *>(g2 + (size_t)r1 * sh.n2 * G::S2 + strip_col + 64 * wave + 4 * lm);
+      *reinterpret_cast<float4 *>(stg + r1 * G::SW + 4 * lm) = v;
+    }
+    __syncthreads();
 #pragma unroll
-    for (int nt = 0; nt < 4; ++nt)
-      breg[ks][nt] = g2[(size_t)(4 * ks + lq) * sh.n2 * G::S2 + strip_col + 64 * wave + 16 * nt + lm];
+    for (int ks = 0; ks < G::KS1; ++ks)
 #pragma unroll
-  for (int ks = 0; ks < 16; ++ks)
+      for (int nt = 0; nt < 4; ++nt) breg[ks][nt] = stg[(4 * ks + lq) * G::SW + 16 * nt + lm];
 #pragma unroll
-    for (int nt = 0; nt < G::NT1; ++nt)
-      breg2[ks][nt] = g2[(size_t)(16 * nt + lm) * sh.n2 * G::S2 + strip_col + 64 * wave + 4 * ks + lq];
-
+    for (int ks = 0; ks < 16; ++ks)
+#pragma unroll
+      for (int nt = 0; nt < G::NT1; ++nt) breg2[ks][nt] = stg[(16 * nt + lm) * G::SW + 4 * ks + lq];
+    __syncthreads();  // the staging tiles are dead: H and P12 may be written
+  }
 
   int bi_p = 0, bi_ubase = 0, bi_nrow = 0, bi_last = 0;  // item record written by one thread per item
   float4 rg[G::CC / 8], r3[G::S3 / 32];
@@ -434,11 +445,17 @@ k_bwd_mfma(TTArg<BATCHED> a) {
     if (more) zero_unused_h(cnt_next);  // Hs is free again; only the last chunk of an i2 is partial
     TT_TICK(5)
     // fold the four K-partials of T1 in wave order and store one contribution per prefix
-    for (int e = threadIdx.x; e < 32 * R1; e += TT_BLOCK) {
-      const int row = e / R1, p = row >> 2;
+    for (int e4 = threadIdx.x; e4 < 32 * R1 / 4; e4 += TT_BLOCK) {
+      const int e = 4 * e4, row = e / R1, p = row >> 2;
       if (p < cnt) {
-        const float sum = ((T1s[e] + T1s[32 * R1 + e]) + T1s[2 * 32 * R1 + e]) + T1s[3 * 32 * R1 + e];
-        t1buf[((size_t)s_q[mo + p] * G::NSTRIP + strip) * G::S1 + (row & 3) * R1 + (e - row * R1)] = sum;
+        const float4 x0 = *reinterpret_cast<const float4 *>(T1s + e),
+                     x1 = *reinterpret_cast<const float4 *>(T1s + 32 * R1 + e),
+                     x2 = *reinterpret_cast<const float4 *>(T1s + 2 * 32 * R1 + e),
+                     x3 = *reinterpret_cast<const float4 *>(T1s + 3 * 32 * R1 + e);
+        const float4 sum = make_float4(((x0.x + x1.x) + x2.x) + x3.x, ((x0.y + x1.y) + x2.y) + x3.y,
+                                       ((x0.z + x1.z) + x2.z) + x3.z, ((x0.w + x1.w) + x2.w) + x3.w);
+        *reinterpret_cast<float4 *>(t1buf + ((size_t)s_q[mo + p] * G::NSTRIP + strip) * G::S1 + (row & 3) * R1 +
+                                    (e - row * R1)) = sum;
       }
     }
     if (more && refill) {  // uniform: the staged plan entries are used up, fetch the next 64

@@ -217,7 +217,7 @@ tt_status ttk_forward_plan(const TTBatch &b, hipStream_t s) {
   const TTShape &sh = b.host[0].sh;  // d[] and r[] are common to the batch
   const long long max_pref = tt_batch_max(b, [](const TTDev &d) { return (long long)d.plan.max_prefixes; });
   const long long max_bags = tt_batch_max(b, [](const TTDev &d) { return (long long)d.num_bags; });
-  if (max_pref > 0 && tt_mfma_enabled() && ttk_forward_mfma_supported(sh)) {
+  if (max_pref > 0 && ttk_batch_mfma(b)) {
     tt_status st = ttk_forward_mfma(b, s);
     if (st != TT_OK) return st;
   } else if (max_pref > 0) {

@@ -66,9 +66,10 @@ struct TTDev {
   float *out;
   int nnz, num_bags;
   int sort_tiles;          // radix tiles of the main lookup sort (hist row length)
-  int strips;              // 256-column strips of a core-1 slice (matrix-core path), else 1
+  int strips;              // contributions per row / prefix in t3buf / t1buf: 256-column strips (matrix-core path), else 1
   float lr;
   int fused;               // backward applies G <- G - lr*dG where each gradient slice is completed
+  int mfma;                // served by the matrix-core kernels (shape supported, operands aligned)
 };
 
 struct TTBatch {
@@ -127,6 +128,17 @@ tt_status ttk_backward_mfma(const TTBatch &b, hipStream_t s);
 // true unless the environment variable TT_EMB_NO_MFMA is set (keeps the plain-ALU kernels
 // selectable for comparison runs)
 bool tt_mfma_enabled();
+// the matrix-core kernels serve a table when they are enabled, support its shape and core 1 is
+// 16-byte aligned (they read its rows as float4)
+static inline bool ttk_mfma_selected(const TTShape &sh, const float *core1) {
+  return tt_mfma_enabled() && ttk_forward_mfma_supported(sh) && ((uintptr_t)core1 % 16) == 0;
+}
+// a batch takes the matrix-core kernels only if every table of it does
+static inline bool ttk_batch_mfma(const TTBatch &b) {
+  for (int t = 0; t < b.T; ++t)
+    if (!b.host[t].mfma) return false;
+  return true;
+}
 tt_status ttk_forward_naive(const TTBatch &b, hipStream_t s);
 tt_status ttk_backward_plan(const TTBatch &b, hipStream_t s);
 tt_status ttk_backward_naive(const TTBatch &b, hipStream_t s);
