@@ -241,7 +241,16 @@ k_seg_stage2(TTArg<BATCHED> arg, int kind, int lanes, int chunk) {
   }
 }
 
-// Host side of one segmented sum over every table of the batch.
+// Stage-1 chunk length for `count` positions.  Short chunks give stage 1 more lane groups to hide
+// the gather latency with (65 k positions: 8 beats 32 by 2x); long chunks leave stage 2 fewer
+// partials to fold for the hottest segment (335 k positions with one segment of 60 k: 32 beats 8).
+static int seg_chunk_for(long long count) {
+  int c = TT_SEG_MIN_CHUNK;
+  while (c < TT_SEG_MAX_CHUNK && (long long)c * 2 * 8192 <= count) c *= 2;
+  return c;
+}
+
+// Host side of one segmented sum over every table of the batch (chunk <= 0: chosen from the count).
 tt_status seg_sum(const TTBatch &b, int kind, int chunk, int prof_kernel, hipStream_t s) {
   const TTShape &sh = b.host[0].sh;
   const int W = kind == SEG_GAGG ? sh.D : (kind == SEG_DG3 ? sh.S3 : sh.S1);
@@ -258,15 +267,16 @@ tt_status seg_sum(const TTBatch &b, int kind, int chunk, int prof_kernel, hipStr
     if (cnt > max_count) max_count = cnt;
     if (nseg > max_seg) max_seg = nseg;
   }
+  if (chunk <= 0) chunk = seg_chunk_for(max_count);
   const int vec = vec4 ? 4 : 1;
   int lanes = 1;
   while (lanes < TT_WAVE && lanes * vec < W) lanes <<= 1;
   const int groups = TT_BLOCK / lanes;
   const int nchunks = tt_ceil_div(max_count, chunk);
+  TTProfScope prof(&b.host[0].plan, prof_kernel, s);  // both stages
   if (nchunks > 0) {
     int blocks = tt_ceil_div(nchunks, groups);
     if (blocks > 8192) blocks = 8192;
-    TTProfScope prof(&b.host[0].plan, prof_kernel, s);
     if (vec4) TT_LAUNCH_T(k_seg_stage1, 4, blocks, TT_BLOCK, 0, s, b, kind, lanes, chunk);
     else TT_LAUNCH_T(k_seg_stage1, 1, blocks, TT_BLOCK, 0, s, b, kind, lanes, chunk);
   }
@@ -557,7 +567,7 @@ tt_status ttk_backward_plan(const TTBatch &b, hipStream_t s) {
   const TTShape &sh = b.host[0].sh;
   tt_status st;
   // 1. merge output gradients per distinct row
-  if ((st = seg_sum(b, SEG_GAGG, 32, TT_KERNEL_GRAD_MERGE, s)) != TT_OK) return st;
+  if ((st = seg_sum(b, SEG_GAGG, 0, TT_KERNEL_GRAD_MERGE, s)) != TT_OK) return st;
   // 2. per-prefix contractions
   const bool mfma = ttk_batch_mfma(b);
   const long long max_pref = tt_batch_max(b, [](const TTDev &d) { return (long long)d.plan.max_prefixes; });
@@ -576,9 +586,9 @@ tt_status ttk_backward_plan(const TTBatch &b, hipStream_t s) {
     TT_LAUNCH(k_bwd_dg2, n2max * col_tiles * r1_tiles, TT_BLOCK, 0, s, b, col_tiles);
   }
   // 4a. core 2: sum the per-row contributions of all rows sharing i3
-  if ((st = seg_sum(b, SEG_DG3, TT_SEG_MIN_CHUNK, -1, s)) != TT_OK) return st;
+  if ((st = seg_sum(b, SEG_DG3, 0, -1, s)) != TT_OK) return st;
   // 4b. core 0: sum the per-prefix contributions of all prefixes sharing i1 (contiguous)
-  if ((st = seg_sum(b, SEG_DG1, TT_SEG_MIN_CHUNK, -1, s)) != TT_OK) return st;
+  if ((st = seg_sum(b, SEG_DG1, 0, -1, s)) != TT_OK) return st;
   return tt_launch_status();
 }
 

@@ -156,21 +156,18 @@ k_bwd_mfma(TTArg<BATCHED> a) {
       AsT2[r1 * G::RT + row] = g1n[k];
     }
     s_i3[par][threadIdx.x / TT_I3_STAGE][threadIdx.x % TT_I3_STAGE] = i3n % sh.n3;
-    if (threadIdx.x == 0) {  // quads per prefix of the chunk, running total
-      int run = 0;
-      for (int p = 0; p < TT_MP; ++p) {
-        s_item_off[par][p] = run;
-        if (p < cnt2) run += (s_nr[mo2 + p] + 3) >> 2;
+    if (wave == 0) {  // quads per prefix of the chunk, running total (scan over the first 8 lanes)
+      const int q4 = (lane < TT_MP && lane < cnt2) ? (s_nr[mo2 + lane] + 3) >> 2 : 0;
+      int incl = q4;
+#pragma unroll
+      for (int o = 1; o < TT_MP; o <<= 1) {
+        const int t = __shfl_up(incl, o, TT_WAVE);
+        if (lane >= o) incl += t;
       }
-      s_item_off[par][TT_MP] = run;
+      if (lane < TT_MP) s_item_off[par][lane] = incl - q4;
+      if (lane == TT_MP - 1) s_item_off[par][TT_MP] = incl;
     }
   };
-  auto zero_unused_h = [&](int cnt2) __attribute__((always_inline)) {
-    // rows of the prefixes a partly filled chunk does not have contribute zeros to T1 / dG2
-    for (int e = 4 * cnt2 * 256 + threadIdx.x; e < 32 * 256; e += TT_BLOCK)
-      Hs[(e >> 8) * G::HS + (e & 255)] = 0.f;
-  };
-
   fetch_meta(seg0);
   __syncthreads();
   fetch_chunk(0);
@@ -198,6 +195,10 @@ k_bwd_mfma(TTArg<BATCHED> a) {
 #pragma unroll
       for (int nt = 0; nt < G::NT1; ++nt) breg2[ks][nt] = stg[(16 * nt + lm) * G::SW + 4 * ks + lq];
     __syncthreads();  // the staging tiles are dead: H and P12 may be written
+    // H rows of prefixes a partly filled chunk does not have are multiplied by zero core-0 rows in
+    // dG2; they must hold finite numbers for that: clear H once, later chunks leave finite values
+    for (int e = threadIdx.x; e < 32 * G::HS / 4; e += TT_BLOCK)
+      reinterpret_cast<float4 *>(Hs)[e] = make_float4(0.f, 0.f, 0.f, 0.f);
   }
 
   int bi_p = 0, bi_ubase = 0, bi_nrow = 0, bi_last = 0;  // item record written by one thread per item
@@ -256,7 +257,6 @@ k_bwd_mfma(TTArg<BATCHED> a) {
   };
 
   stage_chunk(0, 0, (seg1 - seg0) < TT_MP ? (seg1 - seg0) : TT_MP);
-  zero_unused_h((seg1 - seg0) < TT_MP ? (seg1 - seg0) : TT_MP);
   int par = 0;  // buffer pair of the current chunk
   __syncthreads();
   issue_batch(0, 0, 0);  // first row batch of the first chunk
@@ -442,7 +442,6 @@ k_bwd_mfma(TTArg<BATCHED> a) {
     }
     __syncthreads();
     TT_TICK(4)
-    if (more) zero_unused_h(cnt_next);  // Hs is free again; only the last chunk of an i2 is partial
     TT_TICK(5)
     // fold the four K-partials of T1 in wave order and store one contribution per prefix
     for (int e4 = threadIdx.x; e4 < 32 * R1 / 4; e4 += TT_BLOCK) {

@@ -34,7 +34,8 @@ struct TTShape {
 #define TT_MP 8  // distinct prefixes per chunk: two 16-row MFMA tiles of (prefix, j1) rows
 
 // ---- segmented-reduction geometry -----------------------------------------------------------
-#define TT_SEG_MIN_CHUNK 16  // smallest stage-1 chunk of the two-stage segmented sum (sizes the partials)
+#define TT_SEG_MIN_CHUNK 8   // smallest stage-1 chunk of the two-stage segmented sum (sizes the partials)
+#define TT_SEG_MAX_CHUNK 64
 #define TT_SEG_UNROLL 8      // gathers a lane group keeps in flight
 
 static inline int tt_ceil_div(long long a, long long b) { return (int)((a + b - 1) / b); }
