@@ -26,7 +26,9 @@ struct TTShape {
 #define TT_BLOCK 256
 
 // ---- radix sort geometry ----------------------------------------------------------------
+#ifndef TT_SORT_ITEMS
 #define TT_SORT_ITEMS 4
+#endif
 #define TT_SORT_TILE (TT_BLOCK * TT_SORT_ITEMS)  // keys per workgroup per pass
 #define TT_SORT_MAX_BITS 10                      // digit width limit (1024 bins)
 

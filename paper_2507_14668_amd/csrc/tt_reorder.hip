@@ -361,29 +361,31 @@ __global__ void k_group_keys(TTArg<BATCHED> a, int a3, int a2) {
   }
 }
 
-__device__ __forceinline__ int lower_bound_div(const int32_t *__restrict__ a, int count, int div,
-                                               int value) {
-  int lo = 0, hi = count;  // first position with a[pos]/div >= value
-  while (lo < hi) {
-    int mid = (lo + hi) >> 1;
-    if (a[mid] / div < value) lo = mid + 1; else hi = mid;
+// seg[t] = first position of the sorted keys whose key is >= t, for t = 0..nkeys: the thread of
+// position u fills the entries between its predecessor's key and its own (one memory round trip
+// per thread instead of a binary search), the thread of the last position also the tail.
+__device__ __forceinline__ void seg_starts(const int32_t *__restrict__ keys, int div, int count, int nkeys,
+                                           int32_t *__restrict__ seg, int u) {
+  if (count == 0) {
+    if (u <= nkeys) seg[u] = 0;
+    return;
   }
-  return lo;
+  if (u >= count) return;
+  const int key = keys[u] / div, prev = u > 0 ? keys[u - 1] / div : -1;
+  for (int t = prev + 1; t <= key; ++t) seg[t] = u;
+  if (u == count - 1)
+    for (int t = key + 1; t <= nkeys; ++t) seg[t] = count;
 }
 
 template <bool BATCHED>
 __global__ void k_seg_bounds(TTArg<BATCHED> a) {
   const TTDev &d = a.get();
-  const int32_t *__restrict__ counts = d.plan.counts, *__restrict__ k3_sorted = d.plan.i3_of_sorted,
-                *__restrict__ k2_sorted = d.tmp.k2, *__restrict__ uniq_pref = d.plan.uniq_pref;
-  int32_t *__restrict__ i3_seg = d.plan.i3_seg, *__restrict__ i2_seg = d.plan.i2_seg,
-          *__restrict__ i1_seg = d.plan.i1_seg;
-  const int n1 = d.sh.n1, n2 = d.sh.n2, n3 = d.sh.n3;
+  const int32_t *__restrict__ counts = d.plan.counts;
   const int ur = counts[0], up = counts[1];
-  const int t = blockIdx.x * blockDim.x + threadIdx.x;
-  if (t <= n3) i3_seg[t] = lower_bound_div(k3_sorted, ur, 1, t);
-  if (t <= n2) i2_seg[t] = lower_bound_div(k2_sorted, up, 1, t);
-  if (t <= n1) i1_seg[t] = lower_bound_div(uniq_pref, up, n2, t);
+  const int u = blockIdx.x * blockDim.x + threadIdx.x;
+  seg_starts(d.plan.i3_of_sorted, 1, ur, d.sh.n3, d.plan.i3_seg, u);
+  seg_starts(d.tmp.k2, 1, up, d.sh.n2, d.plan.i2_seg, u);
+  seg_starts(d.plan.uniq_pref, d.sh.n2, up, d.sh.n1, d.plan.i1_seg, u);
 }
 
 // Running count of TT_MP-prefix chunks per i2 (single workgroup; n2 may exceed the block size).
@@ -517,10 +519,13 @@ tt_status ttk_reorder(const TTBatch &b, hipStream_t s) {
     st = radix_sort(b, 2, tt_ceil_div(max_pref, TT_SORT_TILE), bits2, s);
     if (st != TT_OK) return st;
   }
+  // one thread per sorted position (and at least one per segment boundary when a count is zero)
   const long long nmax = tt_batch_max(b, [](const TTDev &d) {
     long long m = d.sh.n1 > d.sh.n2 ? d.sh.n1 : d.sh.n2;
-    return m > d.sh.n3 ? m : (long long)d.sh.n3; });
-  TT_LAUNCH(k_seg_bounds, tt_ceil_div(nmax + 1, TT_BLOCK), TT_BLOCK, 0, s, b);
+    m = m > d.sh.n3 ? m : (long long)d.sh.n3;
+    m += 1;
+    return m > d.plan.max_rows ? m : (long long)d.plan.max_rows; });
+  TT_LAUNCH(k_seg_bounds, tt_ceil_div(nmax, TT_BLOCK), TT_BLOCK, 0, s, b);
   TT_LAUNCH(k_chunk_offsets, 1, TT_BLOCK, 0, s, b);
   return tt_launch_status();
 }

@@ -1,0 +1,103 @@
+"""The nn.EmbeddingBag-style module: argument checks on the CPU, parity on the GPU (through the
+same C ABI as everything else) against the direct calls, the oracle and a dense EmbeddingBag."""
+import numpy as np
+import pytest
+import torch
+
+import tt_workloads as wl
+
+
+def test_module_argument_checks_and_shapes():
+    import paper_2507_14668_amd as tt
+    m = tt.TTEmbeddingBag(1000, 16, n=(10, 10, 10), d=(2, 2, 4), ranks=(4, 4), device="cpu")
+    assert [p.numel() for p in m.parameters()] == [10 * 2 * 4, 4 * 10 * 2 * 4, 4 * 10 * 4]
+    assert "smaller than dense" in repr(m)
+    with pytest.raises(ValueError):
+        tt.TTEmbeddingBag(1000, 16, n=(10, 10, 9), d=(2, 2, 4), ranks=(4, 4), device="cpu")
+    with pytest.raises(ValueError):
+        tt.TTEmbeddingBag(1000, 15, n=(10, 10, 10), d=(2, 2, 4), ranks=(4, 4), device="cpu")
+    with pytest.raises(NotImplementedError):
+        tt.TTEmbeddingBag(1000, 16, n=(10, 10, 10), d=(2, 2, 4), ranks=(4, 4), mode="mean", device="cpu")
+    with pytest.raises(RuntimeError):  # no CPU path
+        m(torch.zeros(4, dtype=torch.int64), torch.tensor([0, 2]))
+    for rows in (1, 7, 1000, 1001, 12345, 40_000_000):
+        n = tt.TTEmbeddingBag.near_cubic_factors(rows)
+        assert n[0] * n[1] * n[2] >= rows and (n[0] - 1) * n[1] * n[2] < rows and max(n) - min(n) <= max(1, n[2])
+
+
+@pytest.fixture(scope="module")
+def g():
+    import gpu_util
+    assert torch.cuda.is_available()
+    return gpu_util
+
+
+def _module_like(tt, shape, cores, **kw):
+    m = tt.TTEmbeddingBag(shape.num_rows, shape.dim, shape.n, shape.d, shape.r[1:3], **kw)
+    with torch.no_grad():
+        for p, c in zip(m.cores(), cores):
+            p.copy_(torch.from_numpy(np.asarray(c, dtype=np.float32)))
+    return m
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("d,r", [((2, 3, 4), (1, 5, 6, 1)), ((4, 8, 4), (1, 32, 32, 1))])
+def test_module_matches_direct_calls_and_oracle(g, ora, d, r):
+    import paper_2507_14668_amd as tt
+    print("case module d=%s r=%s" % (d, r), flush=True)
+    shape, cores, idx, off, grad = wl.small_random_problem(91, n=(6, 5, 7), d=d, r=r, num_bags=400, max_len=6, sigma=0.2)
+    d_idx, d_off, d_g = g.to_dev(idx, torch.int64), g.to_dev(off, torch.int64), g.to_dev(grad, torch.float32)
+    # direct calls
+    table = g.gpu_table(shape, cores)
+    plan = tt.tt_index_reorder(table, d_idx, d_off)
+    out_ref = tt.tt_emb_bag_forward(table, plan, d_idx, d_off)
+    dg_ref = tt.tt_emb_bag_backward(table, plan, d_idx, d_off, d_g)
+    # module, offsets in both conventions
+    for last in (True, False):
+        m = _module_like(tt, shape, cores, include_last_offset=last)
+        out = m(d_idx, d_off if last else d_off[:-1])
+        assert torch.equal(out, out_ref)
+        out.backward(d_g.view_as(out))
+        for p, ref in zip(m.cores(), dg_ref):
+            assert torch.equal(p.grad, ref)
+    g.assert_close_rows(out.detach().cpu().numpy(), ora.forward(shape, cores, idx, off), g.FWD_RTOL, shape.dim, "module forward")
+    g.assert_grads_close(shape, [p.grad for p in m.cores()], ora.backward(shape, cores, idx, off, grad), what="module dG")
+    # an optimizer step on the module equals the oracle's update
+    lr = 0.05
+    torch.optim.SGD(m.parameters(), lr=lr).step()
+    g.assert_grads_close(shape, [p.detach() for p in m.cores()], ora.sgd(cores, ora.backward(shape, cores, idx, off, grad), lr),
+                         what="module SGD step")
+    # fused mode: cores updated inside backward, bitwise equal to the fused direct call
+    mf = _module_like(tt, shape, cores, include_last_offset=True, fused_sgd_lr=lr)
+    of = mf(d_idx, d_off)
+    of.backward(d_g.view_as(of))
+    t2 = g.gpu_table(shape, cores)
+    tt.tt_emb_bag_backward_sgd(t2, plan, d_idx, d_off, d_g, lr)
+    torch.cuda.synchronize()
+    for p, ref in zip(mf.cores(), t2.cores):
+        assert p.grad is None and torch.equal(p.detach(), ref)
+
+
+@pytest.mark.gpu
+def test_module_two_dimensional_input_against_dense_embedding_bag(g):
+    """2-D input (bags of equal length) and gradients of a downstream loss: the dense table the
+    cores define, fed to torch.nn.functional.embedding_bag on the CPU in float64, must give the
+    same outputs, and autograd through it the same core gradients."""
+    import paper_2507_14668_amd as tt
+    shape, cores, _, _, _ = wl.small_random_problem(92, n=(4, 3, 5), d=(2, 2, 2), r=(1, 3, 2, 1), num_bags=8, max_len=3, sigma=0.5)
+    rng = np.random.default_rng(5)
+    inp = rng.integers(0, shape.num_rows, size=(64, 5))
+    m = _module_like(tt, shape, cores)
+    out = m(torch.from_numpy(inp).cuda())
+    w = torch.from_numpy(rng.standard_normal(out.shape).astype(np.float32)).cuda()
+    (out * w).sum().backward()
+    # dense route in float64
+    c = [torch.tensor(np.asarray(x, dtype=np.float64), requires_grad=True) for x in cores]
+    G1 = c[0].reshape(shape.n[0], shape.d[0], shape.r[1])
+    G2 = c[1].reshape(shape.r[1], shape.n[1], shape.d[1], shape.r[2])
+    G3 = c[2].reshape(shape.r[2], shape.n[2], shape.d[2])
+    W = torch.einsum("iap,pjbq,qkc->ijkabc", G1, G2, G3).reshape(shape.n[0] * shape.n[1] * shape.n[2], shape.dim)
+    ref = torch.nn.functional.embedding_bag(torch.from_numpy(inp), W, mode="sum")
+    (ref * w.cpu().double()).sum().backward()
+    g.assert_close_rows(out.detach().cpu().numpy(), ref.detach().numpy(), g.FWD_RTOL, shape.dim, "module 2-D forward")
+    g.assert_grads_close(shape, [p.grad for p in m.cores()], [x.grad.reshape(-1).numpy() for x in c], what="module 2-D dG")
