@@ -118,6 +118,8 @@ typedef struct {
   float *partial;         /* segmented-reduction partials                                 */
   float *g3t;             /* [n2][r2][d2] slice-contiguous copy of core 2, refreshed by
                              every forward / backward call that uses the matrix-core path  */
+  float *dg2part;         /* [split][core-1 shape] partial core-1 gradients when the backward
+                             workgroups of a table with few core-1 slices are split        */
   void *sort_tmp;         /* radix-sort ping-pong buffers, histograms, scan temporaries   */
   void *prof;             /* HOST, optional tt_prof* attached by the caller (NULL after
                              tt_index_reorder): brackets one kernel with HIP events       */

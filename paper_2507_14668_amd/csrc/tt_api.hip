@@ -93,6 +93,8 @@ size_t layout(const TTShape &sh, int64_t nnz, int64_t num_bags, char *base, tt_p
   if (part1 > part) part = part1;
   q.partial = floats(part);
   q.g3t = floats((size_t)sh.n3 * sh.S3);
+  const int split = ttk_bwd_split(sh);
+  q.dg2part = floats(split > 1 ? (size_t)split * sh.R1 * sh.n2 * sh.S2 : 0);
   q.sort_tmp = take(tt_sort_tmp_bytes(nnz, max_rows, max_pref));
   if (p) *p = q;
   return off;
@@ -132,6 +134,9 @@ void fill_dev(TTDev *d, const TTShape &sh, const tt_table *t, const tt_plan *pla
   d->sort_tiles = tt_ceil_div(nnz, TT_SORT_TILE);
   d->mfma = ttk_mfma_selected(sh, t->core[1]) ? 1 : 0;
   d->strips = d->mfma ? ttk_mfma_strips(sh) : 1;
+  d->bwd_split = d->mfma ? ttk_bwd_split(sh) : 1;
+  // the kernel that sums split partials stores float4: an unaligned gradient buffer is served unsplit
+  if (d->dg[1] && ((uintptr_t)d->dg[1] % 16) != 0) d->bwd_split = 1;
   d->lr = lr;
   d->fused = fused ? 1 : 0;
 }

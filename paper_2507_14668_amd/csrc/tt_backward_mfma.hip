@@ -90,16 +90,30 @@ k_bwd_mfma(TTArg<BATCHED> a) {
   __shared__ int s_q[TT_META], s_i1[TT_META], s_u0[TT_META], s_nr[TT_META];
   __shared__ int s_i3[2][TT_MP][TT_I3_STAGE];
 
-  if ((int)blockIdx.x >= sh.n2 * G::NSTRIP) return;  // a table of the batch with fewer i2 values
-  const int i2 = blockIdx.x / G::NSTRIP, strip = blockIdx.x - i2 * G::NSTRIP;
+  // workgroup = (i2, strip, part): with split > 1 the chunks of one (i2, strip) are dealt in
+  // contiguous runs to `split` workgroups, each of which leaves a partial core-1 gradient
+  const int split = d.bwd_split;
+  if ((int)blockIdx.x >= sh.n2 * G::NSTRIP * split) return;  // a table of the batch with fewer i2 values
+  const int part = blockIdx.x % split, wg = blockIdx.x / split;
+  const int i2 = wg / G::NSTRIP, strip = wg - i2 * G::NSTRIP;
   const int j2base = strip * G::JW;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int lm = lane & 15, lq = lane >> 4;
-  const int seg0 = i2_seg[i2], seg1 = i2_seg[i2 + 1];
+  int seg0 = i2_seg[i2], seg1 = i2_seg[i2 + 1];
+  const bool touched = seg0 != seg1;
+  if (split > 1) {
+    const int nch = (seg1 - seg0 + TT_MP - 1) / TT_MP, per = (nch + split - 1) / split;
+    const int c0 = part * per, c1 = (c0 + per) < nch ? (c0 + per) : nch;
+    const int lo = seg0 + c0 * TT_MP, hi = seg0 + c1 * TT_MP;
+    seg1 = c0 < c1 ? (hi < seg1 ? hi : seg1) : seg0;
+    seg0 = c0 < c1 ? lo : seg0;
+    // partial gradients have the shape of core 1
+    dg2 = d.plan.dg2part + (size_t)part * R1 * sh.n2 * G::S2;
+  }
   const size_t strip_col = (size_t)i2 * G::S2 + strip * 256;  // + r1*n2*S2 + c
 
-  if (seg0 == seg1) {  // uniform: no lookup touches this i2, its gradient strip is zero
-    if (fused) return;
+  if (seg0 == seg1) {  // uniform: no prefix for this workgroup, its gradient strip is zero
+    if ((fused && split == 1) || (split > 1 && !touched)) return;  // nothing will read it
     for (int e = threadIdx.x; e < R1 * 256; e += TT_BLOCK)
       dg2[(size_t)(e >> 8) * sh.n2 * G::S2 + strip_col + (e & 255)] = 0.f;
     return;
@@ -484,8 +498,42 @@ k_bwd_mfma(TTArg<BATCHED> a) {
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
         float *dst = dg2 + (size_t)(16 * mt + 4 * lq + v) * sh.n2 * G::S2 + strip_col + 64 * wave + 16 * nt + lm;
-        *dst = fused ? fmaf(-lr, acc2[mt][nt][v], *dst) : acc2[mt][nt][v];
+        *dst = (fused && split == 1) ? fmaf(-lr, acc2[mt][nt][v], *dst) : acc2[mt][nt][v];
       }
+}
+
+// Sums the partial core-1 gradients of a split table in part order and stores the gradient, or
+// applies the fused update.  One workgroup per (i2, 1024 elements of the slice); a slice no lookup
+// touched is zero (or, fused, left alone).
+template <bool BATCHED>
+__global__ void __launch_bounds__(TT_BLOCK)
+k_dg2_reduce(TTArg<BATCHED> a, int tiles) {
+  const TTDev &d = a.get();
+  const TTShape &sh = d.sh;
+  const int split = d.bwd_split;
+  if (split <= 1 || (int)blockIdx.x >= sh.n2 * tiles) return;
+  const int i2 = blockIdx.x / tiles, tile = blockIdx.x - i2 * tiles;
+  const int e = (tile * TT_BLOCK + threadIdx.x) * 4;  // element of the slice [R1][S2]
+  if (e >= sh.R1 * sh.S2) return;
+  const int r1 = e / sh.S2, c = e - r1 * sh.S2;
+  const size_t at = ((size_t)r1 * sh.n2 + i2) * sh.S2 + c, len = (size_t)sh.R1 * sh.n2 * sh.S2;
+  const bool touched = d.plan.i2_seg[i2] != d.plan.i2_seg[i2 + 1];
+  float *out = d.fused ? const_cast<float *>(d.g[1]) : d.dg[1];
+  if (!touched) {
+    if (!d.fused) *reinterpret_cast<float4 *>(out + at) = make_float4(0.f, 0.f, 0.f, 0.f);
+    return;
+  }
+  float4 sum = *reinterpret_cast<const float4 *>(d.plan.dg2part + at);
+  for (int p = 1; p < split; ++p) {
+    const float4 x = *reinterpret_cast<const float4 *>(d.plan.dg2part + p * len + at);
+    sum.x += x.x; sum.y += x.y; sum.z += x.z; sum.w += x.w;
+  }
+  if (d.fused) {
+    const float4 g = *reinterpret_cast<const float4 *>(out + at);
+    const float lr = d.lr;
+    sum = make_float4(fmaf(-lr, sum.x, g.x), fmaf(-lr, sum.y, g.y), fmaf(-lr, sum.z, g.z), fmaf(-lr, sum.w, g.w));
+  }
+  *reinterpret_cast<float4 *>(out + at) = sum;
 }
 
 template <int R1, int R2, int D2>
@@ -501,7 +549,8 @@ tt_status launch(const TTBatch &b, hipStream_t s) {
       return TT_ERR_HIP;
     configured = true;
   }
-  const long long blocks = tt_batch_max(b, [](const TTDev &d) { return (long long)d.sh.n2 * G::NSTRIP; });
+  const long long blocks = tt_batch_max(b, [](const TTDev &d) {
+    return (long long)d.sh.n2 * G::NSTRIP * d.bwd_split; });
   TTProfScope prof(&b.host[0].plan, TT_KERNEL_BWD_CONTRACT, s);
   if (b.dev)
     hipLaunchKernelGGL((k_bwd_mfma<true, R1, R2, D2>), dim3((unsigned)blocks, (unsigned)b.T),
@@ -509,6 +558,11 @@ tt_status launch(const TTBatch &b, hipStream_t s) {
   else
     hipLaunchKernelGGL((k_bwd_mfma<false, R1, R2, D2>), dim3((unsigned)blocks), dim3(TT_BLOCK), lds, s,
                        TTArg<false>{b.host[0]});
+  if (tt_batch_max(b, [](const TTDev &d) { return (long long)d.bwd_split; }) > 1) {
+    const int tiles = tt_ceil_div((long long)R1 * G::S2, TT_BLOCK * 4);
+    const long long n2max = tt_batch_max(b, [](const TTDev &d) { return (long long)d.sh.n2; });
+    TT_LAUNCH(k_dg2_reduce, n2max * tiles, TT_BLOCK, 0, s, b, tiles);
+  }
   return tt_launch_status();
 }
 
@@ -516,6 +570,14 @@ tt_status launch(const TTBatch &b, hipStream_t s) {
 
 int ttk_mfma_strips(const TTShape &sh) {
   return ttk_forward_mfma_supported(sh) ? (sh.d2 * sh.R2) / 256 : 1;
+}
+
+int ttk_bwd_split(const TTShape &sh) {
+  if (!ttk_forward_mfma_supported(sh)) return 1;
+  const int wgs = sh.n2 * ttk_mfma_strips(sh);
+  if (wgs >= 128) return 1;
+  const int s = 256 / wgs;
+  return s > TT_BWD_MAX_SPLIT ? TT_BWD_MAX_SPLIT : s;
 }
 
 tt_status ttk_backward_mfma(const TTBatch &b, hipStream_t s) {

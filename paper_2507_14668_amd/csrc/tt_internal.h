@@ -73,6 +73,7 @@ struct TTDev {
   float lr;
   int fused;               // backward applies G <- G - lr*dG where each gradient slice is completed
   int mfma;                // served by the matrix-core kernels (shape supported, operands aligned)
+  int bwd_split;           // workgroups that share one (i2, strip) of the backward matrix-core kernel
 };
 
 struct TTBatch {
@@ -127,6 +128,11 @@ tt_status ttk_pack_g3(const TTBatch &b, hipStream_t s);
 // number of 256-column strips a core-1 slice is cut into by the matrix-core kernels (1 when the
 // shape is served by the plain-ALU kernels); t3buf / t1buf hold one contribution per strip
 int ttk_mfma_strips(const TTShape &sh);
+// The backward matrix-core kernel has n2 * strips workgroups; a table with few core-1 slices
+// leaves most of the 256 CUs idle, so the chunks of one (i2, strip) are then dealt to `split`
+// workgroups that write partial core-1 gradients, summed in a fixed order by a second kernel.
+int ttk_bwd_split(const TTShape &sh);
+#define TT_BWD_MAX_SPLIT 8
 tt_status ttk_backward_mfma(const TTBatch &b, hipStream_t s);
 // true unless the environment variable TT_EMB_NO_MFMA is set (keeps the plain-ALU kernels
 // selectable for comparison runs)
