@@ -177,6 +177,9 @@ k_seg_stage1(TTArg<BATCHED> arg, int kind, int lanes, int chunk) {
   }
 }
 
+#ifndef TT_SEG2_UNROLL
+#define TT_SEG2_UNROLL 8  // partials a lane group of stage 2 keeps in flight
+#endif
 // Stage 2: workgroup per chunk.  The chunk in which a multi-chunk segment begins owns it and adds
 // its own slot-1 partial and the slot-0 partials of the following chunks, in chunk order.
 // With `dense`, workgroup c also zero-fills segment c if it is empty.
@@ -211,12 +214,12 @@ k_seg_stage2(TTArg<BATCHED> arg, int kind, int lanes, int chunk) {
     acc.zero();
     if (g < groups) {
       int cc = c + 1 + g;
-      for (; cc + 3 * groups <= c1; cc += 4 * groups) {
-        Vec<VEC> x[4];
+      for (; cc + (TT_SEG2_UNROLL - 1) * groups <= c1; cc += TT_SEG2_UNROLL * groups) {
+        Vec<VEC> x[TT_SEG2_UNROLL];  // independent loads in flight, added in chunk order
 #pragma unroll
-        for (int k = 0; k < 4; ++k) x[k].load(partial + ((size_t)(cc + k * groups) * 2) * W + e);
+        for (int k = 0; k < TT_SEG2_UNROLL; ++k) x[k].load(partial + ((size_t)(cc + k * groups) * 2) * W + e);
 #pragma unroll
-        for (int k = 0; k < 4; ++k) acc.add(x[k]);
+        for (int k = 0; k < TT_SEG2_UNROLL; ++k) acc.add(x[k]);
       }
       for (; cc <= c1; cc += groups) {
         Vec<VEC> x;
