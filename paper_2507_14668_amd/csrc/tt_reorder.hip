@@ -177,15 +177,21 @@ k_radix_scatter(TTArg<BATCHED> a, int which, int in_a, int shift, int bits) {
   }
   __syncthreads();
 
+  // all keys and payloads of the tile are requested before the first round (one memory round
+  // trip for the tile instead of one per round)
+  int keys_r[TT_SORT_ITEMS], vals_r[TT_SORT_ITEMS];
+#pragma unroll
+  for (int i = 0; i < TT_SORT_ITEMS; ++i) {
+    const int pos = base + i * TT_BLOCK + threadIdx.x;
+    keys_r[i] = pos < count ? keys_in[pos] : 0;
+    vals_r[i] = pos < count ? vals_in[pos] : 0;
+  }
+#pragma unroll
   for (int i = 0; i < TT_SORT_ITEMS; ++i) {
     const int pos = base + i * TT_BLOCK + threadIdx.x;
     const bool valid = pos < count;
-    int key = 0, val = 0, digit = 0;
-    if (valid) {
-      key = keys_in[pos];
-      val = vals_in[pos];
-      digit = (key >> shift) & (nbins - 1);
-    }
+    const int key = keys_r[i], val = vals_r[i];
+    const int digit = valid ? (key >> shift) & (nbins - 1) : 0;
     unsigned long long mask = __ballot(valid);
     for (int b = 0; b < bits; ++b) {
       const bool bit = (digit >> b) & 1;
