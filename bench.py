@@ -34,6 +34,8 @@ def parse_args():
     ap.add_argument("--tables", type=int, default=0, help="use only the first T tables (0 = all)")
     ap.add_argument("--streams", type=int, default=8,
                     help="tables are dealt round-robin to this many (compute, reorder) stream pairs")
+    ap.add_argument("--host-threads", type=int, default=4,
+                    help="host threads that enqueue the stream pairs of a step in parallel")
     ap.add_argument("--graph", action="store_true",
                     help="capture each step of the timed region (all tables, all stream pairs) in a HIP "
                          "graph and replay it, so that the host enqueues one graph instead of ~1000 kernels")
@@ -124,6 +126,10 @@ def main():
         free = [[torch.cuda.Event(), torch.cuda.Event()] for _ in range(ns)]
         groups = [[T for i, T in enumerate(tabs) if i % ns == k] for k in range(ns)]
         timing = [False]
+        pool = None
+        if args.host_threads > 1 and ns > 1 and not use_graph and not bracket:
+            from concurrent.futures import ThreadPoolExecutor
+            pool = ThreadPoolExecutor(max_workers=min(args.host_threads, ns))
 
         def reorder(b, events=True):
             buf = b % 2
@@ -161,11 +167,39 @@ def main():
         def step(b):
             """reorder(b+1) on the reorder streams while batch b computes; plan buffer (b+1)%2 was
             last used by the compute of batch b-1."""
+            if pool is not None:  # the stream pairs are independent: enqueue them from several threads
+                list(pool.map(lambda k: step_pair(b, k), range(ns)))
+                return
             if planned:
                 for k in range(ns):
                     rs[k].wait_event(free[k][(b + 1) % 2])
                 reorder(b + 1)
             compute(b)
+
+        def step_pair(b, k):
+            buf, nxt = b % 2, (b + 1) % 2
+            if planned:
+                rs[k].wait_event(free[k][nxt])
+                for T in groups[k]:
+                    x = T["batches"][(b + 1) % nbatch]
+                    T["plans"][nxt] = tt.tt_index_reorder(T["table"], x["idx"], x["off"], workspace=T["ws"][nxt],
+                                                          stream=rs[k])
+                    if timing[0]:
+                        prof.attach(T["plans"][nxt])
+                ready[k][nxt].record(rs[k])
+                cs[k].wait_event(ready[k][buf])
+            for T in groups[k]:
+                x = T["batches"][b % nbatch]
+                plan = T["plans"][buf] if planned else None
+                if do_fwd:
+                    tt.tt_emb_bag_forward(T["table"], plan, x["idx"], x["off"], out=T["out"], stream=cs[k])
+                if do_bwd and planned and not args.separate_update:
+                    tt.tt_emb_bag_backward_sgd(T["table"], plan, x["idx"], x["off"], x["grad"], cfg.lr, stream=cs[k])
+                elif do_bwd:
+                    tt.tt_emb_bag_backward(T["table"], plan, x["idx"], x["off"], x["grad"], dcores=T["dcores"],
+                                           stream=cs[k])
+                    tt.tt_core_sgd_update(T["table"], plan, T["dcores"], cfg.lr, stream=cs[k])
+            free[k][buf].record(cs[k])
 
         def capture(b):
             """One step as a HIP graph: the capture stream forks into every stream pair, reorder(b+1)
@@ -290,7 +324,7 @@ def main():
                                 phases, args.arm),
                    "lookups_per_step": lookups // max(1, args.steps), "tables": ntab,
                    "overlap_second_stream": (not args.no_overlap) and planned, "stream_pairs": ns,
-                   "hip_graph_replay": bool(args.graph),
+                   "hip_graph_replay": bool(args.graph), "host_enqueue_threads": args.host_threads,
                    "host_enqueue_ms_per_step": round(1e3 * t_enqueue / args.steps, 3),
                    "input_generation_s": round(t_gen, 1)},
         "roofline": roofline,
