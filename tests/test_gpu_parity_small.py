@@ -183,3 +183,38 @@ def test_host_side_argument_errors(g):
     with pytest.raises(tt.TTError) as e:
         tt.tt_emb_bag_forward(bad, None, g.to_dev(idx, torch.int64), g.to_dev(off, torch.int64))
     assert e.value.status == binding.TT_ERR_SHAPE
+    # the fused backward + update needs a plan (the naive arm has no point where a slice is complete)
+    with pytest.raises(tt.TTError) as e:
+        tt.tt_emb_bag_backward_sgd(table, None, g.to_dev(idx, torch.int64), g.to_dev(off, torch.int64),
+                                   g.to_dev(grad, torch.float32), 0.01)
+    assert e.value.status == binding.TT_ERR_INVALID_ARG
+
+
+def test_unaligned_core_and_gradient_buffers_take_the_scalar_paths(g, ora):
+    """Cores and gradient buffers that are only 4-byte aligned (views into larger tensors) must
+    give the same results: the matrix-core kernels and the float4 stores are then bypassed."""
+    import paper_2507_14668_amd as tt
+    print("case unaligned", flush=True)
+    shape, cores, idx, off, grad = wl.small_random_problem(65, n=(6, 4, 5), d=(4, 8, 4), r=(1, 32, 32, 1), num_bags=200,
+                                                          max_len=5, sigma=0.2)
+    d_idx, d_off, d_g = g.to_dev(idx, torch.int64), g.to_dev(off, torch.int64), g.to_dev(grad, torch.float32)
+    views = []
+    for c in cores:  # every core starts one float past a 16-byte boundary
+        buf = torch.empty(len(c) + 1, dtype=torch.float32, device="cuda")
+        buf[1:].copy_(torch.from_numpy(np.asarray(c, dtype=np.float32)))
+        views.append(buf[1:])
+    table = tt.Table(shape.num_rows, shape.n, shape.d, shape.r, views)
+    plan = tt.tt_index_reorder(table, d_idx, d_off)
+    out = tt.tt_emb_bag_forward(table, plan, d_idx, d_off)
+    g.assert_close_rows(out.cpu().numpy(), ora.forward(shape, cores, idx, off), g.FWD_RTOL, shape.dim, "unaligned forward")
+    dviews = [torch.empty(len(c) + 1, dtype=torch.float32, device="cuda")[1:] for c in cores]
+    tt.tt_emb_bag_backward(table, plan, d_idx, d_off, d_g, dcores=dviews)
+    ref_dg = ora.backward(shape, cores, idx, off, grad)
+    g.assert_grads_close(shape, dviews, ref_dg, what="unaligned dG")
+    # aligned cores (matrix-core kernels, split workgroups) with an unaligned core-1 gradient buffer
+    table2 = g.gpu_table(shape, cores)
+    plan2 = tt.tt_index_reorder(table2, d_idx, d_off)
+    mixed = table2.core_grads_like()
+    mixed[1] = torch.empty(len(cores[1]) + 1, dtype=torch.float32, device="cuda")[1:]
+    tt.tt_emb_bag_backward(table2, plan2, d_idx, d_off, d_g, dcores=mixed)
+    g.assert_grads_close(shape, mixed, ref_dg, what="unaligned dG2 buffer")
