@@ -1,0 +1,186 @@
+// Sanitizer harness of the CPU emulation: runs the C ABI of the library, single-table and batched,
+// on a few small tables with seeded inputs and checks that the batched calls give bit-for-bit the
+// single-table results.  Built with AddressSanitizer + UBSan (or MemorySanitizer / ThreadSanitizer,
+// see build.py), so every out-of-bounds, misaligned or racing LDS access of a kernel is reported.
+// usage: harness <mfma | plain | unaligned | cfg5like> [planned: 1 | 0] [bags for cfg5like]
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+#include <stdint.h>
+#include <math.h>
+#include <vector>
+#include "tt_emb.h"
+
+static int g_off = 0;  // floats by which core and gradient pointers are shifted off their alignment
+static uint64_t rs = 88172645463325252ull;
+static uint32_t rnd() { rs ^= rs << 13; rs ^= rs >> 7; rs ^= rs << 17; return (uint32_t)(rs >> 11); }
+static float rndf() { return ((int)(rnd() % 2001) - 1000) / 1000.0f; }
+
+struct Tab {
+  tt_table t;
+  std::vector<float> core[3], core0[3];
+  std::vector<int64_t> idx, off;
+  std::vector<float> grad;
+  int64_t nnz, bags;
+  int D;
+};
+
+static void *amalloc(size_t n) { void *p = nullptr; if (posix_memalign(&p, 256, n ? n : 256)) abort();
+#ifdef EMU_MSAN
+  return p;  // left uninitialised on purpose: MemorySanitizer tracks reads of it
+#endif
+  { const char *e = getenv("EMU_FILL"); memset(p, e ? (int)strtol(e, 0, 0) : 0xA5, n); } return p; }
+
+static Tab make_tab(const int n[3], const int d[3], int R1, int R2, int bags, int maxlen, int64_t num_rows) {
+  Tab T;
+  memset(&T.t, 0, sizeof(T.t));
+  T.t.num_rows = num_rows;
+  for (int k = 0; k < 3; ++k) { T.t.n[k] = n[k]; T.t.d[k] = d[k]; }
+  T.t.r[0] = 1; T.t.r[1] = R1; T.t.r[2] = R2; T.t.r[3] = 1;
+  for (int k = 0; k < 3; ++k) {
+    size_t len = (size_t)T.t.r[k] * n[k] * d[k] * T.t.r[k + 1];
+    T.core[k].resize(len + 1);
+    for (auto &x : T.core[k]) x = rndf() * 0.3f;
+    T.core0[k] = T.core[k];
+  }
+  T.D = d[0] * d[1] * d[2];
+  T.bags = bags;
+  T.off.push_back(0);
+  for (int b = 0; b < bags; ++b) {
+    int len = maxlen <= 1 ? 1 : (int)(rnd() % (maxlen + 1));
+    for (int l = 0; l < len; ++l) {
+      // skewed: small rows are hot
+      // roughly Zipf(1): rank = N^u, u uniform
+      double u = (rnd() % 1000003) / 1000003.0;
+      uint32_t r = (uint32_t)exp(u * log((double)num_rows));
+      if (r >= (uint32_t)num_rows) r = (uint32_t)num_rows - 1;
+      T.idx.push_back(r);
+    }
+    T.off.push_back((int64_t)T.idx.size());
+  }
+  T.nnz = (int64_t)T.idx.size();
+  T.grad.resize((size_t)bags * T.D);
+  for (auto &x : T.grad) x = rndf();
+  return T;
+}
+
+struct Res { std::vector<float> out, dg[3], core[3]; };
+
+#define CK(x) do { tt_status st_ = (x); if (st_ != TT_OK) { fprintf(stderr, "FAIL %s -> %d (%s)\n", #x, st_, tt_strerror(st_)); exit(1); } } while (0)
+
+int main(int argc, char **argv) {
+  const char *kind = argc > 1 ? argv[1] : "mfma";
+  const int planned_only = argc > 2 ? atoi(argv[2]) : -1;
+  std::vector<Tab> tabs;
+  if (!strcmp(kind, "unaligned")) { g_off = 1; kind = "mfma"; }
+  if (!strcmp(kind, "mfma")) {
+    const int d[3] = {4, 8, 4};
+    const int ns[3][3] = {{3, 5, 4}, {6, 2, 7}, {2, 9, 3}};
+    const int bags[3] = {90, 40, 130};
+    for (int t = 0; t < 3; ++t)
+      tabs.push_back(make_tab(ns[t], d, 32, 32, bags[t], 5, (int64_t)ns[t][0] * ns[t][1] * ns[t][2] - (t == 1 ? 3 : 0)));
+  } else if (!strcmp(kind, "cfg5like")) {
+    const int d[3] = {4, 8, 4};
+    const int ns[4][3] = {{10, 10, 10}, {46, 46, 46}, {342, 342, 342}, {44, 45, 45}};
+    const int64_t rows[4] = {1000, 95857, 40000000, 87386};
+    const int nb = argc > 3 ? atoi(argv[3]) : 600;
+    for (int t = 0; t < 4; ++t) tabs.push_back(make_tab(ns[t], d, 64, 64, nb, 1, rows[t]));
+  } else {
+    const int d[3] = {2, 3, 4};
+    const int ns[3][3] = {{5, 7, 9}, {11, 3, 4}, {2, 13, 6}};
+    const int bags[3] = {300, 120, 500};
+    for (int t = 0; t < 3; ++t)
+      tabs.push_back(make_tab(ns[t], d, 5, 6, bags[t], 7, (int64_t)ns[t][0] * ns[t][1] * ns[t][2]));
+  }
+  const int T = (int)tabs.size();
+  const float lr = 0.01f;
+  for (int planned = 1; planned >= 0; --planned) {
+    if (planned_only >= 0 && planned != planned_only) continue;
+    fprintf(stderr, "== kind %s planned %d\n", kind, planned);
+    std::vector<Res> single(T), batch(T);
+    // ---- single-table calls
+    for (int t = 0; t < T; ++t) {
+      Tab &B = tabs[t];
+      for (int k = 0; k < 3; ++k) { B.core[k] = B.core0[k]; B.t.core[k] = B.core[k].data() + g_off; }
+      tt_plan plan; memset(&plan, 0, sizeof(plan));
+      void *ws = nullptr;
+      if (planned) {
+        size_t wb = tt_workspace_bytes(&B.t, B.nnz, B.bags);
+        ws = amalloc(wb);
+        CK(tt_index_reorder(&B.t, B.idx.data(), B.off.data(), B.nnz, B.bags, nullptr, ws, wb, &plan, nullptr));
+      }
+      Res &R = single[t];
+      R.out.assign((size_t)B.bags * B.D, -7.f);
+      CK(tt_emb_bag_forward(&B.t, planned ? &plan : nullptr, B.idx.data(), B.off.data(), B.nnz, B.bags, R.out.data(), nullptr));
+      float *dc[3];
+      for (int k = 0; k < 3; ++k) { R.dg[k].assign(B.core[k].size() + 1, -9.f); dc[k] = R.dg[k].data() + g_off; }
+      CK(tt_emb_bag_backward(&B.t, planned ? &plan : nullptr, B.idx.data(), B.off.data(), B.nnz, B.bags, B.grad.data(), dc, nullptr));
+      CK(tt_core_sgd_update(&B.t, planned ? &plan : nullptr, dc, lr, nullptr));
+      for (int k = 0; k < 3; ++k) R.core[k] = B.core[k];
+      free(ws);
+      fprintf(stderr, "single table %d done\n", t);
+    }
+    // ---- batched calls
+    std::vector<tt_batch_item> items(T);
+    std::vector<tt_plan> plans(T);
+    std::vector<void *> wss(T, nullptr);
+    size_t db = tt_batch_desc_bytes(T);
+    void *desc = amalloc(db);
+    for (int t = 0; t < T; ++t) {
+      Tab &B = tabs[t];
+      for (int k = 0; k < 3; ++k) { B.core[k] = B.core0[k]; B.t.core[k] = B.core[k].data() + g_off; }
+      memset(&items[t], 0, sizeof(tt_batch_item));
+      memset(&plans[t], 0, sizeof(tt_plan));
+      items[t].table = &B.t;
+      items[t].indices = B.idx.data(); items[t].offsets = B.off.data();
+      items[t].nnz = B.nnz; items[t].num_bags = B.bags;
+      if (planned) {
+        items[t].plan = &plans[t];
+        items[t].workspace_bytes = tt_workspace_bytes(&B.t, B.nnz, B.bags);
+        items[t].workspace = wss[t] = amalloc(items[t].workspace_bytes);
+      }
+      batch[t].out.assign((size_t)B.bags * B.D, -7.f);
+      items[t].out = batch[t].out.data();
+      items[t].grad_out = B.grad.data();
+      for (int k = 0; k < 3; ++k) { batch[t].dg[k].assign(B.core[k].size() + 1, -9.f); items[t].dcore[k] = batch[t].dg[k].data() + g_off; }
+    }
+    if (planned) CK(tt_index_reorder_batched(T, items.data(), desc, db, nullptr));
+    fprintf(stderr, "batched reorder done\n");
+    CK(tt_emb_bag_forward_batched(T, items.data(), desc, db, nullptr));
+    fprintf(stderr, "batched forward done\n");
+    CK(tt_emb_bag_backward_batched(T, items.data(), desc, db, nullptr));
+    fprintf(stderr, "batched backward done\n");
+    CK(tt_core_sgd_update_batched(T, items.data(), lr, desc, db, nullptr));
+    fprintf(stderr, "batched sgd done\n");
+    int bad = 0;
+    for (int t = 0; t < T; ++t) {
+      for (int k = 0; k < 3; ++k) batch[t].core[k] = tabs[t].core[k];
+      auto cmp = [&](const std::vector<float> &a, const std::vector<float> &b, const char *what, bool exact) {
+        size_t nbad = 0; double worst = 0;
+        for (size_t i = 0; i < a.size(); ++i) {
+          if (exact ? memcmp(&a[i], &b[i], 4) != 0 : fabs((double)a[i] - b[i]) > 1e-4) { ++nbad; }
+          double e = fabs((double)a[i] - b[i]); if (e > worst) worst = e;
+        }
+        if (nbad) { fprintf(stderr, "MISMATCH table %d %s: %zu of %zu differ (max %.3g)\n", t, what, nbad, a.size(), worst); ++bad; }
+      };
+      cmp(single[t].out, batch[t].out, "out", true);
+      for (int k = 0; k < 3; ++k) {
+        char nm[16]; snprintf(nm, sizeof nm, "dg%d", k + 1);
+        cmp(single[t].dg[k], batch[t].dg[k], nm, planned != 0);
+        snprintf(nm, sizeof nm, "core%d", k + 1);
+        cmp(single[t].core[k], batch[t].core[k], nm, planned != 0);
+      }
+    }
+    {
+      uint64_t h = 1469598103934665603ull;
+      auto mix = [&](const std::vector<float> &v) { for (float x : v) { uint32_t u; memcpy(&u, &x, 4); h = (h ^ u) * 1099511628211ull; } };
+      for (int t = 0; t < T; ++t) { mix(single[t].out); for (int k = 0; k < 3; ++k) { mix(single[t].dg[k]); mix(single[t].core[k]); } }
+      fprintf(stderr, "checksum of single-table results: %016llx\n", (unsigned long long)h);
+    }
+    for (void *w : wss) free(w);
+    free(desc);
+    fprintf(stderr, "== kind %s planned %d: %s\n", kind, planned, bad ? "MISMATCH" : "identical");
+    if (bad) return 2;
+  }
+  return 0;
+}

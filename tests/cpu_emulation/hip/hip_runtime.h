@@ -1,0 +1,95 @@
+// CPU stand-in for the parts of the HIP runtime and device language the TT kernels use.
+// One workgroup runs at a time on a pool of OS threads (one per lane), so that
+// AddressSanitizer / UBSan see every memory access of a kernel.
+#pragma once
+#include <stdint.h>
+#include <stddef.h>
+#include <string.h>
+#include <math.h>
+#include <functional>
+
+struct dim3 {
+  unsigned x, y, z;
+  dim3(unsigned x_ = 1, unsigned y_ = 1, unsigned z_ = 1) : x(x_), y(y_), z(z_) {}
+};
+struct alignas(16) float4 { float x, y, z, w; };
+static inline float4 make_float4(float x, float y, float z, float w) { return float4{x, y, z, w}; }
+
+typedef void *hipStream_t;
+typedef void *hipEvent_t;
+typedef int hipError_t;
+enum { hipSuccess = 0 };
+enum { hipMemcpyDeviceToHost = 2, hipMemcpyHostToDevice = 1 };
+enum { hipFuncAttributeMaxDynamicSharedMemorySize = 8 };
+
+namespace emu {
+extern thread_local dim3 t_threadIdx;
+extern dim3 g_blockIdx, g_blockDim, g_gridDim;
+void launch(dim3 grid, dim3 block, size_t lds, const char *name, const std::function<void()> &body);
+void syncthreads();
+void *dyn_lds();
+uint64_t wave_exchange(uint64_t v, int src_lane);          // value of lane src_lane (own lane if out of range)
+uint64_t wave_ballot(bool pred);
+void wave_mfma_16x16x4(float a, float b, float *c4);
+}  // namespace emu
+
+#define threadIdx emu::t_threadIdx
+#define blockIdx emu::g_blockIdx
+#define blockDim emu::g_blockDim
+#define gridDim emu::g_gridDim
+
+#define __global__
+#define __device__
+#define __host__
+#define __shared__ static
+#define __forceinline__ inline __attribute__((always_inline))
+#define __launch_bounds__(...)
+
+#define hipLaunchKernelGGL(kernel, grid, block, lds, stream, ...) \
+  emu::launch(grid, block, lds, #kernel, [=]() { kernel(__VA_ARGS__); })
+
+static inline hipError_t hipGetLastError() { return hipSuccess; }
+static inline hipError_t hipFuncSetAttribute(const void *, int, int) { return hipSuccess; }
+static inline hipError_t hipMemcpyAsync(void *d, const void *s, size_t n, int, hipStream_t) { memcpy(d, s, n); return hipSuccess; }
+static inline hipError_t hipStreamSynchronize(hipStream_t) { return hipSuccess; }
+static inline hipError_t hipEventCreate(hipEvent_t *e) { *e = nullptr; return hipSuccess; }
+static inline hipError_t hipEventDestroy(hipEvent_t) { return hipSuccess; }
+static inline hipError_t hipEventRecord(hipEvent_t, hipStream_t) { return hipSuccess; }
+static inline hipError_t hipEventSynchronize(hipEvent_t) { return hipSuccess; }
+static inline hipError_t hipEventElapsedTime(float *ms, hipEvent_t, hipEvent_t) { *ms = 0.f; return hipSuccess; }
+
+static inline void __syncthreads() { emu::syncthreads(); }
+static inline int __lane() { return (int)(emu::t_threadIdx.x & 63); }
+static inline int __shfl_up(int v, int delta, int = 64) {
+  return (int)(uint32_t)emu::wave_exchange((uint32_t)v, __lane() - delta);
+}
+static inline float __shfl_xor(float v, int mask, int = 64) {
+  uint32_t u; memcpy(&u, &v, 4);
+  u = (uint32_t)emu::wave_exchange(u, __lane() ^ mask);
+  float r; memcpy(&r, &u, 4); return r;
+}
+static inline unsigned long long __ballot(bool p) { return emu::wave_ballot(p); }
+static inline int __popcll(unsigned long long v) { return __builtin_popcountll(v); }
+static inline int __builtin_amdgcn_readfirstlane(int v) { return (int)(uint32_t)emu::wave_exchange((uint32_t)v, -2); }
+static inline long long clock64() { return 0; }
+
+static inline int atomicAdd(int *p, int v) { return __atomic_fetch_add(p, v, __ATOMIC_RELAXED); }
+static inline int atomicOr(int *p, int v) { return __atomic_fetch_or(p, v, __ATOMIC_RELAXED); }
+static inline float atomicAdd(float *p, float v) {
+  uint32_t *u = reinterpret_cast<uint32_t *>(p);
+  uint32_t old = __atomic_load_n(u, __ATOMIC_RELAXED);
+  for (;;) {
+    float f; memcpy(&f, &old, 4);
+    f += v;
+    uint32_t nu; memcpy(&nu, &f, 4);
+    if (__atomic_compare_exchange_n(u, &old, nu, false, __ATOMIC_RELAXED, __ATOMIC_RELAXED)) { memcpy(&f, &old, 4); return f; }
+  }
+}
+
+typedef float emu_f32x4 __attribute__((ext_vector_type(4)));
+static inline emu_f32x4 emu_mfma(float a, float b, emu_f32x4 c, int, int, int) {
+  float t[4] = {c[0], c[1], c[2], c[3]};
+  emu::wave_mfma_16x16x4(a, b, t);
+  return (emu_f32x4){t[0], t[1], t[2], t[3]};
+}
+#define __builtin_amdgcn_mfma_f32_16x16x4f32 emu_mfma

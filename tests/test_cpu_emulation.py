@@ -1,0 +1,149 @@
+"""The library's HIP kernels and host code compiled for the CPU (tests/cpu_emulation) and
+
+  * compared with the oracle through the same C ABI (forward, backward, update, fused update, plan
+    arrays, both arms) -- the kernels' logic is checked here without a GPU;
+  * run under AddressSanitizer + UBSan, single-table and batched, on seeded inputs: any
+    out-of-bounds or misaligned access of a kernel fails the test.  The batched entry points, which
+    are switched off in the GPU build, are switched on in this build.
+
+Nothing here stands in for the GPU parity tests: the emulation runs one workgroup at a time and
+knows nothing about the hardware's memory system."""
+import ctypes
+import os
+import subprocess
+import sys
+
+import numpy as np
+import pytest
+
+import tt_workloads as wl
+
+sys.path.insert(0, os.path.join(os.path.dirname(os.path.abspath(__file__)), "cpu_emulation"))
+import build as emu_build  # noqa: E402
+
+BUILD_DIR = os.path.join(os.path.dirname(os.path.abspath(__file__)), "cpu_emulation", "_build")
+pytestmark = pytest.mark.skipif(not emu_build.available(), reason="host clang++ of the ROCm toolchain not found")
+
+
+@pytest.fixture(scope="module")
+def emu():
+    from paper_2507_14668_amd import binding
+    lib = ctypes.CDLL(emu_build.build_shared(BUILD_DIR))
+    vp, i64, f32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_float
+    lib.tt_workspace_bytes.restype = ctypes.c_size_t
+    lib.tt_workspace_bytes.argtypes = [vp, i64, i64]
+    lib.tt_index_reorder.argtypes = [vp, vp, vp, i64, i64, vp, vp, ctypes.c_size_t, vp, vp]
+    lib.tt_emb_bag_forward.argtypes = [vp, vp, vp, vp, i64, i64, vp, vp]
+    lib.tt_emb_bag_backward.argtypes = [vp, vp, vp, vp, i64, i64, vp, vp, vp]
+    lib.tt_core_sgd_update.argtypes = [vp, vp, vp, f32, vp]
+    lib.tt_emb_bag_backward_sgd.argtypes = [vp, vp, vp, vp, i64, i64, vp, f32, vp]
+    return lib, binding
+
+
+def _ptr(a):
+    return ctypes.c_void_p(a.ctypes.data)
+
+
+def _aligned(nbytes):
+    raw = np.empty(nbytes + 256, dtype=np.uint8)
+    off = (-raw.ctypes.data) % 256
+    return raw[off:off + nbytes]
+
+
+def _table(binding, shape, cores):
+    t = binding.CTable()
+    t.num_rows = shape.num_rows
+    t.n[:], t.d[:], t.r[:] = shape.n, shape.d, shape.r
+    for k in range(3):
+        t.core[k] = cores[k].ctypes.data
+    return t
+
+
+def _run(emu, shape, cores, idx, off, grad, lr):
+    lib, binding = emu
+    cores = [np.ascontiguousarray(c, dtype=np.float32).copy() for c in cores]
+    idx, off = np.ascontiguousarray(idx, dtype=np.int64), np.ascontiguousarray(off, dtype=np.int64)
+    grad = np.ascontiguousarray(grad, dtype=np.float32)
+    nnz, nb = len(idx), len(off) - 1
+    table = _table(binding, shape, cores)
+    ws = _aligned(lib.tt_workspace_bytes(ctypes.byref(table), nnz, nb))
+    plan = binding.CPlan()
+    assert lib.tt_index_reorder(ctypes.byref(table), _ptr(idx), _ptr(off), nnz, nb, None, _ptr(ws), ws.nbytes,
+                                ctypes.byref(plan), None) == 0
+    res = {}
+
+    def ints(name, count):
+        o = getattr(plan, name) - ws.ctypes.data
+        return ws[o:o + 4 * count].view(np.int32).copy()
+
+    counts = ints("counts", 16)
+    ur, up = int(counts[0]), int(counts[1])
+    res["plan_arrays"] = dict(U_r=ur, U_p=up, num_valid=int(counts[2]), status=int(counts[4]), uniq_row=ints("uniq_row", ur),
+                       row_seg=ints("row_seg", ur + 1), uniq_pref=ints("uniq_pref", up), pref_seg=ints("pref_seg", up + 1),
+                       lookup2row=ints("lookup2row", nnz), i2_seg=ints("i2_seg", shape.n[1] + 1),
+                       i3_seg=ints("i3_seg", shape.n[2] + 1), i1_seg=ints("i1_seg", shape.n[0] + 1))
+    for arm, pl in (("plan", ctypes.byref(plan)), ("naive", None)):
+        out = np.full((nb, shape.dim), np.nan, dtype=np.float32)
+        assert lib.tt_emb_bag_forward(ctypes.byref(table), pl, _ptr(idx), _ptr(off), nnz, nb, _ptr(out), None) == 0
+        dg = [np.full_like(c, np.nan) for c in cores]
+        arr = (ctypes.c_void_p * 3)(*[g.ctypes.data for g in dg])
+        assert lib.tt_emb_bag_backward(ctypes.byref(table), pl, _ptr(idx), _ptr(off), nnz, nb, _ptr(grad), arr, None) == 0
+        res[arm] = (out, dg)
+    # update (touched slices) after the planned backward, and the fused call on fresh cores
+    dg = res["plan"][1]
+    arr = (ctypes.c_void_p * 3)(*[g.ctypes.data for g in dg])
+    upd = [c.copy() for c in cores]
+    t_upd = _table(binding, shape, upd)
+    assert lib.tt_core_sgd_update(ctypes.byref(t_upd), ctypes.byref(plan), arr, ctypes.c_float(lr), None) == 0
+    fused = [c.copy() for c in cores]
+    t_fused = _table(binding, shape, fused)
+    assert lib.tt_emb_bag_backward_sgd(ctypes.byref(t_fused), ctypes.byref(plan), _ptr(idx), _ptr(off), nnz, nb,
+                                       _ptr(grad), ctypes.c_float(lr), None) == 0
+    res["updated"], res["fused"] = upd, fused
+    return res
+
+
+@pytest.mark.parametrize("name,n,d,r,nb,ml", [
+    ("plain", (5, 4, 6), (2, 3, 2), (1, 3, 5, 1), 150, 6),
+    ("mfma_r32_split", (9, 3, 5), (4, 8, 4), (1, 32, 32, 1), 260, 5),   # 3 core-1 slices: split workgroups
+    ("mfma_r64_two_strips", (3, 2, 11), (4, 8, 4), (1, 64, 64, 1), 120, 4),
+])
+def test_emulated_kernels_match_oracle(emu, ora, name, n, d, r, nb, ml):
+    import gpu_util as g
+    shape, cores, idx, off, grad = wl.small_random_problem(301, n=n, d=d, r=r, num_bags=nb, max_len=ml, sigma=0.2)
+    lr = 0.05
+    res = _run(emu, shape, cores, idx, off, grad, lr)
+    ref_plan = ora.reorder_plan(shape, idx, off)
+    p = res["plan_arrays"]
+    assert p["status"] == 0 and p["num_valid"] == ref_plan["num_valid"]
+    for key in ("uniq_row", "row_seg", "uniq_pref", "pref_seg", "lookup2row"):
+        assert np.array_equal(p[key], ref_plan[key]), key
+    i3 = np.sort(ref_plan["uniq_row"] % shape.n[2])
+    assert np.array_equal(p["i3_seg"], np.searchsorted(i3, np.arange(shape.n[2] + 1)))
+    i2 = np.sort(ref_plan["uniq_pref"] % shape.n[1])
+    assert np.array_equal(p["i2_seg"], np.searchsorted(i2, np.arange(shape.n[1] + 1)))
+    assert np.array_equal(p["i1_seg"], np.searchsorted(ref_plan["uniq_pref"] // shape.n[1], np.arange(shape.n[0] + 1)))
+    ref_out = ora.forward(shape, cores, idx, off)
+    ref_dg = ora.backward(shape, cores, idx, off, grad)
+    for arm in ("plan", "naive"):
+        out, dg = res[arm]
+        g.assert_close_rows(out, ref_out, g.FWD_RTOL, shape.dim, "%s forward (%s)" % (name, arm))
+        g.assert_grads_close(shape, dg, ref_dg, what="%s dG (%s)" % (name, arm))
+    g.assert_grads_close(shape, res["updated"], ora.sgd(cores, ref_dg, lr), what="%s updated G" % name)
+    for k in range(3):
+        assert np.array_equal(res["fused"][k], res["updated"][k]), "fused update differs from backward + update"
+
+
+@pytest.fixture(scope="module")
+def asan_harness():
+    return emu_build.build_harness(BUILD_DIR, "address")
+
+
+@pytest.mark.parametrize("kind", ["mfma", "plain", "unaligned"])
+def test_sanitized_single_and_batched_calls(asan_harness, kind):
+    env = dict(os.environ, ASAN_OPTIONS="detect_stack_use_after_return=0:detect_leaks=0", UBSAN_OPTIONS="halt_on_error=1")
+    res = subprocess.run([asan_harness, kind], capture_output=True, text=True, env=env, timeout=600)
+    text = res.stdout + res.stderr
+    assert res.returncode == 0, text[-4000:]
+    assert "ERROR" not in text and "runtime error" not in text, text[-4000:]
+    assert text.count("identical") == 2, text[-2000:]  # planned and naive arms: batched == single-table
