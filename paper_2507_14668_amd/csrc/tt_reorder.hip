@@ -105,24 +105,26 @@ k_radix_hist(TTArg<BATCHED> a, int which, int in_a, int shift, int bits) {
     }
   }
   __syncthreads();
-  for (int b = threadIdx.x; b < nbins; b += TT_BLOCK) hist[(size_t)b * ntiles + tile] = h[b];
+  for (int b = threadIdx.x; b < nbins; b += TT_BLOCK) hist[(size_t)tile * nbins + b] = h[b];  // [tile][bin]
 }
 
-// One workgroup per bin: exclusive scan of that bin's per-tile counts, in place.
+// One workgroup per bin: exclusive scan of that bin's per-tile counts (a column of the [tile][bin]
+// matrix), in place.  Only launched for sorts of many tiles; short sorts let every scatter
+// workgroup add up its own column prefixes (one launch less per pass).
 template <bool BATCHED>
 __global__ void __launch_bounds__(TT_BLOCK)
-k_radix_binscan(TTArg<BATCHED> a, int which) {
+k_radix_binscan(TTArg<BATCHED> a, int which, int nbins) {
   const TTDev &d = a.get();
   const int ntiles = sort_bufs(d, which).ntiles;
   int32_t *__restrict__ bin_total = d.tmp.bin_total;
   __shared__ int tmp[TT_BLOCK / TT_WAVE + 1];
-  int32_t *row = d.tmp.hist + (size_t)blockIdx.x * ntiles;
+  int32_t *col = d.tmp.hist + blockIdx.x;
   int carry = 0;
   for (int base = 0; base < ntiles; base += TT_BLOCK) {
     int t = base + threadIdx.x;
-    int v = t < ntiles ? row[t] : 0, total;
+    int v = t < ntiles ? col[(size_t)t * nbins] : 0, total;
     int ex = tt_block_excl_scan(v, tmp, &total);
-    if (t < ntiles) row[t] = carry + ex;
+    if (t < ntiles) col[(size_t)t * nbins] = carry + ex;
     carry += total;
   }
   if (threadIdx.x == 0) bin_total[blockIdx.x] = carry;
@@ -132,7 +134,7 @@ k_radix_binscan(TTArg<BATCHED> a, int which) {
 // digits keep their relative order.
 template <bool BATCHED>
 __global__ void __launch_bounds__(TT_BLOCK)
-k_radix_scatter(TTArg<BATCHED> a, int which, int in_a, int shift, int bits) {
+k_radix_scatter(TTArg<BATCHED> a, int which, int in_a, int shift, int bits, int self_scan) {
   const TTDev &d = a.get();
   const SortBufs sb = sort_bufs(d, which);
   const int ntiles = sb.ntiles;
@@ -155,19 +157,33 @@ k_radix_scatter(TTArg<BATCHED> a, int which, int in_a, int shift, int bits) {
   // global offset of (bin, this tile) = exclusive scan of bin totals + tile prefix inside the bin
   {
     constexpr int PER = MAXB / TT_BLOCK;
-    int loc[PER], sum = 0;
+    int loc[PER], pre[PER], sum = 0;
 #pragma unroll
     for (int k = 0; k < PER; ++k) {
       int b = threadIdx.x * PER + k;
-      loc[k] = b < nbins ? bin_total[b] : 0;
-      sum += loc[k];
+      loc[k] = (b < nbins && !self_scan) ? bin_total[b] : 0;
+      pre[k] = (b < nbins && !self_scan) ? hist[(size_t)tile * nbins + b] : 0;
     }
+    if (self_scan) {  // raw per-tile counts: column totals and the prefix over the earlier tiles
+#pragma unroll 8
+      for (int t = 0; t < ntiles; ++t) {  // independent loads: eight tiles in flight
+#pragma unroll
+        for (int k = 0; k < PER; ++k) {
+          const int b = threadIdx.x * PER + k;
+          const int v = b < nbins ? hist[(size_t)t * nbins + b] : 0;
+          loc[k] += v;
+          pre[k] += t < tile ? v : 0;
+        }
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < PER; ++k) sum += loc[k];
     int total, ex = tt_block_excl_scan(sum, tmp, &total);
 #pragma unroll
     for (int k = 0; k < PER; ++k) {
       int b = threadIdx.x * PER + k;
       if (b < nbins) {
-        gofs[b] = ex + hist[(size_t)b * ntiles + tile];
+        gofs[b] = ex + pre[k];
         run[b] = 0;
 #pragma unroll
         for (int w = 0; w < NW; ++w) wave_cnt[w][b] = 0;
@@ -424,6 +440,9 @@ int bit_length(long long v) {
   return b;
 }
 
+#ifndef TT_SELF_SCAN_TILES
+#define TT_SELF_SCAN_TILES 64  // sorts of at most this many tiles skip the bin-scan launch
+#endif
 struct RadixPlan { int passes; int bits_per_pass; };
 RadixPlan radix_plan(int key_bits) {
   RadixPlan p;
@@ -442,11 +461,12 @@ tt_status radix_sort(const TTBatch &b, int which, int max_tiles, int key_bits, h
   int shift = 0;
   for (int p = 0; p < rp.passes; ++p) {
     const int bits = (key_bits - shift) < rp.bits_per_pass ? (key_bits - shift) : rp.bits_per_pass;
+    const int self_scan = max_tiles <= TT_SELF_SCAN_TILES ? 1 : 0;
     TT_LAUNCH(k_radix_hist, max_tiles, TT_BLOCK, 0, s, b, which, in_a, shift, bits);
-    TT_LAUNCH(k_radix_binscan, 1 << bits, TT_BLOCK, 0, s, b, which);
+    if (!self_scan) TT_LAUNCH(k_radix_binscan, 1 << bits, TT_BLOCK, 0, s, b, which, 1 << bits);
     {
       TTProfScope prof(which == 0 ? &b.host[0].plan : nullptr, TT_KERNEL_SORT_SCATTER, s);
-      TT_LAUNCH(k_radix_scatter, max_tiles, TT_BLOCK, 0, s, b, which, in_a, shift, bits);
+      TT_LAUNCH(k_radix_scatter, max_tiles, TT_BLOCK, 0, s, b, which, in_a, shift, bits, self_scan);
     }
     shift += bits;
     in_a = !in_a;
