@@ -330,6 +330,20 @@ def main():
         "roofline": roofline,
         "cpu_baseline": None,
     }
+    if planned:  # whole-step roofline: algorithmic work of one step against the published peaks
+        flops = bytes_ = 0.0
+        first = main_region["last_b"] - args.steps
+        for k in range(args.steps):
+            for T in tabs:
+                x = T["batches"][(first + k) % nbatch]
+                flops += kernel_work("fwd_contract", T["shape"], x, cfg.batch) + x["nnz"] * T["shape"].dim
+                bytes_ += 8.0 * x["nnz"] + 8.0 * (cfg.batch + 1) + 4.0 * cfg.batch * T["shape"].dim  # indices, offsets, out
+                if do_bwd:
+                    flops += kernel_work("bwd_contract", T["shape"], x, cfg.batch) + x["nnz"] * T["shape"].dim
+                    bytes_ += 4.0 * cfg.batch * T["shape"].dim  # output gradients
+        t_flop, t_hbm = flops / args.steps / (PEAK_FP32_TFLOPS * 1e12), bytes_ / args.steps / (PEAK_HBM_GBS * 1e9)
+        result["config"]["step_bound_ms"] = {"fp32_mfma": round(1e3 * t_flop, 4), "hbm": round(1e3 * t_hbm, 4),
+                                             "frac_of_measured": round(max(t_flop, t_hbm) / (dt / args.steps), 4)}
     if counts:
         result["config"]["distinct_rows_last_batch"] = int(sum(c[0] for c in counts))
         result["config"]["distinct_prefixes_last_batch"] = int(sum(c[1] for c in counts))
