@@ -147,3 +147,37 @@ def test_sanitized_single_and_batched_calls(asan_harness, kind):
     assert res.returncode == 0, text[-4000:]
     assert "ERROR" not in text and "runtime error" not in text, text[-4000:]
     assert text.count("identical") == 2, text[-2000:]  # planned and naive arms: batched == single-table
+
+
+def test_emulated_kernels_on_random_shapes(emu, ora):
+    """Seeded random shapes within the library's limits (ranks and factors that are not powers of
+    two, single-slice cores, padded row counts, the matrix-core shapes): every arm against the
+    oracle, and the fused update bit for bit against backward + update."""
+    import gpu_util as g
+    rng = np.random.default_rng(20250714)
+    for case in range(14):
+        while True:
+            n = tuple(int(x) for x in rng.integers(1, 9, size=3))
+            d = tuple(int(x) for x in rng.choice([1, 2, 3, 4, 5, 8], size=3))
+            r1, r2 = int(rng.choice([1, 2, 3, 7, 16, 33, 64])), int(rng.choice([1, 2, 5, 8, 17, 32, 64]))
+            if rng.random() < 0.25:
+                d, r1 = (4, 8, 4), int(rng.choice([32, 64]))
+                r2 = r1
+            dim, p12, s2 = d[0] * d[1] * d[2], d[0] * d[1] * r2, d[1] * r2
+            lds = d[0] * r1 + d[0] * d[1] * (r2 | 1) + p12 + dim + 8 * r2 * d[2]
+            if dim <= 1024 and p12 <= 4096 and s2 <= 4096 and lds * 4 <= 65536:
+                break
+        cap = n[0] * n[1] * n[2]
+        num_rows = int(rng.integers(max(1, cap - n[2] + 1), cap + 1))
+        nb, ml = int(rng.integers(1, 100)), int(rng.integers(1, 8))
+        shape, cores, idx, off, grad = wl.small_random_problem(7000 + case, n=n, d=d, r=(1, r1, r2, 1), num_rows=num_rows,
+                                                              num_bags=nb, max_len=ml, sigma=0.3)
+        what = "n=%s d=%s r=(%d,%d) rows=%d" % (n, d, r1, r2, num_rows)
+        res = _run(emu, shape, cores, idx, off, grad, 0.05)
+        ref_out, ref_dg = ora.forward(shape, cores, idx, off), ora.backward(shape, cores, idx, off, grad)
+        for arm in ("plan", "naive"):
+            out, dg = res[arm]
+            g.assert_close_rows(out, ref_out, g.FWD_RTOL, shape.dim, "%s forward (%s)" % (what, arm))
+            g.assert_grads_close(shape, dg, ref_dg, what="%s dG (%s)" % (what, arm))
+        for k in range(3):
+            assert np.array_equal(res["fused"][k], res["updated"][k]), what
