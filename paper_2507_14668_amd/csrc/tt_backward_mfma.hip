@@ -66,9 +66,8 @@ k_bwd_mfma(TTArg<BATCHED> a) {
   // with the fused update the strip of core 1 this workgroup reads is also the one it rewrites at
   // the end (no other workgroup touches it), so g2 / dg2 may alias and carry no __restrict__
   const float *__restrict__ g1 = d.g[0], *g2 = d.g[1], *__restrict__ g3t = d.plan.g3t;
-  const int32_t *__restrict__ uniq_pref = d.plan.uniq_pref, *__restrict__ pref_seg = d.plan.pref_seg,
-                *__restrict__ uniq_row = d.plan.uniq_row, *__restrict__ prefs_by_i2 = d.plan.prefs_by_i2,
-                *__restrict__ i2_seg = d.plan.i2_seg;
+  const int32_t *__restrict__ uniq_row = d.plan.uniq_row, *__restrict__ i2_seg = d.plan.i2_seg;
+  const int4 *__restrict__ pref_meta = reinterpret_cast<const int4 *>(d.plan.pref_meta);
   const float *__restrict__ gagg = d.plan.gagg;
   float *__restrict__ t3buf = d.plan.t3buf, *__restrict__ t1buf = d.plan.t1buf;
   const int fused = d.fused;
@@ -139,10 +138,8 @@ k_bwd_mfma(TTArg<BATCHED> a) {
     if (threadIdx.x < TT_META) {
       int q = -1, i1 = -1, u0 = 0, nr = 0;
       if (base + (int)threadIdx.x < seg1) {
-        q = prefs_by_i2[base + threadIdx.x];
-        i1 = uniq_pref[q] / sh.n2;
-        u0 = pref_seg[q];
-        nr = pref_seg[q + 1] - u0;
+        const int4 m = pref_meta[base + threadIdx.x];  // i1, first row slot, rows, prefix slot
+        i1 = m.x; u0 = m.y; nr = m.z; q = m.w;
       }
       s_q[threadIdx.x] = q; s_i1[threadIdx.x] = i1; s_u0[threadIdx.x] = u0; s_nr[threadIdx.x] = nr;
     }

@@ -45,10 +45,10 @@ k_fwd_mfma(TTArg<BATCHED> a) {
   const TTDev &d = a.get();
   const TTShape &sh = d.sh;
   const float *__restrict__ g1 = d.g[0], *__restrict__ g2 = d.g[1], *__restrict__ g3t = d.plan.g3t;
-  const int32_t *__restrict__ counts = d.plan.counts, *__restrict__ uniq_pref = d.plan.uniq_pref,
-                *__restrict__ pref_seg = d.plan.pref_seg, *__restrict__ uniq_row = d.plan.uniq_row,
-                *__restrict__ prefs_by_i2 = d.plan.prefs_by_i2, *__restrict__ i2_seg = d.plan.i2_seg,
-                *__restrict__ i2_chunk_off = d.plan.i2_chunk_off;
+  const int32_t *__restrict__ counts = d.plan.counts, *__restrict__ uniq_row = d.plan.uniq_row,
+                *__restrict__ i2_seg = d.plan.i2_seg, *__restrict__ i2_chunk_off = d.plan.i2_chunk_off,
+                *__restrict__ chunk_i2 = d.plan.chunk_i2;
+  const int4 *__restrict__ pref_meta = reinterpret_cast<const int4 *>(d.plan.pref_meta);
   float *__restrict__ rowbuf = d.plan.rowbuf;
   using G = FwdGeom<R1, R2, D2>;
   extern __shared__ float lds[];
@@ -63,13 +63,7 @@ k_fwd_mfma(TTArg<BATCHED> a) {
   for (int work = blockIdx.x; work < nchunks * G::NSTRIP; work += gridDim.x) {
     const int chunk = work / G::NSTRIP, strip = work - chunk * G::NSTRIP;
     const int j2base = strip * G::JW;
-    // i2 = last entry of the running chunk count that is <= chunk (empty i2 repeat the count)
-    int lo = 0, hi = sh.n2;
-    while (hi - lo > 1) {
-      const int mid = (lo + hi) >> 1;
-      if (i2_chunk_off[mid] <= chunk) lo = mid; else hi = mid;
-    }
-    const int i2 = lo;
+    const int i2 = chunk_i2[chunk];
     const int cs = i2_seg[i2] + (chunk - i2_chunk_off[i2]) * TT_MP;
     const int left_in_seg = i2_seg[i2 + 1] - cs;
     const int cnt = left_in_seg < TT_MP ? left_in_seg : TT_MP;
@@ -88,10 +82,8 @@ k_fwd_mfma(TTArg<BATCHED> a) {
     if (threadIdx.x < TT_MP) {
       int i1 = -1, u0 = 0, nr = 0;
       if ((int)threadIdx.x < cnt) {
-        const int q = prefs_by_i2[cs + threadIdx.x];
-        i1 = uniq_pref[q] / sh.n2;
-        u0 = pref_seg[q];
-        nr = pref_seg[q + 1] - u0;
+        const int4 m = pref_meta[cs + threadIdx.x];  // i1, first row slot, rows, prefix slot
+        i1 = m.x; u0 = m.y; nr = m.z;
       }
       s_i1[threadIdx.x] = i1;
       s_u0[threadIdx.x] = u0;

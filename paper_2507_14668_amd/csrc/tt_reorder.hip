@@ -408,6 +408,10 @@ __global__ void k_seg_bounds(TTArg<BATCHED> a) {
   seg_starts(d.plan.i3_of_sorted, 1, ur, d.sh.n3, d.plan.i3_seg, u);
   seg_starts(d.tmp.k2, 1, up, d.sh.n2, d.plan.i2_seg, u);
   seg_starts(d.plan.uniq_pref, d.sh.n2, up, d.sh.n1, d.plan.i1_seg, u);
+  if (u < up) {  // what the matrix-core kernels need to know about the u-th prefix in i2 order
+    const int q = d.plan.prefs_by_i2[u], u0 = d.plan.pref_seg[q];
+    reinterpret_cast<int4 *>(d.plan.pref_meta)[u] = make_int4(d.plan.uniq_pref[q] / d.sh.n2, u0, d.plan.pref_seg[q + 1] - u0, q);
+  }
 }
 
 // Running count of TT_MP-prefix chunks per i2 (single workgroup; n2 may exceed the block size).
@@ -431,6 +435,12 @@ k_chunk_offsets(TTArg<BATCHED> a) {
   if (threadIdx.x == 0) {
     chunk_off[n2] = carry;
     counts[5] = carry;
+  }
+  __syncthreads();  // the offsets written above are read back below (same workgroup)
+  int32_t *__restrict__ chunk_i2 = d.plan.chunk_i2;
+  for (int t = threadIdx.x; t < n2; t += TT_BLOCK) {
+    const int c1 = t + 1 < n2 ? chunk_off[t + 1] : carry;
+    for (int c = chunk_off[t]; c < c1; ++c) chunk_i2[c] = t;
   }
 }
 

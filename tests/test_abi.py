@@ -32,7 +32,7 @@ def test_struct_mirrors_match_header_sizes():
     # tt_table: int64 + 3*int32 + 3*int32 + 4*int32 + 3 pointers = 8 + 40 + 24 = 72 bytes
     assert ctypes.sizeof(binding.CTable) == 72
     # tt_plan: 4*int64 + 10*int32 (+pad) + 18 + 7 + 3 pointers + size_t
-    assert ctypes.sizeof(binding.CPlan) == 32 + 40 + 8 * (18 + 8 + 3) + 8
+    assert ctypes.sizeof(binding.CPlan) == 32 + 40 + 8 * (20 + 8 + 3) + 8
 
 
 def test_workspace_query_and_host_validation_without_gpu():
