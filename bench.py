@@ -30,6 +30,9 @@ def parse_args():
     ap.add_argument("--arm", default="plan", choices=["plan", "naive"])
     ap.add_argument("--no-overlap", action="store_true", help="reorder on the compute stream")
     ap.add_argument("--permute", action="store_true", help="seeded random row permutation of the Zipf ranks")
+    ap.add_argument("--bijection", action="store_true",
+                    help="build the offline index bijection (frequency order; the synthetic batches have no "
+                         "co-occurrence structure) from the batches and pass it to the reorder as `remap`")
     ap.add_argument("--batches", type=int, default=8, help="distinct batches cycled through")
     ap.add_argument("--tables", type=int, default=0, help="use only the first T tables (0 = all)")
     ap.add_argument("--streams", type=int, default=8,
@@ -92,16 +95,26 @@ def main():
         shape = cfg.tables[t]
         table = tt.Table.from_numpy(shape, wl.make_cores(cfg, t))
         batches = []
+        host = [wl.make_batch(cfg, t, batch=b, permute_rows=True if args.permute else None) for b in range(nbatch)]
+        remap = None
+        if args.bijection:
+            from paper_2507_14668_amd.bijection import build_index_bijection
+            # learned from OTHER batches of the same distribution than the ones that are timed
+            sample = [wl.make_batch(cfg, t, batch=nbatch + b, permute_rows=True if args.permute else None)
+                      for b in range(nbatch)]
+            remap = build_index_bijection(sample, shape.num_rows, hot_ratio=1.0)
         for b in range(nbatch):
-            idx, off = wl.make_batch(cfg, t, batch=b, permute_rows=True if args.permute else None)
+            idx, off = host[b]
             grad = wl.make_grad(cfg, t, batch=b)
+            seen = idx if remap is None else remap[idx]  # the rows the kernels actually touch
             batches.append(dict(idx=torch.from_numpy(idx).cuda(), off=torch.from_numpy(off).cuda(),
                                 grad=torch.from_numpy(grad).cuda(), nnz=len(idx),
                                 # workload statistics used only to count algorithmic work
-                                u_r=int(np.unique(idx).size), u_p=int(np.unique(idx // shape.n[2]).size)))
+                                u_r=int(np.unique(seen).size), u_p=int(np.unique(seen // shape.n[2]).size)))
         max_nnz = max(x["nnz"] for x in batches)
         ws = [tt.alloc_workspace(table, max_nnz, cfg.batch) for _ in range(2)] if args.arm == "plan" else None
         tabs.append(dict(shape=shape, table=table, batches=batches, ws=ws, plans=[None, None],
+                         remap=None if remap is None else torch.from_numpy(remap).cuda(),
                          out=torch.empty((cfg.batch, shape.dim), dtype=torch.float32, device="cuda"),
                          dcores=table.core_grads_like()))
     torch.cuda.synchronize()
@@ -137,8 +150,8 @@ def main():
                 for T in groups[k]:
                     x = T["batches"][b % nbatch]
                     # workspace sized for the largest batch; the plan is rebuilt for this batch's nnz
-                    T["plans"][buf] = tt.tt_index_reorder(T["table"], x["idx"], x["off"], workspace=T["ws"][buf],
-                                                          stream=rs[k])
+                    T["plans"][buf] = tt.tt_index_reorder(T["table"], x["idx"], x["off"], remap=T["remap"],
+                                                          workspace=T["ws"][buf], stream=rs[k])
                     if timing[0]:
                         prof.attach(T["plans"][buf])
                 if events:
@@ -182,8 +195,8 @@ def main():
                 rs[k].wait_event(free[k][nxt])
                 for T in groups[k]:
                     x = T["batches"][(b + 1) % nbatch]
-                    T["plans"][nxt] = tt.tt_index_reorder(T["table"], x["idx"], x["off"], workspace=T["ws"][nxt],
-                                                          stream=rs[k])
+                    T["plans"][nxt] = tt.tt_index_reorder(T["table"], x["idx"], x["off"], remap=T["remap"],
+                                                          workspace=T["ws"][nxt], stream=rs[k])
                     if timing[0]:
                         prof.attach(T["plans"][nxt])
                 ready[k][nxt].record(rs[k])
@@ -320,7 +333,8 @@ def main():
                                "Zipf(alpha=%g)%s, %s, %s arm" %
                                (args.workload, ntab, cfg.tables[0].dim, cfg.tables[0].r[1], cfg.tables[0].r[2],
                                 cfg.batch, "multi-hot" if cfg.multi_hot else "one-hot", cfg.alpha,
-                                " + row permutation" if (args.permute or cfg.permute_rows) else "",
+                                (" + row permutation" if (args.permute or cfg.permute_rows) else "") +
+                                (" + offline index bijection" if args.bijection else ""),
                                 phases, args.arm),
                    "lookups_per_step": lookups // max(1, args.steps), "tables": ntab,
                    "overlap_second_stream": (not args.no_overlap) and planned, "stream_pairs": ns,
