@@ -17,6 +17,7 @@
 //
 // MFMA operand layout (D = A[16x4] * B[4x16] + C): lane l supplies A[m = l%16][k = l/16] and
 // B[k = l/16][n = l%16] and holds C[m = 4*(l/16) + v][n = l%16] in component v.
+#include <stdlib.h>
 #include "tt_internal.h"
 
 namespace {
@@ -549,7 +550,11 @@ tt_status launch(const TTBatch &b, hipStream_t s) {
   const long long blocks = tt_batch_max(b, [](const TTDev &d) {
     return (long long)d.sh.n2 * G::NSTRIP * d.bwd_split; });
   TTProfScope prof(&b.host[0].plan, TT_KERNEL_BWD_CONTRACT, s);
-  if (b.dev)
+  static const bool eight = getenv("TT_EMB_BWD4") == nullptr;
+  if (eight) {
+    const tt_status st = ttk_backward_mfma8_kernel(b, s);
+    if (st != TT_OK) return st;
+  } else if (b.dev)
     hipLaunchKernelGGL((k_bwd_mfma<true, R1, R2, D2>), dim3((unsigned)blocks, (unsigned)b.T),
                        dim3(TT_BLOCK), lds, s, TTArg<true>{b.dev});
   else

@@ -61,7 +61,7 @@ thread_local dim3 t_threadIdx;
 dim3 g_blockIdx, g_blockDim, g_gridDim;
 
 namespace {
-constexpr int NW = 4, WL = 64;
+constexpr int NW = 8, WL = 64;
 constexpr size_t STACK = 512 * 1024;
 
 enum State { RUNNABLE, AT_WAVE, AT_BLOCK, DONE };
@@ -91,7 +91,7 @@ thread_local Wave *t_wave = nullptr;
 void *g_lds = nullptr;
 const std::function<void()> *g_body = nullptr;
 
-// block barrier among wave threads (spinning: at most four threads take part)
+// block barrier among wave threads (spinning: at most eight threads take part)
 std::atomic<int> b_alive{0}, b_arrived{0};
 std::atomic<unsigned> b_gen{0};
 std::mutex bm;

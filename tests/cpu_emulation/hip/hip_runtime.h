@@ -44,6 +44,7 @@ void wave_mfma_16x16x4(float a, float b, float *c4);
 #define __device__
 #define __host__
 #define __shared__ static
+#define __align__(n) __attribute__((aligned(n)))
 #define __forceinline__ inline __attribute__((always_inline))
 #define __launch_bounds__(...)
 
@@ -73,6 +74,7 @@ static inline float __shfl_xor(float v, int mask, int = 64) {
 static inline unsigned long long __ballot(bool p) { return emu::wave_ballot(p); }
 static inline int __popcll(unsigned long long v) { return __builtin_popcountll(v); }
 static inline int __builtin_amdgcn_readfirstlane(int v) { return (int)(uint32_t)emu::wave_exchange((uint32_t)v, -2); }
+static inline int __builtin_amdgcn_readlane(int v, int lane) { return (int)(uint32_t)emu::wave_exchange((uint32_t)v, lane); }
 static inline long long clock64() { return 0; }
 
 static inline int atomicAdd(int *p, int v) { return __atomic_fetch_add(p, v, __ATOMIC_RELAXED); }
