@@ -134,7 +134,6 @@ int ttk_mfma_strips(const TTShape &sh);
 int ttk_bwd_split(const TTShape &sh);
 #define TT_BWD_MAX_SPLIT 8
 tt_status ttk_backward_mfma(const TTBatch &b, hipStream_t s);
-tt_status ttk_backward_mfma8_kernel(const TTBatch &b, hipStream_t s);
 // true unless the environment variable TT_EMB_NO_MFMA is set (keeps the plain-ALU kernels
 // selectable for comparison runs)
 bool tt_mfma_enabled();
