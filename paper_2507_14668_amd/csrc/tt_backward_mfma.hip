@@ -165,12 +165,16 @@ k_bwd_mfma(TTArg<BATCHED> a) {
 #pragma unroll
     for (int k = 0; k < GPT; ++k) {
       const int e = threadIdx.x + k * NTHR, row = e / R1, r1 = e - row * R1;
+      // unconditional loads (slice 0 stands in for a prefix the chunk does not have, and is zeroed
+      // below): a load under a branch would make every later wait for an older load a wait for all
+      // (the stand-in is replaced by zero when the chunk is staged, not here: using the value now
+      // would wait for the load)
       const int i1 = s_i1[mo + (row >> 2)];
-      g1n[k] = i1 >= 0 ? g1[(size_t)i1 * G::S1 + (row & 3) * R1 + r1] : 0.f;
+      g1n[k] = g1[(size_t)(i1 >= 0 ? i1 : 0) * G::S1 + (row & 3) * R1 + r1];
     }
     const int p = threadIdx.x / I3_STAGE, r = threadIdx.x - p * I3_STAGE;
     // the row index is kept raw here; taking it modulo n3 now would wait for the load at once
-    i3n = r < s_nr[mo + p] ? uniq_row[s_u0[mo + p] + r] : 0;
+    i3n = uniq_row[s_u0[mo + p] + (r < s_nr[mo + p] ? r : 0)];
   };
 
   // registers -> LDS (buffer pair `par`) for a chunk whose operands were fetched earlier
@@ -179,8 +183,9 @@ k_bwd_mfma(TTArg<BATCHED> a) {
 #pragma unroll
     for (int k = 0; k < GPT; ++k) {
       const int e = threadIdx.x + k * NTHR, row = e / R1, r1 = e - row * R1;
-      As2[row * G::RS + r1] = g1n[k];
-      AsT2[r1 * G::RT + row] = g1n[k];
+      const float v = s_i1[mo2 + (row >> 2)] >= 0 ? g1n[k] : 0.f;  // zero rows for prefixes the chunk does not have
+      As2[row * G::RS + r1] = v;
+      AsT2[r1 * G::RT + row] = v;
     }
     s_i3[par][threadIdx.x / I3_STAGE][threadIdx.x % I3_STAGE] = i3n % sh.n3;
     if (wave == 0) {  // quads per prefix of the chunk, running total (scan over the first 8 lanes)
