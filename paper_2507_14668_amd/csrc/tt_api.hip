@@ -134,7 +134,7 @@ void fill_dev(TTDev *d, const TTShape &sh, const tt_table *t, const tt_plan *pla
   d->grad_out = grad_out; d->out = out;
   d->nnz = (int)nnz; d->num_bags = (int)num_bags;
   d->sort_tiles = tt_ceil_div(nnz, TT_SORT_TILE);
-  d->mfma = ttk_mfma_selected(sh, t->core[1]) ? 1 : 0;
+  d->mfma = ttk_mfma_selected(sh, t->core[1], t->core[2]) ? 1 : 0;
   d->strips = d->mfma ? ttk_mfma_strips(sh) : 1;
   d->bwd_split = d->mfma ? ttk_bwd_split(sh) : 1;
   // the kernel that sums split partials stores float4: an unaligned gradient buffer is served unsplit

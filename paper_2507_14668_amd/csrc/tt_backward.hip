@@ -117,8 +117,13 @@ k_seg_stage1(TTArg<BATCHED> arg, int kind, int lanes, int chunk) {
   const int fused = sv.fused;
   const float lr = sv.lr;
   const int groups = blockDim.x / lanes, g = threadIdx.x / lanes, lane = threadIdx.x - g * lanes;
+  extern __shared__ float red[];  // [groups][W]
   for (int c = blockIdx.x * groups + g; c < nchunks; c += gridDim.x * groups) {
     const int lo = c * chunk, hi = lo + chunk, end = hi < M ? hi : M;
+    // the `groups` chunks of this workgroup; a segment that starts before and ends after them makes
+    // every lane group see the same thing, so `merged` is uniform over the workgroup
+    const int block_lo = (c - g) * chunk, block_hi = block_lo + groups * chunk;
+    bool merged = false;
     for (int e = lane * VEC; e < W; e += lanes * VEC) {
       Vec<VEC> acc;
       acc.zero();
@@ -128,6 +133,9 @@ k_seg_stage1(TTArg<BATCHED> arg, int kind, int lanes, int chunk) {
         if (a >= lo && b <= hi) {
           float *dst = out + seg_out_index(cur, e, out_inner, nseg);
           if (fused) acc.store_sgd(dst, lr); else acc.store(dst);
+        } else if (a < block_lo && b > block_hi) {  // one partial for the whole workgroup, summed below
+          acc.store(red + (size_t)g * W + e);
+          merged = true;
         } else acc.store(partial + ((size_t)c * 2 + (a < lo ? 0 : 1)) * W + e);
       };
       int pos = lo;
@@ -174,6 +182,20 @@ k_seg_stage1(TTArg<BATCHED> arg, int kind, int lanes, int chunk) {
       }
       if (cur >= 0) flush();
     }
+    if (merged) {  // uniform: the chunks' sums in chunk order -> slot 0 of the workgroup's first chunk
+      __syncthreads();
+      if (g == 0)
+        for (int e = lane * VEC; e < W; e += lanes * VEC) {
+          Vec<VEC> acc, x;
+          acc.load(red + e);
+          for (int k = 1; k < groups; ++k) {
+            x.load(red + (size_t)k * W + e);
+            acc.add(x);
+          }
+          acc.store(partial + ((size_t)(c - g) * 2) * W + e);
+        }
+      __syncthreads();
+    }
   }
 }
 
@@ -209,25 +231,39 @@ k_seg_stage2(TTArg<BATCHED> arg, int kind, int lanes, int chunk) {
   const int a = seg_off[s], b = seg_off[s + 1];
   if (!(a >= lo && b > hi)) return;  // uniform: no segment starts here and runs past the chunk
   const int c1 = (b - 1) / chunk;
+  // Partials to add: slot 0 of the chunks c+1 .. c1, except that stage 1 has left ONE partial (in
+  // the first chunk) for every run of `groups` chunks handled by one workgroup that lies strictly
+  // inside the segment: the runs B0 .. B1.  Units in order: single chunks before the runs, one per
+  // run, single chunks after.
+  const int gc = groups * chunk;
+  int B0 = a / gc + 1, B1 = (b + gc - 1) / gc - 2;
+  int nh = c1 - c, nm = 0, nt = 0;
+  if (B0 <= B1) {
+    nh = B0 * groups - (c + 1);
+    nm = B1 - B0 + 1;
+    nt = c1 - (B1 + 1) * groups + 1;
+  }
+  const int units = nh + nm + nt;
+  auto unit_chunk = [&](int u) {
+    return u < nh ? c + 1 + u : (u < nh + nm ? (B0 + (u - nh)) * groups : (B1 + 1) * groups + (u - nh - nm));
+  };
   for (int e = lane * VEC; e < W; e += lanes * VEC) {
     Vec<VEC> acc;
     acc.zero();
-    if (g < groups) {
-      int cc = c + 1 + g;
-      for (; cc + (TT_SEG2_UNROLL - 1) * groups <= c1; cc += TT_SEG2_UNROLL * groups) {
-        Vec<VEC> x[TT_SEG2_UNROLL];  // independent loads in flight, added in chunk order
+    int u = g;
+    for (; u + (TT_SEG2_UNROLL - 1) * groups < units; u += TT_SEG2_UNROLL * groups) {
+      Vec<VEC> x[TT_SEG2_UNROLL];  // independent loads in flight, added in unit order
 #pragma unroll
-        for (int k = 0; k < TT_SEG2_UNROLL; ++k) x[k].load(partial + ((size_t)(cc + k * groups) * 2) * W + e);
+      for (int k = 0; k < TT_SEG2_UNROLL; ++k) x[k].load(partial + ((size_t)unit_chunk(u + k * groups) * 2) * W + e);
 #pragma unroll
-        for (int k = 0; k < TT_SEG2_UNROLL; ++k) acc.add(x[k]);
-      }
-      for (; cc <= c1; cc += groups) {
-        Vec<VEC> x;
-        x.load(partial + ((size_t)cc * 2) * W + e);
-        acc.add(x);
-      }
-      acc.store(red + (size_t)g * W + e);
+      for (int k = 0; k < TT_SEG2_UNROLL; ++k) acc.add(x[k]);
     }
+    for (; u < units; u += groups) {
+      Vec<VEC> x;
+      x.load(partial + ((size_t)unit_chunk(u) * 2) * W + e);
+      acc.add(x);
+    }
+    acc.store(red + (size_t)g * W + e);
   }
   __syncthreads();
   if (g == 0) {
@@ -280,8 +316,9 @@ tt_status seg_sum(const TTBatch &b, int kind, int chunk, int prof_kernel, hipStr
   if (nchunks > 0) {
     int blocks = tt_ceil_div(nchunks, groups);
     if (blocks > 8192) blocks = 8192;
-    if (vec4) TT_LAUNCH_T(k_seg_stage1, 4, blocks, TT_BLOCK, 0, s, b, kind, lanes, chunk);
-    else TT_LAUNCH_T(k_seg_stage1, 1, blocks, TT_BLOCK, 0, s, b, kind, lanes, chunk);
+    const size_t lds1 = sizeof(float) * (size_t)groups * W;
+    if (vec4) TT_LAUNCH_T(k_seg_stage1, 4, blocks, TT_BLOCK, lds1, s, b, kind, lanes, chunk);
+    else TT_LAUNCH_T(k_seg_stage1, 1, blocks, TT_BLOCK, lds1, s, b, kind, lanes, chunk);
   }
   long long blocks2 = nchunks;
   if (max_seg > blocks2) blocks2 = max_seg;  // dense kinds also zero-fill empty segments

@@ -74,7 +74,7 @@ k_bwd_mfma(TTArg<BATCHED> a) {
   const TTShape &sh = d.sh;
   // with the fused update the strip of core 1 this workgroup reads is also the one it rewrites at
   // the end (no other workgroup touches it), so g2 / dg2 may alias and carry no __restrict__
-  const float *__restrict__ g1 = d.g[0], *g2 = d.g[1], *__restrict__ g3t = d.plan.g3t;
+  const float *__restrict__ g1 = d.g[0], *g2 = d.g[1], *__restrict__ g3 = d.g[2];
   const int32_t *__restrict__ uniq_row = d.plan.uniq_row, *__restrict__ i2_seg = d.plan.i2_seg;
   const int4 *__restrict__ pref_meta = reinterpret_cast<const int4 *>(d.plan.pref_meta);
   const float *__restrict__ gagg = d.plan.gagg;
@@ -265,14 +265,15 @@ k_bwd_mfma(TTArg<BATCHED> a) {
         const int u = s_u0[mo + p] + r0;
         const int i3 = r0 < I3_STAGE ? s_i3[par][p][r0] : uniq_row[u] % sh.n3;
         const float4 *gp = reinterpret_cast<const float4 *>(gagg + (size_t)u * G::D);
-        const float4 *g3p = reinterpret_cast<const float4 *>(g3t + (size_t)i3 * G::S3) + sub;
+        // core 2 as stored, G3[r2][i3][0..3]: float4 r2 = sub + 16k of the row's slice
+        const float4 *g3p = reinterpret_cast<const float4 *>(g3) + (size_t)sub * sh.n3 + i3;
 #pragma unroll
         for (int k = 0; k < GQ; ++k) {  // float4 cc = sub + 16k of the strip: (j1, j2, 0..3)
           const int cc = sub + 16 * k;
           rg[k] = gp[(cc / G::JW) * D2 + j2base + (cc % G::JW)];
         }
 #pragma unroll
-        for (int k = 0; k < G3Q; ++k) r3[k] = g3p[16 * k];
+        for (int k = 0; k < G3Q; ++k) r3[k] = g3p[(size_t)16 * k * sh.n3];
         rvalid = 1;
       }
     }
@@ -617,8 +618,6 @@ int ttk_bwd_split(const TTShape &sh) {
 }
 
 tt_status ttk_backward_mfma(const TTBatch &b, hipStream_t s) {
-  tt_status st = ttk_pack_g3(b, s);
-  if (st != TT_OK) return st;
   if (b.host[0].sh.R1 == 32) return launch<32, 32, 8>(b, s);
   return launch<64, 64, 8>(b, s);
 }

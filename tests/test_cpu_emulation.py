@@ -107,6 +107,9 @@ def _run(emu, shape, cores, idx, off, grad, lr):
     ("plain", (5, 4, 6), (2, 3, 2), (1, 3, 5, 1), 150, 6),
     ("mfma_r32_split", (9, 3, 5), (4, 8, 4), (1, 32, 32, 1), 260, 5),   # 3 core-1 slices: split workgroups
     ("mfma_r64_two_strips", (3, 2, 11), (4, 8, 4), (1, 64, 64, 1), 120, 4),
+    # rows looked up hundreds of times: segments of the gradient merge that span whole workgroups of stage 1
+    ("mfma_r64_hot_rows", (2, 1, 2), (4, 8, 4), (1, 64, 64, 1), 800, 4),
+    ("plain_hot_rows", (1, 2, 2), (2, 3, 2), (1, 3, 5, 1), 2500, 3),
 ])
 def test_emulated_kernels_match_oracle(emu, ora, name, n, d, r, nb, ml):
     import gpu_util as g
