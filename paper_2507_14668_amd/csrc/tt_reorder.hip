@@ -130,8 +130,19 @@ k_radix_binscan(TTArg<BATCHED> a, int which, int nbins) {
   if (threadIdx.x == 0) bin_total[blockIdx.x] = carry;
 }
 
-// Stable scatter: elements of a tile are ranked in tile order (round i, thread t) so that equal
-// digits keep their relative order.
+// Orders the LDS accesses of the lanes of one wavefront (a wavefront executes them in program
+// order; this keeps the compiler from moving them across).
+__device__ __forceinline__ void tt_wave_lds_order() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Stable scatter.  Wavefront w of a tile owns its keys [w*256, w*256 + 256) and ranks them in four
+// rounds of 64 (position order), keeping per-digit running counts in its own row of wave_cnt; one
+// scan over the four rows per digit then gives every wavefront its base inside the tile's run of
+// that digit.  Equal digits keep their relative order: tiles in order, wavefronts in order, rounds
+// in order, lanes in order.
 template <bool BATCHED>
 __global__ void __launch_bounds__(TT_BLOCK)
 k_radix_scatter(TTArg<BATCHED> a, int which, int in_a, int shift, int bits, int self_scan) {
@@ -145,8 +156,9 @@ k_radix_scatter(TTArg<BATCHED> a, int which, int in_a, int shift, int bits, int 
                 *__restrict__ bin_total = d.tmp.bin_total;
   constexpr int MAXB = 1 << TT_SORT_MAX_BITS;
   constexpr int NW = TT_BLOCK / TT_WAVE;
+  constexpr int PER = MAXB / TT_BLOCK;  // bins per thread: PER consecutive ones
+  static_assert(PER == 4 && TT_SORT_ITEMS * TT_WAVE * NW == TT_SORT_TILE, "scatter geometry");
   __shared__ int gofs[MAXB];
-  __shared__ int run[MAXB];
   __shared__ int wave_cnt[NW][MAXB];
   __shared__ int tmp[NW + 1];
   const int nbins = 1 << bits, tile = blockIdx.x, count = *count_ptr;
@@ -154,26 +166,44 @@ k_radix_scatter(TTArg<BATCHED> a, int which, int in_a, int shift, int bits, int 
   if (base >= count) return;  // uniform for the workgroup
   const int lane = threadIdx.x & (TT_WAVE - 1), wave = threadIdx.x / TT_WAVE;
 
+  // all keys and payloads of the tile are requested first (one memory round trip for the tile,
+  // overlapped with the offset computation below)
+  int keys_r[TT_SORT_ITEMS], vals_r[TT_SORT_ITEMS];
+#pragma unroll
+  for (int i = 0; i < TT_SORT_ITEMS; ++i) {
+    const int pos = base + (wave * TT_SORT_ITEMS + i) * TT_WAVE + lane;
+    keys_r[i] = pos < count ? keys_in[pos] : 0;
+    vals_r[i] = pos < count ? vals_in[pos] : 0;
+  }
+
   // global offset of (bin, this tile) = exclusive scan of bin totals + tile prefix inside the bin
   {
-    constexpr int PER = MAXB / TT_BLOCK;
     int loc[PER], pre[PER], sum = 0;
+    const int b0 = threadIdx.x * PER;
 #pragma unroll
     for (int k = 0; k < PER; ++k) {
-      int b = threadIdx.x * PER + k;
-      loc[k] = (b < nbins && !self_scan) ? bin_total[b] : 0;
-      pre[k] = (b < nbins && !self_scan) ? hist[(size_t)tile * nbins + b] : 0;
+      loc[k] = (b0 + k < nbins && !self_scan) ? bin_total[b0 + k] : 0;
+      pre[k] = (b0 + k < nbins && !self_scan) ? hist[(size_t)tile * nbins + b0 + k] : 0;
     }
     if (self_scan) {  // raw per-tile counts: column totals and the prefix over the earlier tiles
-#pragma unroll 8
-      for (int t = 0; t < ntiles; ++t) {  // independent loads: eight tiles in flight
-#pragma unroll
-        for (int k = 0; k < PER; ++k) {
-          const int b = threadIdx.x * PER + k;
-          const int v = b < nbins ? hist[(size_t)t * nbins + b] : 0;
-          loc[k] += v;
-          pre[k] += t < tile ? v : 0;
+      if (nbins >= PER) {  // rows are multiples of 16 bytes: one int4 per tile and thread
+        if (b0 < nbins) {
+#pragma unroll 16
+          for (int t = 0; t < ntiles; ++t) {  // independent loads: sixteen tiles in flight
+            const int4 v = *reinterpret_cast<const int4 *>(hist + (size_t)t * nbins + b0);
+            const int m = t < tile ? -1 : 0;
+            loc[0] += v.x; loc[1] += v.y; loc[2] += v.z; loc[3] += v.w;
+            pre[0] += v.x & m; pre[1] += v.y & m; pre[2] += v.z & m; pre[3] += v.w & m;
+          }
         }
+      } else {
+        for (int t = 0; t < ntiles; ++t)
+#pragma unroll
+          for (int k = 0; k < PER; ++k) {
+            const int v = b0 + k < nbins ? hist[(size_t)t * nbins + b0 + k] : 0;
+            loc[k] += v;
+            pre[k] += t < tile ? v : 0;
+          }
       }
     }
 #pragma unroll
@@ -181,61 +211,60 @@ k_radix_scatter(TTArg<BATCHED> a, int which, int in_a, int shift, int bits, int 
     int total, ex = tt_block_excl_scan(sum, tmp, &total);
 #pragma unroll
     for (int k = 0; k < PER; ++k) {
-      int b = threadIdx.x * PER + k;
-      if (b < nbins) {
-        gofs[b] = ex + pre[k];
-        run[b] = 0;
+      if (b0 + k < nbins) {
+        gofs[b0 + k] = ex + pre[k];
 #pragma unroll
-        for (int w = 0; w < NW; ++w) wave_cnt[w][b] = 0;
+        for (int w = 0; w < NW; ++w) wave_cnt[w][b0 + k] = 0;
       }
       ex += loc[k];
     }
   }
   __syncthreads();
 
-  // all keys and payloads of the tile are requested before the first round (one memory round
-  // trip for the tile instead of one per round)
-  int keys_r[TT_SORT_ITEMS], vals_r[TT_SORT_ITEMS];
+  int rank[TT_SORT_ITEMS], digit[TT_SORT_ITEMS];
 #pragma unroll
   for (int i = 0; i < TT_SORT_ITEMS; ++i) {
-    const int pos = base + i * TT_BLOCK + threadIdx.x;
-    keys_r[i] = pos < count ? keys_in[pos] : 0;
-    vals_r[i] = pos < count ? vals_in[pos] : 0;
-  }
-#pragma unroll
-  for (int i = 0; i < TT_SORT_ITEMS; ++i) {
-    const int pos = base + i * TT_BLOCK + threadIdx.x;
+    const int pos = base + (wave * TT_SORT_ITEMS + i) * TT_WAVE + lane;
     const bool valid = pos < count;
-    const int key = keys_r[i], val = vals_r[i];
-    const int digit = valid ? (key >> shift) & (nbins - 1) : 0;
-    unsigned long long mask = __ballot(valid);
+    digit[i] = valid ? (keys_r[i] >> shift) & (nbins - 1) : 0;
+    unsigned long long mask = __ballot(valid);  // lanes of this round with the same digit
     for (int b = 0; b < bits; ++b) {
-      const bool bit = (digit >> b) & 1;
+      const bool bit = (digit[i] >> b) & 1;
       unsigned long long m = __ballot(valid && bit);
       mask &= bit ? m : ~m;
     }
     const unsigned long long lt = (lane == 0) ? 0ull : (~0ull >> (TT_WAVE - lane));
-    const int rank_in_wave = __popcll(mask & lt);
-    if (valid && rank_in_wave == 0) wave_cnt[wave][digit] = __popcll(mask);
-    __syncthreads();
-    int my = 0;
-    if (valid) {
-      my = run[digit] + rank_in_wave;
-      for (int w = 0; w < wave; ++w) my += wave_cnt[w][digit];
-    }
-    __syncthreads();
-    for (int b = threadIdx.x; b < nbins; b += TT_BLOCK) {
-      int add = 0;
+    const int rank_in_round = __popcll(mask & lt);
+    const int prev = valid ? wave_cnt[wave][digit[i]] : 0;  // this wavefront's earlier rounds
+    tt_wave_lds_order();
+    if (valid && rank_in_round == 0) wave_cnt[wave][digit[i]] = prev + __popcll(mask);
+    tt_wave_lds_order();
+    rank[i] = prev + rank_in_round;
+  }
+  __syncthreads();
+  {  // per digit: counts of the wavefronts -> their bases inside the tile's run of the digit
+    const int b0 = threadIdx.x * PER;
 #pragma unroll
-      for (int w = 0; w < NW; ++w) { add += wave_cnt[w][b]; wave_cnt[w][b] = 0; }
-      run[b] += add;
+    for (int k = 0; k < PER; ++k)
+      if (b0 + k < nbins) {
+        int run = 0;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+          const int c = wave_cnt[w][b0 + k];
+          wave_cnt[w][b0 + k] = run;
+          run += c;
+        }
+      }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < TT_SORT_ITEMS; ++i) {
+    const int pos = base + (wave * TT_SORT_ITEMS + i) * TT_WAVE + lane;
+    if (pos < count) {
+      const int dst = gofs[digit[i]] + wave_cnt[wave][digit[i]] + rank[i];
+      keys_out[dst] = keys_r[i];
+      vals_out[dst] = vals_r[i];
     }
-    if (valid) {
-      const int dst = gofs[digit] + my;
-      keys_out[dst] = key;
-      vals_out[dst] = val;
-    }
-    __syncthreads();
   }
 }
 

@@ -75,6 +75,10 @@ static inline unsigned long long __ballot(bool p) { return emu::wave_ballot(p); 
 static inline int __popcll(unsigned long long v) { return __builtin_popcountll(v); }
 static inline int __builtin_amdgcn_readfirstlane(int v) { return (int)(uint32_t)emu::wave_exchange((uint32_t)v, -2); }
 static inline int __builtin_amdgcn_readlane(int v, int lane) { return (int)(uint32_t)emu::wave_exchange((uint32_t)v, lane); }
+// lanes are fibers that run one after the other between collectives: a point that orders LDS
+// accesses inside a wavefront has to be one
+static inline void __builtin_amdgcn_wave_barrier() { emu::wave_exchange(0, -1); }
+#define __builtin_amdgcn_fence(order, scope) ((void)0)
 static inline long long clock64() { return 0; }
 
 static inline int atomicAdd(int *p, int v) { return __atomic_fetch_add(p, v, __ATOMIC_RELAXED); }
