@@ -106,7 +106,8 @@ typedef struct {
   int32_t *i1_seg;        /* [n[0]+1] prefix-slot range of each i1                        */
   int32_t *i2_chunk_off;  /* [n[1]+1] running count of 8-prefix chunks per i2 (the unit of
                              work of the matrix-core kernels); total in counts[5]          */
-  int32_t *chunk_i2;      /* [chunks] the i2 of every 8-prefix chunk                              */
+  int32_t *chunk_i2;      /* [chunks][4] per 8-prefix chunk: i2, position of its first prefix in  */
+                          /* prefs_by_i2 order, number of prefixes, 0                              */
   int32_t *pref_meta;     /* [max_prefixes][4] per prefix in i2 order: i1, first distinct-row
                              slot, distinct rows, prefix slot (one 16-byte load per prefix for
                              the matrix-core kernels)                                        */

@@ -79,7 +79,7 @@ size_t layout(const TTShape &sh, int64_t nnz, int64_t num_bags, char *base, tt_p
   q.i2_seg = ints(sh.n2 + 1);
   q.i1_seg = ints(sh.n1 + 1);
   q.i2_chunk_off = ints(sh.n2 + 1);
-  q.chunk_i2 = ints(max_pref / TT_MP + sh.n2 + 1);  // every i2 adds at most one partly filled chunk
+  q.chunk_i2 = ints(4 * (max_pref / TT_MP + sh.n2 + 1) + 4);  // 4 ints per chunk; every i2 adds at most one partly filled chunk
   q.pref_meta = ints(4 * max_pref + 4);
   q.counts = ints(16);
   q.rowbuf = floats((size_t)max_rows * sh.D);

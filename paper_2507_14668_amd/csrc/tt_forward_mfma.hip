@@ -39,15 +39,16 @@ struct FwdGeom {
   static_assert(TT_MP * 4 * RS <= TT_MP * PS && TT_MP % 4 == 0, "core-0 tile must fit in the P12 area it aliases");
 };
 
+constexpr int FWD_I3_STAGE = TT_BLOCK / TT_MP;  // i3 of the first 32 distinct rows of each prefix is staged in LDS
+
 template <bool BATCHED, int R1, int R2, int D2>
 __global__ void __launch_bounds__(TT_BLOCK)
 k_fwd_mfma(TTArg<BATCHED> a) {
   const TTDev &d = a.get();
   const TTShape &sh = d.sh;
   const float *__restrict__ g1 = d.g[0], *__restrict__ g2 = d.g[1], *__restrict__ g3t = d.plan.g3t;
-  const int32_t *__restrict__ counts = d.plan.counts, *__restrict__ uniq_row = d.plan.uniq_row,
-                *__restrict__ i2_seg = d.plan.i2_seg, *__restrict__ i2_chunk_off = d.plan.i2_chunk_off,
-                *__restrict__ chunk_i2 = d.plan.chunk_i2;
+  const int32_t *__restrict__ counts = d.plan.counts, *__restrict__ uniq_row = d.plan.uniq_row;
+  const int4 *__restrict__ chunk_rec = reinterpret_cast<const int4 *>(d.plan.chunk_i2);
   const int4 *__restrict__ pref_meta = reinterpret_cast<const int4 *>(d.plan.pref_meta);
   float *__restrict__ rowbuf = d.plan.rowbuf;
   using G = FwdGeom<R1, R2, D2>;
@@ -55,6 +56,7 @@ k_fwd_mfma(TTArg<BATCHED> a) {
   float *As = lds;    // [32][RS]  core-0 slices of the chunk (dead once F1 is done)
   float *P12s = lds;  // [8][PS]   prefix products of the chunk
   __shared__ int s_i1[TT_MP], s_u0[TT_MP], s_nr[TT_MP], s_item_off[TT_MP + 1];
+  __shared__ int s_i3[TT_MP][FWD_I3_STAGE];
 
   const int nchunks = counts[5];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -63,20 +65,17 @@ k_fwd_mfma(TTArg<BATCHED> a) {
   for (int work = blockIdx.x; work < nchunks * G::NSTRIP; work += gridDim.x) {
     const int chunk = work / G::NSTRIP, strip = work - chunk * G::NSTRIP;
     const int j2base = strip * G::JW;
-    const int i2 = chunk_i2[chunk];
-    const int cs = i2_seg[i2] + (chunk - i2_chunk_off[i2]) * TT_MP;
-    const int left_in_seg = i2_seg[i2 + 1] - cs;
-    const int cnt = left_in_seg < TT_MP ? left_in_seg : TT_MP;
+    const int4 rec = chunk_rec[chunk];  // i2, position of the chunk's first prefix, its prefixes
+    const int i2 = rec.x, cs = rec.y, cnt = rec.z;
 
-    // this wave's 64 columns of the strip of G2[:, i2], all r1 (B operand of F1)
-    float breg[G::KS1][4];
+    // This wavefront's 64 columns of the strip of G2[:, i2], all r1 (B operand of F1), as one
+    // float4 per row and lane: lane lm holds columns 4*lm .. 4*lm + 3, and MFMA tile nt takes
+    // component nt, i.e. tile column lm stands for strip column 64*wave + 4*lm + nt.
+    float4 bq[G::KS1];
 #pragma unroll
-    for (int ks = 0; ks < G::KS1; ++ks) {
-      const int r1 = 4 * ks + lq;
-      const float *rowp = g2 + ((size_t)r1 * sh.n2 + i2) * G::S2 + strip * 256 + 64 * wave + lm;
-#pragma unroll
-      for (int nt = 0; nt < 4; ++nt) breg[ks][nt] = rowp[16 * nt];
-    }
+    for (int ks = 0; ks < G::KS1; ++ks)
+      bq[ks] = *reinterpret_cast<const float4 *>(g2 + ((size_t)(4 * ks + lq) * sh.n2 + i2) * G::S2 + strip * 256 +
+                                                 64 * wave + 4 * lm);
 
     __syncthreads();  // the previous work item's readers of P12s / s_* are done
     if (threadIdx.x < TT_MP) {
@@ -95,6 +94,10 @@ k_fwd_mfma(TTArg<BATCHED> a) {
       for (int p = 0; p < TT_MP; ++p) { s_item_off[p] = run; run += (s_nr[p] + 3) >> 2; }
       s_item_off[TT_MP] = run;
     }
+    {  // i3 of the first rows of every prefix (F2 would otherwise start each item with this load)
+      const int p = threadIdx.x / FWD_I3_STAGE, r = threadIdx.x - p * FWD_I3_STAGE;
+      s_i3[p][r] = uniq_row[s_u0[p] + (r < s_nr[p] ? r : 0)] % sh.n3;
+    }
     // stage the core-0 slices: As[(p*4 + j1)][r1], zero rows for the unused tail of the chunk
     for (int e = threadIdx.x; e < TT_MP * 4 * R1; e += TT_BLOCK) {
       const int row = e / R1, r1 = e - row * R1;
@@ -111,14 +114,15 @@ k_fwd_mfma(TTArg<BATCHED> a) {
       for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int ks = 0; ks < G::KS1; ++ks) {
-      float a[MT];
+      float av[MT];
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) a[mt] = As[(16 * mt + lm) * G::RS + 4 * ks + lq];
+      for (int mt = 0; mt < MT; ++mt) av[mt] = As[(16 * mt + lm) * G::RS + 4 * ks + lq];
+      const float bv[4] = {bq[ks].x, bq[ks].y, bq[ks].z, bq[ks].w};
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt)
-          acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[mt], breg[ks][nt], acc[mt][nt], 0, 0, 0);
+          acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[mt], bv[nt], acc[mt][nt], 0, 0, 0);
     }
     __syncthreads();  // every wave has finished reading As before P12s overwrites it
 #pragma unroll
@@ -126,7 +130,7 @@ k_fwd_mfma(TTArg<BATCHED> a) {
       const int p = 4 * mt + lq;  // C row m = 4*lq + v  ->  prefix 4*mt + lq, j1 = v
 #pragma unroll
       for (int nt = 0; nt < 4; ++nt) {
-        const int cl = 64 * wave + 16 * nt + lm, j2loc = cl / R2, r2 = cl - j2loc * R2;
+        const int cl = 64 * wave + 4 * lm + nt, j2loc = cl / R2, r2 = cl - j2loc * R2;
 #pragma unroll
         for (int v = 0; v < 4; ++v)
           P12s[p * G::PS + (v * G::JW + j2loc) * G::Rp + r2] = acc[mt][nt][v];
@@ -135,23 +139,30 @@ k_fwd_mfma(TTArg<BATCHED> a) {
     __syncthreads();
 
     // ---- F2: items = (prefix, four distinct rows), dealt round-robin to the wavefronts -------
+    // The core-2 operand of a wavefront's next item is requested before the MFMAs of the current
+    // one (unconditionally: past the last item the last one is requested again and not used).
     const int total = s_item_off[TT_MP];
-    for (int it = wave; it < total; it += TT_BLOCK / 64) {
+    struct Item { int p, ubase, nrow; float a[G::KS2]; };
+    auto fetch = [&](int it, Item &x) __attribute__((always_inline)) {
+      it = it < total ? it : total - 1;
       int p = 0;
 #pragma unroll
       for (int k = 1; k < TT_MP; ++k) p += (s_item_off[k] <= it) ? 1 : 0;
       // p = number of k in 1..TT_MP-1 with item_off[k] <= it = the prefix whose range holds `it`
       const int quad = it - s_item_off[p];
-      const int ubase = s_u0[p] + 4 * quad;
-      const int left = s_nr[p] - 4 * quad, nrow = left < 4 ? left : 4;
+      x.p = p;
+      x.ubase = s_u0[p] + 4 * quad;
+      const int left = s_nr[p] - 4 * quad;
+      x.nrow = left < 4 ? left : 4;
       // A operand: G3[r2][i3(row)][j3], m = (row, j3) = lm, k = r2
-      const int arow = (lm >> 2) < nrow ? (lm >> 2) : nrow - 1;
-      const int i3 = uniq_row[ubase + arow] % sh.n3;
+      const int arow = 4 * quad + ((lm >> 2) < x.nrow ? (lm >> 2) : x.nrow - 1);
+      const int i3 = arow < FWD_I3_STAGE ? s_i3[p][arow] : uniq_row[s_u0[p] + arow] % sh.n3;
       const float *ap = g3t + (size_t)i3 * (R2 * 4) + lq * 4 + (lm & 3);
-      float a[G::KS2];
 #pragma unroll
-      for (int ks = 0; ks < G::KS2; ++ks) a[ks] = ap[16 * ks];
-      const float *bp = P12s + p * G::PS + lm * G::Rp + lq;
+      for (int ks = 0; ks < G::KS2; ++ks) x.a[ks] = ap[16 * ks];
+    };
+    auto compute = [&](const Item &x) __attribute__((always_inline)) {
+      const float *bp = P12s + x.p * G::PS + lm * G::Rp + lq;
       f32x4 o[G::NT2];
 #pragma unroll
       for (int nt = 0; nt < G::NT2; ++nt) o[nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
@@ -159,15 +170,29 @@ k_fwd_mfma(TTArg<BATCHED> a) {
       for (int ks = 0; ks < G::KS2; ++ks)
 #pragma unroll
         for (int nt = 0; nt < G::NT2; ++nt)
-          o[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[ks], bp[16 * nt * G::Rp + 4 * ks], o[nt], 0, 0, 0);
+          o[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(x.a[ks], bp[16 * nt * G::Rp + 4 * ks], o[nt], 0, 0, 0);
       // C[m = (row = lq, j3 = v)][n = cc]: one float4 of row ubase+lq at columns (j1, j2, 0..3)
-      if (lq < nrow) {
+      if (lq < x.nrow) {
 #pragma unroll
         for (int nt = 0; nt < G::NT2; ++nt) {
           const int cc = 16 * nt + lm, j1 = cc / G::JW, j2 = j2base + (cc - j1 * G::JW);
-          *reinterpret_cast<float4 *>(rowbuf + (size_t)(ubase + lq) * G::D + (j1 * D2 + j2) * 4) =
+          *reinterpret_cast<float4 *>(rowbuf + (size_t)(x.ubase + lq) * G::D + (j1 * D2 + j2) * 4) =
               make_float4(o[nt][0], o[nt][1], o[nt][2], o[nt][3]);
         }
+      }
+    };
+    constexpr int NWV = TT_BLOCK / 64;
+    if (wave < total) {  // uniform per wavefront
+      Item xa, xb;
+      fetch(wave, xa);
+      int it = wave;
+      while (true) {  // written out twice so that both operand sets stay in registers
+        fetch(it + NWV, xb);
+        compute(xa);
+        if ((it += NWV) >= total) break;
+        fetch(it + NWV, xa);
+        compute(xb);
+        if ((it += NWV) >= total) break;
       }
     }
   }

@@ -466,10 +466,14 @@ k_chunk_offsets(TTArg<BATCHED> a) {
     counts[5] = carry;
   }
   __syncthreads();  // the offsets written above are read back below (same workgroup)
-  int32_t *__restrict__ chunk_i2 = d.plan.chunk_i2;
+  int4 *__restrict__ chunk_rec = reinterpret_cast<int4 *>(d.plan.chunk_i2);  // i2, first prefix position, prefixes, 0
   for (int t = threadIdx.x; t < n2; t += TT_BLOCK) {
-    const int c1 = t + 1 < n2 ? chunk_off[t + 1] : carry;
-    for (int c = chunk_off[t]; c < c1; ++c) chunk_i2[c] = t;
+    const int c0 = chunk_off[t], c1 = t + 1 < n2 ? chunk_off[t + 1] : carry;
+    const int first = i2_seg[t], end = i2_seg[t + 1];
+    for (int c = c0; c < c1; ++c) {
+      const int cs = first + (c - c0) * TT_MP;
+      chunk_rec[c] = make_int4(t, cs, (end - cs) < TT_MP ? (end - cs) : TT_MP, 0);
+    }
   }
 }
 
