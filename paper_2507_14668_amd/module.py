@@ -128,3 +128,47 @@ class TTEmbeddingBag(torch.nn.Module):
             n2 += 1
         n1 = max(1, -(-num_embeddings // (n2 * n3)))
         return (n1, n2, n3)
+
+
+class TTEmbeddingBagCollection(torch.nn.Module):
+    """The sparse side of a DLRM: one `TTEmbeddingBag` per categorical feature (Section IV: the TT
+    tables replace the model's embedding tables one for one).
+
+    tables    iterable of `TTEmbeddingBag`, or of keyword dicts for its constructor
+    streams   number of side streams the tables are dealt to in forward (1: the current stream).
+              Tables are independent and a table's kernels are short, so several streams let the
+              GPU overlap them; autograd runs a table's backward on the stream of its forward.
+    forward(inputs) takes one `(input, offsets)` pair (or a 2-D `input`) per table and returns the
+    list of pooled outputs `[bags x embedding_dim]`, in table order.
+    """
+
+    def __init__(self, tables, streams: int = 1):
+        super().__init__()
+        self.tables = torch.nn.ModuleList(
+            [t if isinstance(t, TTEmbeddingBag) else TTEmbeddingBag(**t) for t in tables])
+        if streams < 1:
+            raise ValueError("streams must be at least 1")
+        self.num_streams = int(streams)
+        self._side = None
+
+    def forward(self, inputs):
+        inputs = list(inputs)
+        if len(inputs) != len(self.tables):
+            raise ValueError("one input per table: got %d for %d tables" % (len(inputs), len(self.tables)))
+        pairs = [x if isinstance(x, (tuple, list)) else (x, None) for x in inputs]
+        if self.num_streams == 1:
+            return [bag(inp, off) for bag, (inp, off) in zip(self.tables, pairs)]
+        if self._side is None:
+            self._side = [torch.cuda.Stream() for _ in range(self.num_streams)]
+        cur = torch.cuda.current_stream()
+        for s in self._side:
+            s.wait_stream(cur)
+        outs = []
+        for i, (bag, (inp, off)) in enumerate(zip(self.tables, pairs)):
+            with torch.cuda.stream(self._side[i % self.num_streams]):
+                outs.append(bag(inp, off))
+        for s in self._side:
+            cur.wait_stream(s)
+        for o in outs:
+            o.record_stream(cur)
+        return outs

@@ -101,3 +101,38 @@ def test_module_two_dimensional_input_against_dense_embedding_bag(g):
     (ref * w.cpu().double()).sum().backward()
     g.assert_close_rows(out.detach().cpu().numpy(), ref.detach().numpy(), g.FWD_RTOL, shape.dim, "module 2-D forward")
     g.assert_grads_close(shape, [p.grad for p in m.cores()], [x.grad.reshape(-1).numpy() for x in c], what="module 2-D dG")
+
+
+def test_collection_argument_checks():
+    import paper_2507_14668_amd as tt
+    kw = dict(num_embeddings=1000, embedding_dim=16, n=(10, 10, 10), d=(2, 2, 4), ranks=(4, 4), device="cpu")
+    coll = tt.TTEmbeddingBagCollection([kw, tt.TTEmbeddingBag(**kw)], streams=2)
+    assert len(coll.tables) == 2 and len(list(coll.parameters())) == 6
+    with pytest.raises(ValueError):
+        coll([torch.zeros(4, dtype=torch.int64)])  # one input per table
+    with pytest.raises(ValueError):
+        tt.TTEmbeddingBagCollection([kw], streams=0)
+
+
+@pytest.mark.gpu
+def test_collection_on_side_streams_equals_single_modules(g):
+    """Three tables of different shapes dealt to two side streams: outputs and core gradients must
+    equal, bit for bit, those of the same modules called one after the other on the current stream."""
+    import paper_2507_14668_amd as tt
+    problems = [wl.small_random_problem(400 + k, n=n, d=d, r=r, num_bags=300, max_len=4, sigma=0.3)
+                for k, (n, d, r) in enumerate([((6, 5, 7), (2, 3, 4), (1, 5, 6, 1)),
+                                               ((9, 3, 5), (4, 8, 4), (1, 32, 32, 1)),
+                                               ((3, 4, 11), (4, 8, 4), (1, 64, 64, 1))])]
+    results = []
+    for streams in (1, 2):
+        coll = tt.TTEmbeddingBagCollection([_module_like(tt, p[0], p[1]) for p in problems], streams=streams)
+        inputs = [(torch.from_numpy(p[2]).cuda(), torch.from_numpy(p[3]).cuda()) for p in problems]
+        for bag in coll.tables:
+            bag.include_last_offset = True  # the generator's offsets are CSR (bags + 1 entries)
+        outs = coll(inputs)
+        loss = sum((o * torch.from_numpy(p[4]).cuda().view_as(o)).sum() for o, p in zip(outs, problems))
+        loss.backward()
+        torch.cuda.synchronize()
+        results.append(([o.detach().clone() for o in outs], [p.grad.clone() for p in coll.parameters()]))
+    for a, b in zip(results[0][0] + results[0][1], results[1][0] + results[1][1]):
+        assert torch.equal(a, b)
