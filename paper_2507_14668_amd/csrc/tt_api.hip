@@ -91,8 +91,7 @@ size_t layout(const TTShape &sh, int64_t nnz, int64_t num_bags, char *base, tt_p
   size_t part = (size_t)(tt_ceil_div(nnz, TT_SEG_MIN_CHUNK) + 1) * 2 * sh.D;
   size_t part3 = (size_t)(tt_ceil_div(max_rows, TT_SEG_MIN_CHUNK) + 1) * 2 * sh.S3;
   size_t part1 = (size_t)(tt_ceil_div(max_pref, TT_SEG_MIN_CHUNK) + 1) * 2 * sh.S1;
-  if (part3 > part) part = part3;
-  if (part1 > part) part = part1;
+  if (part3 + part1 > part) part = part3 + part1;  // the core-2 and core-0 reductions run side by side
   q.partial = floats(part);
   q.g3t = floats((size_t)sh.n3 * sh.S3);
   const int split = ttk_bwd_split(sh);

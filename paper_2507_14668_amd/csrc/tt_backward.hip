@@ -103,22 +103,45 @@ __device__ __forceinline__ SegView seg_view(const TTDev &d, int kind) {
   return v;
 }
 
+// One launch serves one segmented sum, or two of the same vector width side by side (the first
+// `blocks` workgroups the first kind, the rest the second, whose partials follow the first kind's
+// in the table's partial buffer).
+struct SegLaunch {
+  int kind, chunk, blocks;
+  int kind_b, chunk_b;  // kind_b < 0: a single sum
+};
+struct SegPick { int kind, chunk, bid, nblk; size_t poff; };
+__device__ __forceinline__ SegPick seg_pick(const SegLaunch &L, const TTDev &d) {
+  SegPick p = {L.kind, L.chunk, (int)blockIdx.x, L.kind_b < 0 ? (int)gridDim.x : L.blocks, 0};
+  if (L.kind_b >= 0 && (int)blockIdx.x >= L.blocks) {
+    p.kind = L.kind_b; p.chunk = L.chunk_b; p.bid = (int)blockIdx.x - L.blocks;
+    p.nblk = (int)gridDim.x - L.blocks;
+    // the first kind's share of this table's partial buffer: two slots per chunk it can have
+    const long long cap = L.kind == SEG_GAGG ? d.plan.nnz : (L.kind == SEG_DG3 ? d.plan.max_rows : d.plan.max_prefixes);
+    const int W = L.kind == SEG_GAGG ? d.sh.D : (L.kind == SEG_DG3 ? d.sh.S3 : d.sh.S1);
+    p.poff = (size_t)((cap + L.chunk - 1) / L.chunk + 1) * 2 * W;
+  }
+  return p;
+}
+
 template <bool BATCHED, int VEC>
 __global__ void __launch_bounds__(TT_BLOCK)
-k_seg_stage1(TTArg<BATCHED> arg, int kind, int lanes, int chunk) {
-  const SegView sv = seg_view(arg.get(), kind);
+k_seg_stage1(TTArg<BATCHED> arg, SegLaunch L, int lanes) {
+  const SegPick pk = seg_pick(L, arg.get());
+  const int chunk = pk.chunk;
+  const SegView sv = seg_view(arg.get(), pk.kind);
   const int W = sv.W, seg_div = sv.seg_div, nsub = sv.nsub, out_inner = sv.out_inner, nseg = sv.nseg;
   const int32_t *__restrict__ seg_src = sv.seg_src, *__restrict__ gidx = sv.gidx,
                 *__restrict__ seg_off = sv.seg_off;
   const float *__restrict__ src = sv.src;
-  float *__restrict__ out = sv.out, *__restrict__ partial = sv.partial;
+  float *__restrict__ out = sv.out, *__restrict__ partial = sv.partial + pk.poff;
   const int M = *sv.count_ptr;
   const int nchunks = (M + chunk - 1) / chunk;
   const int fused = sv.fused;
   const float lr = sv.lr;
   const int groups = blockDim.x / lanes, g = threadIdx.x / lanes, lane = threadIdx.x - g * lanes;
   extern __shared__ float red[];  // [groups][W]
-  for (int c = blockIdx.x * groups + g; c < nchunks; c += gridDim.x * groups) {
+  for (int c = pk.bid * groups + g; c < nchunks; c += pk.nblk * groups) {
     const int lo = c * chunk, hi = lo + chunk, end = hi < M ? hi : M;
     // the `groups` chunks of this workgroup; a segment that starts before and ends after them makes
     // every lane group see the same thing, so `merged` is uniform over the workgroup
@@ -208,16 +231,18 @@ k_seg_stage1(TTArg<BATCHED> arg, int kind, int lanes, int chunk) {
 // LDS: red[groups][W]
 template <bool BATCHED, int VEC>
 __global__ void __launch_bounds__(TT_BLOCK)
-k_seg_stage2(TTArg<BATCHED> arg, int kind, int lanes, int chunk) {
-  const SegView sv = seg_view(arg.get(), kind);
+k_seg_stage2(TTArg<BATCHED> arg, SegLaunch L, int lanes) {
+  const SegPick pk = seg_pick(L, arg.get());
+  const int chunk = pk.chunk;
+  const SegView sv = seg_view(arg.get(), pk.kind);
   const int W = sv.W, seg_div = sv.seg_div, out_inner = sv.out_inner, nseg = sv.nseg, dense = sv.dense;
   const int32_t *__restrict__ seg_src = sv.seg_src, *__restrict__ seg_off = sv.seg_off;
   float *__restrict__ out = sv.out;
-  const float *__restrict__ partial = sv.partial;
+  const float *__restrict__ partial = sv.partial + pk.poff;
   extern __shared__ float red[];
   const int M = *sv.count_ptr;
   const int nchunks = (M + chunk - 1) / chunk;
-  const int c = blockIdx.x;
+  const int c = pk.bid;
   const int groups = blockDim.x / lanes, g = threadIdx.x / lanes, lane = threadIdx.x - g * lanes;
   if (dense && c < nseg && seg_off[c] == seg_off[c + 1] && g == 0) {
     Vec<VEC> z;
@@ -289,12 +314,14 @@ static int seg_chunk_for(long long count) {
   return c;
 }
 
-// Host side of one segmented sum over every table of the batch (chunk <= 0: chosen from the count).
-tt_status seg_sum(const TTBatch &b, int kind, int chunk, int prof_kernel, hipStream_t s) {
+// Launch shape of one segmented sum over every table of the batch (chunk <= 0: chosen from the count).
+struct SegParams { int W, vec, lanes, groups, chunk, nchunks, blocks1; long long blocks2; };
+static SegParams seg_params(const TTBatch &b, int kind, int chunk) {
   const TTShape &sh = b.host[0].sh;
-  const int W = kind == SEG_GAGG ? sh.D : (kind == SEG_DG3 ? sh.S3 : sh.S1);
-  const int out_inner = kind == SEG_DG3 ? sh.d3 : W;
-  bool vec4 = (W % 4) == 0 && (out_inner % 4) == 0;
+  SegParams p;
+  p.W = kind == SEG_GAGG ? sh.D : (kind == SEG_DG3 ? sh.S3 : sh.S1);
+  const int out_inner = kind == SEG_DG3 ? sh.d3 : p.W;
+  bool vec4 = (p.W % 4) == 0 && (out_inner % 4) == 0;
   long long max_count = 0, max_seg = 0;
   for (int t = 0; t < b.T; ++t) {
     const TTDev &d = b.host[t];
@@ -306,28 +333,53 @@ tt_status seg_sum(const TTBatch &b, int kind, int chunk, int prof_kernel, hipStr
     if (cnt > max_count) max_count = cnt;
     if (nseg > max_seg) max_seg = nseg;
   }
-  if (chunk <= 0) chunk = seg_chunk_for(max_count);
-  const int vec = vec4 ? 4 : 1;
-  int lanes = 1;
-  while (lanes < TT_WAVE && lanes * vec < W) lanes <<= 1;
-  const int groups = TT_BLOCK / lanes;
-  const int nchunks = tt_ceil_div(max_count, chunk);
+  p.chunk = chunk > 0 ? chunk : seg_chunk_for(max_count);
+  p.vec = vec4 ? 4 : 1;
+  p.lanes = 1;
+  while (p.lanes < TT_WAVE && p.lanes * p.vec < p.W) p.lanes <<= 1;
+  p.groups = TT_BLOCK / p.lanes;
+  p.nchunks = tt_ceil_div(max_count, p.chunk);
+  p.blocks1 = tt_ceil_div(p.nchunks, p.groups);
+  if (p.blocks1 > 8192) p.blocks1 = 8192;
+  p.blocks2 = p.nchunks > max_seg ? p.nchunks : max_seg;  // dense kinds also zero-fill empty segments
+  return p;
+}
+
+// One segmented sum, or (kind_b >= 0) two of the same launch shape in the same two launches.
+static tt_status seg_launch(const TTBatch &b, const SegParams &pa, int kind, const SegParams *pb, int kind_b,
+                            int prof_kernel, hipStream_t s) {
   TTProfScope prof(&b.host[0].plan, prof_kernel, s);  // both stages
-  if (nchunks > 0) {
-    int blocks = tt_ceil_div(nchunks, groups);
-    if (blocks > 8192) blocks = 8192;
-    const size_t lds1 = sizeof(float) * (size_t)groups * W;
-    if (vec4) TT_LAUNCH_T(k_seg_stage1, 4, blocks, TT_BLOCK, lds1, s, b, kind, lanes, chunk);
-    else TT_LAUNCH_T(k_seg_stage1, 1, blocks, TT_BLOCK, lds1, s, b, kind, lanes, chunk);
+  const size_t lds = sizeof(float) * (size_t)pa.groups * pa.W;
+  SegLaunch L1 = {kind, pa.chunk, pa.blocks1, pb ? kind_b : -1, pb ? pb->chunk : 0};
+  const long long g1 = pa.blocks1 + (pb ? pb->blocks1 : 0);
+  if (g1 > 0) {
+    if (pa.vec == 4) TT_LAUNCH_T(k_seg_stage1, 4, g1, TT_BLOCK, lds, s, b, L1, pa.lanes);
+    else TT_LAUNCH_T(k_seg_stage1, 1, g1, TT_BLOCK, lds, s, b, L1, pa.lanes);
   }
-  long long blocks2 = nchunks;
-  if (max_seg > blocks2) blocks2 = max_seg;  // dense kinds also zero-fill empty segments
-  if (blocks2 > 0) {
-    const size_t lds = sizeof(float) * (size_t)groups * W;
-    if (vec4) TT_LAUNCH_T(k_seg_stage2, 4, blocks2, TT_BLOCK, lds, s, b, kind, lanes, chunk);
-    else TT_LAUNCH_T(k_seg_stage2, 1, blocks2, TT_BLOCK, lds, s, b, kind, lanes, chunk);
+  SegLaunch L2 = L1;
+  L2.blocks = (int)pa.blocks2;
+  const long long g2 = pa.blocks2 + (pb ? pb->blocks2 : 0);
+  if (g2 > 0) {
+    if (pa.vec == 4) TT_LAUNCH_T(k_seg_stage2, 4, g2, TT_BLOCK, lds, s, b, L2, pa.lanes);
+    else TT_LAUNCH_T(k_seg_stage2, 1, g2, TT_BLOCK, lds, s, b, L2, pa.lanes);
   }
   return tt_launch_status();
+}
+
+tt_status seg_sum(const TTBatch &b, int kind, int chunk, int prof_kernel, hipStream_t s) {
+  const SegParams p = seg_params(b, kind, chunk);
+  return seg_launch(b, p, kind, nullptr, -1, prof_kernel, s);
+}
+
+// The core-2 and core-0 reductions are independent; when their vectors have the same width they
+// share their launches (the smaller one would otherwise pay two launches for a few workgroups).
+tt_status seg_sum_dg3_dg1(const TTBatch &b, hipStream_t s) {
+  const SegParams p3 = seg_params(b, SEG_DG3, 0), p1 = seg_params(b, SEG_DG1, 0);
+  if (p3.W == p1.W && p3.vec == p1.vec && p3.lanes == p1.lanes && p3.blocks1 > 0 && p1.blocks1 > 0)
+    return seg_launch(b, p3, SEG_DG3, &p1, SEG_DG1, -1, s);
+  tt_status st = seg_launch(b, p3, SEG_DG3, nullptr, -1, -1, s);
+  if (st != TT_OK) return st;
+  return seg_launch(b, p1, SEG_DG1, nullptr, -1, -1, s);
 }
 
 // ------------------------------------------------------------------ per-prefix contractions
@@ -625,10 +677,9 @@ tt_status ttk_backward_plan(const TTBatch &b, hipStream_t s) {
     const long long n2max = tt_batch_max(b, [](const TTDev &d) { return (long long)d.sh.n2; });
     TT_LAUNCH(k_bwd_dg2, n2max * col_tiles * r1_tiles, TT_BLOCK, 0, s, b, col_tiles);
   }
-  // 4a. core 2: sum the per-row contributions of all rows sharing i3
-  if ((st = seg_sum(b, SEG_DG3, 0, -1, s)) != TT_OK) return st;
-  // 4b. core 0: sum the per-prefix contributions of all prefixes sharing i1 (contiguous)
-  if ((st = seg_sum(b, SEG_DG1, 0, -1, s)) != TT_OK) return st;
+  // 4. core 2: sum the per-row contributions of all rows sharing i3; core 0: sum the per-prefix
+  //    contributions of all prefixes sharing i1 (contiguous)
+  if ((st = seg_sum_dg3_dg1(b, s)) != TT_OK) return st;
   return tt_launch_status();
 }
 
