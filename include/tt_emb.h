@@ -121,8 +121,7 @@ typedef struct {
   float *t3buf;           /* [max_rows][r2*d2] per-row contributions to core 2            */
   float *t1buf;           /* [max_prefixes][d0*r1] per-prefix contributions to core 0     */
   float *partial;         /* segmented-reduction partials                                 */
-  float *g3t;             /* [n2][r2][d2] slice-contiguous copy of core 2, refreshed by
-                             every forward / backward call that uses the matrix-core path  */
+  float *g3t;             /* reserved (4 floats): the kernels read core 2 as the table stores it */
   float *dg2part;         /* [split][core-1 shape] partial core-1 gradients when the backward
                              workgroups of a table with few core-1 slices are split        */
   void *sort_tmp;         /* radix-sort ping-pong buffers, histograms, scan temporaries   */

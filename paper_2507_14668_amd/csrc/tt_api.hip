@@ -93,7 +93,7 @@ size_t layout(const TTShape &sh, int64_t nnz, int64_t num_bags, char *base, tt_p
   size_t part1 = (size_t)(tt_ceil_div(max_pref, TT_SEG_MIN_CHUNK) + 1) * 2 * sh.S1;
   if (part3 + part1 > part) part = part3 + part1;  // the core-2 and core-0 reductions run side by side
   q.partial = floats(part);
-  q.g3t = floats((size_t)sh.n3 * sh.S3);
+  q.g3t = floats(0);
   const int split = ttk_bwd_split(sh);
   q.dg2part = floats(split > 1 ? (size_t)split * sh.R1 * sh.n2 * sh.S2 : 0);
   q.sort_tmp = take(tt_sort_tmp_bytes(nnz, max_rows, max_pref));

@@ -46,7 +46,7 @@ __global__ void __launch_bounds__(TT_BLOCK)
 k_fwd_mfma(TTArg<BATCHED> a) {
   const TTDev &d = a.get();
   const TTShape &sh = d.sh;
-  const float *__restrict__ g1 = d.g[0], *__restrict__ g2 = d.g[1], *__restrict__ g3t = d.plan.g3t;
+  const float *__restrict__ g1 = d.g[0], *__restrict__ g2 = d.g[1], *__restrict__ g3 = d.g[2];
   const int32_t *__restrict__ counts = d.plan.counts, *__restrict__ uniq_row = d.plan.uniq_row;
   const int4 *__restrict__ chunk_rec = reinterpret_cast<const int4 *>(d.plan.chunk_i2);
   const int4 *__restrict__ pref_meta = reinterpret_cast<const int4 *>(d.plan.pref_meta);
@@ -157,9 +157,9 @@ k_fwd_mfma(TTArg<BATCHED> a) {
       // A operand: G3[r2][i3(row)][j3], m = (row, j3) = lm, k = r2
       const int arow = 4 * quad + ((lm >> 2) < x.nrow ? (lm >> 2) : x.nrow - 1);
       const int i3 = arow < FWD_I3_STAGE ? s_i3[p][arow] : uniq_row[s_u0[p] + arow] % sh.n3;
-      const float *ap = g3t + (size_t)i3 * (R2 * 4) + lq * 4 + (lm & 3);
+      const float *ap = g3 + ((size_t)lq * sh.n3 + i3) * 4 + (lm & 3);  // G3[r2 = 4*ks + lq][i3][j3], as stored
 #pragma unroll
-      for (int ks = 0; ks < G::KS2; ++ks) x.a[ks] = ap[16 * ks];
+      for (int ks = 0; ks < G::KS2; ++ks) x.a[ks] = ap[(size_t)16 * ks * sh.n3];
     };
     auto compute = [&](const Item &x) __attribute__((always_inline)) {
       const float *bp = P12s + x.p * G::PS + lm * G::Rp + lq;
@@ -198,21 +198,6 @@ k_fwd_mfma(TTArg<BATCHED> a) {
   }
 }
 
-// g3t[i3][r2][j3] = G3[r2][i3][j3]: a row's core-2 slice becomes one contiguous block, so the
-// MFMA operand gathers touch 2-4 cache lines per wavefront load instead of 16.
-template <bool BATCHED>
-__global__ void k_pack_g3(TTArg<BATCHED> a) {
-  const TTDev &d = a.get();
-  const int n3 = d.sh.n3, R2 = d.sh.R2, d3 = d.sh.d3;
-  const float *__restrict__ g3 = d.g[2];
-  float *__restrict__ g3t = d.plan.g3t;
-  const int total = n3 * R2 * d3;
-  for (int e = blockIdx.x * blockDim.x + threadIdx.x; e < total; e += gridDim.x * blockDim.x) {
-    const int j3 = e % d3, r2 = (e / d3) % R2, i3 = e / (d3 * R2);
-    g3t[e] = g3[((size_t)r2 * n3 + i3) * d3 + j3];
-  }
-}
-
 template <int R1, int R2, int D2>
 tt_status launch(const TTBatch &b, hipStream_t s) {
   using G = FwdGeom<R1, R2, D2>;
@@ -242,22 +227,12 @@ tt_status launch(const TTBatch &b, hipStream_t s) {
 
 }  // namespace
 
-tt_status ttk_pack_g3(const TTBatch &b, hipStream_t s) {
-  const long long total = tt_batch_max(b, [](const TTDev &d) { return (long long)d.sh.n3 * d.sh.S3; });
-  int blocks = tt_ceil_div(total, TT_BLOCK);
-  if (blocks > 1024) blocks = 1024;
-  TT_LAUNCH(k_pack_g3, blocks, TT_BLOCK, 0, s, b);
-  return tt_launch_status();
-}
-
 bool ttk_forward_mfma_supported(const TTShape &sh) {
   if (sh.d1 != 4 || sh.d3 != 4 || sh.d2 != 8) return false;
   return (sh.R1 == 32 && sh.R2 == 32) || (sh.R1 == 64 && sh.R2 == 64);
 }
 
 tt_status ttk_forward_mfma(const TTBatch &b, hipStream_t s) {
-  tt_status st = ttk_pack_g3(b, s);
-  if (st != TT_OK) return st;
   if (b.host[0].sh.R1 == 32) return launch<32, 32, 8>(b, s);
   return launch<64, 64, 8>(b, s);
 }

@@ -123,8 +123,6 @@ tt_status ttk_reorder(const TTBatch &b, hipStream_t s);
 tt_status ttk_forward_plan(const TTBatch &b, hipStream_t s);
 bool ttk_forward_mfma_supported(const TTShape &sh);
 tt_status ttk_forward_mfma(const TTBatch &b, hipStream_t s);
-// slice-contiguous copy of core 2 for the matrix-core kernels: g3t[i3][r2][j3] = G3[r2][i3][j3]
-tt_status ttk_pack_g3(const TTBatch &b, hipStream_t s);
 // number of 256-column strips a core-1 slice is cut into by the matrix-core kernels (1 when the
 // shape is served by the plain-ALU kernels); t3buf / t1buf hold one contribution per strip
 int ttk_mfma_strips(const TTShape &sh);
