@@ -18,6 +18,9 @@ template <bool BATCHED>
 __global__ void k_init_counts(TTArg<BATCHED> a) {
   const TTDev &d = a.get();
   if (threadIdx.x < 16) d.plan.counts[threadIdx.x] = (threadIdx.x == 3) ? d.nnz : 0;
+  // a table without lookups has no workgroup that would write the terminal segment entries
+  if (threadIdx.x == 16) d.plan.row_seg[0] = 0;
+  if (threadIdx.x == 17) d.plan.pref_seg[0] = 0;
 }
 
 // One thread per lookup: validate, apply the optional bijection, emit (row, position) and the
@@ -66,20 +69,18 @@ struct SortBufs {
   const int32_t *count_ptr;
   int ntiles;
 };
+// (selects, not an if / else chain: with a `which` that depended on the workgroup index such a
+// chain was once compiled to code that left one pointer of sort 2 at sort 1's value)
 __device__ __forceinline__ SortBufs sort_bufs(const TTDev &d, int which) {
   SortBufs b;
-  if (which == 0) {
-    b.ka = d.plan.sorted_row; b.va = d.plan.perm; b.kb = d.tmp.keys_alt; b.vb = d.tmp.vals_alt;
-    b.count_ptr = d.plan.counts + 3; b.ntiles = d.sort_tiles;
-  } else if (which == 1) {
-    b.ka = d.plan.i3_of_sorted; b.va = d.plan.rows_by_i3; b.kb = d.tmp.k3_alt; b.vb = d.tmp.v3_alt;
-    b.count_ptr = d.plan.counts + 0;
-    b.ntiles = (int)((d.plan.max_rows + TT_SORT_TILE - 1) / TT_SORT_TILE);
-  } else {
-    b.ka = d.tmp.k2; b.va = d.plan.prefs_by_i2; b.kb = d.tmp.k2_alt; b.vb = d.tmp.v2_alt;
-    b.count_ptr = d.plan.counts + 1;
-    b.ntiles = (int)((d.plan.max_prefixes + TT_SORT_TILE - 1) / TT_SORT_TILE);
-  }
+  const bool s0 = which == 0, s1 = which == 1;
+  b.ka = s0 ? d.plan.sorted_row : (s1 ? d.plan.i3_of_sorted : d.tmp.k2);
+  b.va = s0 ? d.plan.perm : (s1 ? d.plan.rows_by_i3 : d.plan.prefs_by_i2);
+  b.kb = s0 ? d.tmp.keys_alt : (s1 ? d.tmp.k3_alt : d.tmp.k2_alt);
+  b.vb = s0 ? d.tmp.vals_alt : (s1 ? d.tmp.v3_alt : d.tmp.v2_alt);
+  b.count_ptr = d.plan.counts + (s0 ? 3 : (s1 ? 0 : 1));
+  const long long cap = s1 ? d.plan.max_rows : d.plan.max_prefixes;
+  b.ntiles = s0 ? d.sort_tiles : (int)((cap + TT_SORT_TILE - 1) / TT_SORT_TILE);
   return b;
 }
 
@@ -271,6 +272,7 @@ k_radix_scatter(TTArg<BATCHED> a, int which, int in_a, int shift, int bits, int 
 // ------------------------------------------------------------------ distinct rows / prefixes
 #define TT_UNIQ_ITEMS 4
 #define TT_UNIQ_TILE (TT_BLOCK * TT_UNIQ_ITEMS)
+#define TT_UNIQ_SELF_SCAN_TILES 1024  // up to this many tiles k_uniq_emit does without k_uniq_scan
 
 __device__ __forceinline__ void head_flags(const int32_t *__restrict__ keys, int s, int nnz,
                                            int sentinel, int n3, int &hr, int &hp) {
@@ -342,11 +344,15 @@ k_uniq_scan(TTArg<BATCHED> a) {
   }
 }
 
+// Also emits the keys of the two grouping sorts (i3 of every distinct row, i2 of every distinct
+// prefix; a3 / a2: which of their ping-pong buffers the sorts start from).  With `self_scan` the
+// tile sums are the raw ones of k_uniq_reduce: every workgroup adds up those of the earlier tiles
+// itself and the last one writes the totals (one launch less than scanning them first).
 template <bool BATCHED>
 __global__ void __launch_bounds__(TT_BLOCK)
-k_uniq_emit(TTArg<BATCHED> a) {
+k_uniq_emit(TTArg<BATCHED> a, int a3, int a2, int self_scan) {
   const TTDev &d = a.get();
-  const int nnz = d.nnz, sentinel = d.sh.sentinel, n3 = d.sh.n3;
+  const int nnz = d.nnz, sentinel = d.sh.sentinel, n3 = d.sh.n3, n2 = d.sh.n2;
   const int ntiles = (nnz + TT_UNIQ_TILE - 1) / TT_UNIQ_TILE;
   if ((int)blockIdx.x >= ntiles) return;  // uniform
   const int32_t *__restrict__ keys = d.plan.sorted_row, *__restrict__ perm = d.plan.perm,
@@ -356,6 +362,10 @@ k_uniq_emit(TTArg<BATCHED> a) {
           *__restrict__ lookup2row = d.plan.lookup2row, *__restrict__ uniq_row = d.plan.uniq_row,
           *__restrict__ row_seg = d.plan.row_seg, *__restrict__ row2pref = d.plan.row2pref,
           *__restrict__ uniq_pref = d.plan.uniq_pref, *__restrict__ pref_seg = d.plan.pref_seg;
+  int32_t *__restrict__ k3 = a3 ? d.plan.i3_of_sorted : d.tmp.k3_alt;
+  int32_t *__restrict__ v3 = a3 ? d.plan.rows_by_i3 : d.tmp.v3_alt;
+  int32_t *__restrict__ k2 = a2 ? d.tmp.k2 : d.tmp.k2_alt;
+  int32_t *__restrict__ v2 = a2 ? d.plan.prefs_by_i2 : d.tmp.v2_alt;
   __shared__ int tmp[TT_BLOCK / TT_WAVE + 1];
   const int s0 = blockIdx.x * TT_UNIQ_TILE + threadIdx.x * TT_UNIQ_ITEMS;
   int hr[TT_UNIQ_ITEMS], hp[TT_UNIQ_ITEMS], sr = 0, sp = 0;
@@ -364,9 +374,29 @@ k_uniq_emit(TTArg<BATCHED> a) {
     head_flags(keys, s0 + i, nnz, sentinel, n3, hr[i], hp[i]);
     sr += hr[i]; sp += hp[i];
   }
-  int tot;
-  int er = tt_block_excl_scan(sr, tmp, &tot) + tile_sums[blockIdx.x];
-  int ep = tt_block_excl_scan(sp, tmp, &tot) + tile_sums[ntiles + blockIdx.x];
+  int base_r, base_p;
+  if (self_scan) {  // uniform
+    int vr = 0, vp = 0;
+    for (int t = threadIdx.x; t < (int)blockIdx.x; t += TT_BLOCK) {
+      vr += tile_sums[t];
+      vp += tile_sums[ntiles + t];
+    }
+    tt_block_excl_scan(vr, tmp, &base_r);
+    tt_block_excl_scan(vp, tmp, &base_p);
+  } else {
+    base_r = tile_sums[blockIdx.x];
+    base_p = tile_sums[ntiles + blockIdx.x];
+  }
+  int tot_r, tot_p;
+  int er = tt_block_excl_scan(sr, tmp, &tot_r) + base_r;
+  int ep = tt_block_excl_scan(sp, tmp, &tot_p) + base_p;
+  if (self_scan && (int)blockIdx.x == ntiles - 1 && threadIdx.x == 0) {  // the totals
+    int32_t *__restrict__ counts = d.plan.counts;
+    counts[0] = base_r + tot_r;
+    counts[1] = base_p + tot_p;
+    row_seg[base_r + tot_r] = counts[2];
+    pref_seg[base_p + tot_p] = base_r + tot_r;
+  }
 #pragma unroll
   for (int i = 0; i < TT_UNIQ_ITEMS; ++i) {
     const int s = s0 + i;
@@ -382,36 +412,19 @@ k_uniq_emit(TTArg<BATCHED> a) {
       uniq_row[slot_r] = key;
       row_seg[slot_r] = s;
       row2pref[slot_r] = ep - 1;
+      k3[slot_r] = key % n3;
+      v3[slot_r] = slot_r;
     }
     if (hp[i]) {
       uniq_pref[ep - 1] = key / n3;
       pref_seg[ep - 1] = slot_r;
+      k2[ep - 1] = (key / n3) % n2;
+      v2[ep - 1] = ep - 1;
     }
   }
 }
 
 // ------------------------------------------------------------------ groupings by i3 / i2 / i1
-template <bool BATCHED>
-__global__ void k_group_keys(TTArg<BATCHED> a, int a3, int a2) {
-  const TTDev &d = a.get();
-  const int32_t *__restrict__ counts = d.plan.counts, *__restrict__ uniq_row = d.plan.uniq_row,
-                *__restrict__ uniq_pref = d.plan.uniq_pref;
-  const int n3 = d.sh.n3, n2 = d.sh.n2;
-  int32_t *__restrict__ k3 = a3 ? d.plan.i3_of_sorted : d.tmp.k3_alt;
-  int32_t *__restrict__ v3 = a3 ? d.plan.rows_by_i3 : d.tmp.v3_alt;
-  int32_t *__restrict__ k2 = a2 ? d.tmp.k2 : d.tmp.k2_alt;
-  int32_t *__restrict__ v2 = a2 ? d.plan.prefs_by_i2 : d.tmp.v2_alt;
-  const int ur = counts[0], up = counts[1];
-  for (int u = blockIdx.x * blockDim.x + threadIdx.x; u < ur; u += gridDim.x * blockDim.x) {
-    k3[u] = uniq_row[u] % n3;
-    v3[u] = u;
-    if (u < up) {
-      k2[u] = uniq_pref[u] % n2;
-      v2[u] = u;
-    }
-  }
-}
-
 // seg[t] = first position of the sorted keys whose key is >= t, for t = 0..nkeys: the thread of
 // position u fills the entries between its predecessor's key and its own (one memory round trip
 // per thread instead of a binary search), the thread of the last position also the tail.
@@ -569,20 +582,18 @@ tt_status ttk_reorder(const TTBatch &b, hipStream_t s) {
   // distinct rows and prefixes
   const int utiles = (int)tt_batch_max(b, [](const TTDev &d) {
     return (long long)tt_ceil_div(d.nnz, TT_UNIQ_TILE); });
-  if (utiles > 0) TT_LAUNCH(k_uniq_reduce, utiles, TT_BLOCK, 0, s, b);
-  TT_LAUNCH(k_uniq_scan, 1, TT_BLOCK, 0, s, b);
-  if (utiles > 0) TT_LAUNCH(k_uniq_emit, utiles, TT_BLOCK, 0, s, b);
-
   // groupings: distinct rows by i3, distinct prefixes by i2 (stable), i1 ranges
   const int bits3 = bit_length(tt_batch_max(b, [](const TTDev &d) { return (long long)d.sh.n3 - 1; }));
   const int bits2 = bit_length(tt_batch_max(b, [](const TTDev &d) { return (long long)d.sh.n2 - 1; }));
   const int a3 = (radix_plan(bits3).passes % 2) == 0, a2 = (radix_plan(bits2).passes % 2) == 0;
   const long long max_rows = tt_batch_max(b, [](const TTDev &d) { return (long long)d.plan.max_rows; });
   const long long max_pref = tt_batch_max(b, [](const TTDev &d) { return (long long)d.plan.max_prefixes; });
+  // short inputs: every emit workgroup adds up the earlier tiles' sums itself (no scan launch)
+  const int uniq_self = (utiles > 0 && utiles <= TT_UNIQ_SELF_SCAN_TILES) ? 1 : 0;
+  if (utiles > 0) TT_LAUNCH(k_uniq_reduce, utiles, TT_BLOCK, 0, s, b);
+  if (!uniq_self) TT_LAUNCH(k_uniq_scan, 1, TT_BLOCK, 0, s, b);
+  if (utiles > 0) TT_LAUNCH(k_uniq_emit, utiles, TT_BLOCK, 0, s, b, a3, a2, uniq_self);
   if (max_rows > 0) {
-    int blocks = tt_ceil_div(max_rows, TT_BLOCK);
-    if (blocks > 2048) blocks = 2048;
-    TT_LAUNCH(k_group_keys, blocks, TT_BLOCK, 0, s, b, a3, a2);
     st = radix_sort(b, 1, tt_ceil_div(max_rows, TT_SORT_TILE), bits3, s);
     if (st != TT_OK) return st;
     st = radix_sort(b, 2, tt_ceil_div(max_pref, TT_SORT_TILE), bits2, s);

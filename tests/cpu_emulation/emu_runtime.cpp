@@ -253,8 +253,11 @@ void launch(dim3 grid, dim3 block, size_t lds, const char *name, const std::func
   g_gridDim = grid; g_blockDim = block;
   g_lds = lds ? malloc(lds) : nullptr;   // exact size: ASan sees dynamic-LDS overruns
   if (g_lds) memset(g_lds, 0x7F, lds);   // defined garbage (NaN pattern): uninitialised-read hunts target global memory
+  // EMU_REVERSE runs the workgroups of a launch last to first: results must not depend on the order
+  static const bool reverse = getenv("EMU_REVERSE") != nullptr;
   for (unsigned by = 0; by < grid.y; ++by)
-    for (unsigned bx = 0; bx < grid.x; ++bx) {
+    for (unsigned bi = 0; bi < grid.x; ++bi) {
+      const unsigned bx = reverse ? grid.x - 1 - bi : bi;
       g_blockIdx = dim3(bx, by, 0);
       int nwaves = 0;
       for (int w = 0; w < NW; ++w) {
