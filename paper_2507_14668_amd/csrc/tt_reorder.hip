@@ -69,18 +69,22 @@ struct SortBufs {
   const int32_t *count_ptr;
   int ntiles;
 };
-// (selects, not an if / else chain: with a `which` that depended on the workgroup index such a
-// chain was once compiled to code that left one pointer of sort 2 at sort 1's value)
+// `which` has to be a plain kernel argument: a variant that took it from the workgroup index (two
+// sorts in one launch) was compiled to code that left one pointer of sort 2 at sort 1's value.
 __device__ __forceinline__ SortBufs sort_bufs(const TTDev &d, int which) {
   SortBufs b;
-  const bool s0 = which == 0, s1 = which == 1;
-  b.ka = s0 ? d.plan.sorted_row : (s1 ? d.plan.i3_of_sorted : d.tmp.k2);
-  b.va = s0 ? d.plan.perm : (s1 ? d.plan.rows_by_i3 : d.plan.prefs_by_i2);
-  b.kb = s0 ? d.tmp.keys_alt : (s1 ? d.tmp.k3_alt : d.tmp.k2_alt);
-  b.vb = s0 ? d.tmp.vals_alt : (s1 ? d.tmp.v3_alt : d.tmp.v2_alt);
-  b.count_ptr = d.plan.counts + (s0 ? 3 : (s1 ? 0 : 1));
-  const long long cap = s1 ? d.plan.max_rows : d.plan.max_prefixes;
-  b.ntiles = s0 ? d.sort_tiles : (int)((cap + TT_SORT_TILE - 1) / TT_SORT_TILE);
+  if (which == 0) {
+    b.ka = d.plan.sorted_row; b.va = d.plan.perm; b.kb = d.tmp.keys_alt; b.vb = d.tmp.vals_alt;
+    b.count_ptr = d.plan.counts + 3; b.ntiles = d.sort_tiles;
+  } else if (which == 1) {
+    b.ka = d.plan.i3_of_sorted; b.va = d.plan.rows_by_i3; b.kb = d.tmp.k3_alt; b.vb = d.tmp.v3_alt;
+    b.count_ptr = d.plan.counts + 0;
+    b.ntiles = (int)((d.plan.max_rows + TT_SORT_TILE - 1) / TT_SORT_TILE);
+  } else {
+    b.ka = d.tmp.k2; b.va = d.plan.prefs_by_i2; b.kb = d.tmp.k2_alt; b.vb = d.tmp.v2_alt;
+    b.count_ptr = d.plan.counts + 1;
+    b.ntiles = (int)((d.plan.max_prefixes + TT_SORT_TILE - 1) / TT_SORT_TILE);
+  }
   return b;
 }
 
