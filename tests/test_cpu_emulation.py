@@ -184,3 +184,20 @@ def test_emulated_kernels_on_random_shapes(emu, ora):
             g.assert_grads_close(shape, dg, ref_dg, what="%s dG (%s)" % (what, arm))
         for k in range(3):
             assert np.array_equal(res["fused"][k], res["updated"][k]), what
+
+
+def test_results_do_not_depend_on_workgroup_order(asan_harness):
+    """The emulation runs the workgroups of a launch one after the other; last to first must give
+    the same bits as first to last (no kernel relies on another workgroup of its launch)."""
+    sums = []
+    for reverse in (False, True):
+        env = dict(os.environ, ASAN_OPTIONS="detect_stack_use_after_return=0:detect_leaks=0", UBSAN_OPTIONS="halt_on_error=1")
+        if reverse:
+            env["EMU_REVERSE"] = "1"
+        res = subprocess.run([asan_harness, "mfma"], capture_output=True, text=True, env=env, timeout=900)
+        text = res.stdout + res.stderr
+        assert res.returncode == 0 and "ERROR" not in text, text[-3000:]
+        sums.append([ln for ln in text.splitlines() if ln.startswith("checksum")])
+    # first checksum: the planned arm (no atomics, must not move); second: the naive arm, whose
+    # backward adds with float atomics in arrival order and is not expected to be bit-stable
+    assert len(sums[0]) == 2 and sums[0][0] == sums[1][0]
