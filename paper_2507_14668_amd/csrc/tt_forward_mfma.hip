@@ -30,7 +30,10 @@ struct FwdGeom {
   static constexpr int RS = R1 + 4;        // LDS row stride of the core-0 tile
   static constexpr int Rp = R2 + 4;        // LDS row stride of a P12 row [(j1,j2)][r2]
   static constexpr int CC = 4 * JW;        // (j1, j2) columns per strip
-  static constexpr int PS = CC * Rp + 16;  // LDS stride between the P12 blocks of two prefixes
+  // LDS stride between the P12 blocks of two prefixes.  F1 stores one value per lane at
+  // [prefix = lq (+4 mt)][...][r2 = 4*lm + nt]: 4*lm covers every fourth bank, so the stride is
+  // 17 mod 32 (lq -> 0, 17, 2, 19: the four residues mod 4) and a store is 2-way at worst.
+  static constexpr int PS = CC * Rp + 17;
   static constexpr int KS1 = R1 / 4, KS2 = R2 / 4;
   static constexpr int NT2 = CC / 16;
   static constexpr int D = 4 * D2 * 4;
