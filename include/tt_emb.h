@@ -8,10 +8,11 @@
  * Conventions shared by every call
  * --------------------------------
  * - "DEVICE" pointers are HIP device memory of the current device; "HOST"
- *   pointers are ordinary host memory.  The library allocates nothing and keeps
- *   no global state: every buffer, including the workspace a plan lives in, is
- *   owned by the caller and merely borrowed until the work enqueued by the call
- *   has finished on `stream`.
+ *   pointers are ordinary host memory.  The library allocates no device memory:
+ *   every buffer, including the workspace a plan lives in, is owned by the caller
+ *   and merely borrowed until the work enqueued by the call has finished on
+ *   `stream`.  The only process-wide state is a once-per-process set-up of kernel
+ *   launch attributes (thread-safe); calls may be issued from several host threads.
  * - All work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
  *   default stream).  No call synchronises or copies device->host, except
  *   tt_plan_status.
@@ -117,11 +118,12 @@ typedef struct {
   /* -- float scratch used by forward / backward (contents are transient) --------------- */
   float *rowbuf;          /* [max_rows][D] reconstructed distinct rows                    */
   float *gagg;            /* [max_rows][D] output gradients merged per distinct row       */
-  float *hbuf;            /* [max_prefixes][d0*d1*r2] per-prefix right partial gradients  */
+  float *hbuf;            /* [max_prefixes][d0*d1*r2] per-prefix right partial gradients;
+                             NULL when the table is served by the matrix-core kernels, which
+                             keep them on chip                                               */
   float *t3buf;           /* [max_rows][r2*d2] per-row contributions to core 2            */
   float *t1buf;           /* [max_prefixes][d0*r1] per-prefix contributions to core 0     */
   float *partial;         /* segmented-reduction partials                                 */
-  float *g3t;             /* reserved (4 floats): the kernels read core 2 as the table stores it */
   float *dg2part;         /* [split][core-1 shape] partial core-1 gradients when the backward
                              workgroups of a table with few core-1 slices are split        */
   void *sort_tmp;         /* radix-sort ping-pong buffers, histograms, scan temporaries   */
@@ -132,7 +134,10 @@ typedef struct {
 } tt_plan;
 
 /* Bytes of DEVICE workspace tt_index_reorder needs for this table shape and batch size
- * (0 on invalid arguments).  The workspace must be 256-byte aligned. */
+ * (0 on invalid arguments).  The workspace must be 256-byte aligned.  The size depends on which
+ * kernels serve the table (shape, and whether table->core[1] and core[2] are 16-byte aligned): pass
+ * the table with the cores it will be used with.  A backward call whose cores are less aligned than
+ * those the workspace was sized for returns TT_ERR_WORKSPACE. */
 size_t tt_workspace_bytes(const tt_table *table, int64_t nnz, int64_t num_bags);
 
 /*

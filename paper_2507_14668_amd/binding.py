@@ -13,8 +13,7 @@ import os
 import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-# TT_EMB_LIB lets a developer load an instrumented build of the same library
-LIB_PATH = os.environ.get("TT_EMB_LIB", os.path.join(_PKG, "libtt_emb.so"))
+LIB_PATH = os.path.join(_PKG, "libtt_emb.so")
 
 TT_OK = 0
 TT_ERR_INVALID_ARG = -1
@@ -46,7 +45,7 @@ _I32P = ctypes.c_void_p
 _PLAN_INT_ARRAYS = ("sorted_row", "perm", "bag_of_sorted", "slot_of_sorted", "lookup2row", "uniq_row",
                     "row_seg", "row2pref", "uniq_pref", "pref_seg", "rows_by_i3", "i3_of_sorted",
                     "i3_seg", "prefs_by_i2", "i2_seg", "i1_seg", "i2_chunk_off", "chunk_i2", "pref_meta", "counts")
-_PLAN_FLOAT_ARRAYS = ("rowbuf", "gagg", "hbuf", "t3buf", "t1buf", "partial", "g3t", "dg2part")
+_PLAN_FLOAT_ARRAYS = ("rowbuf", "gagg", "hbuf", "t3buf", "t1buf", "partial", "dg2part")
 
 
 class CPlan(ctypes.Structure):

@@ -2,12 +2,9 @@
 #include <stdlib.h>
 #include <string.h>
 
-#include "tt_internal.h"
+#include <mutex>
 
-bool tt_mfma_enabled() {
-  static const bool enabled = getenv("TT_EMB_NO_MFMA") == nullptr;
-  return enabled;
-}
+#include "tt_internal.h"
 
 namespace {
 
@@ -46,7 +43,11 @@ bool cores_present(const tt_table *t) { return t->core[0] && t->core[1] && t->co
 size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 
 // Carves the workspace.  With base == nullptr only the total size is computed.
-size_t layout(const TTShape &sh, int64_t nnz, int64_t num_bags, char *base, tt_plan *p) {
+// `mfma`: the table is served by the matrix-core kernels, which keep the per-prefix right partials
+// in LDS; only the plain-ALU kernels need them in memory (hbuf).
+// `forward_only`: the plan will serve tt_emb_bag_forward only; the backward scratch is left out.
+size_t layout(const TTShape &sh, bool mfma, int64_t nnz, int64_t num_bags, char *base, tt_plan *p,
+              bool forward_only = false) {
   (void)num_bags;
   const int64_t max_rows = nnz < sh.num_rows ? nnz : sh.num_rows;
   const int64_t pref_cap = (int64_t)sh.n1 * sh.n2;
@@ -83,19 +84,20 @@ size_t layout(const TTShape &sh, int64_t nnz, int64_t num_bags, char *base, tt_p
   q.pref_meta = ints(4 * max_pref + 4);
   q.counts = ints(16);
   q.rowbuf = floats((size_t)max_rows * sh.D);
-  q.gagg = floats((size_t)max_rows * sh.D);
-  q.hbuf = floats((size_t)max_pref * sh.P);
-  const size_t strips = (size_t)ttk_mfma_strips(sh);
-  q.t3buf = floats((size_t)max_rows * sh.S3 * strips);
-  q.t1buf = floats((size_t)max_pref * sh.S1 * strips);
-  size_t part = (size_t)(tt_ceil_div(nnz, TT_SEG_MIN_CHUNK) + 1) * 2 * sh.D;
-  size_t part3 = (size_t)(tt_ceil_div(max_rows, TT_SEG_MIN_CHUNK) + 1) * 2 * sh.S3;
-  size_t part1 = (size_t)(tt_ceil_div(max_pref, TT_SEG_MIN_CHUNK) + 1) * 2 * sh.S1;
-  if (part3 + part1 > part) part = part3 + part1;  // the core-2 and core-0 reductions run side by side
-  q.partial = floats(part);
-  q.g3t = floats(0);
-  const int split = ttk_bwd_split(sh);
-  q.dg2part = floats(split > 1 ? (size_t)split * sh.R1 * sh.n2 * sh.S2 : 0);
+  if (!forward_only) {
+    q.gagg = floats((size_t)max_rows * sh.D);
+    q.hbuf = mfma ? nullptr : floats((size_t)max_pref * sh.P);
+    const size_t strips = (size_t)ttk_mfma_strips(sh);
+    q.t3buf = floats((size_t)max_rows * sh.S3 * strips);
+    q.t1buf = floats((size_t)max_pref * sh.S1 * strips);
+    size_t part = (size_t)(tt_ceil_div(nnz, TT_SEG_MIN_CHUNK) + 1) * 2 * sh.D;
+    size_t part3 = (size_t)(tt_ceil_div(max_rows, TT_SEG_MIN_CHUNK) + 1) * 2 * sh.S3;
+    size_t part1 = (size_t)(tt_ceil_div(max_pref, TT_SEG_MIN_CHUNK) + 1) * 2 * sh.S1;
+    if (part3 + part1 > part) part = part3 + part1;  // the core-2 and core-0 reductions run side by side
+    q.partial = floats(part);
+    const int split = ttk_bwd_split(sh);
+    q.dg2part = floats(split > 1 ? (size_t)split * sh.R1 * sh.n2 * sh.S2 : 0);
+  }
   q.sort_tmp = take(tt_sort_tmp_bytes(nnz, max_rows, max_pref));
   if (p) *p = q;
   return off;
@@ -156,8 +158,9 @@ tt_status prepare_item(BatchOp op, const tt_batch_item *it, float lr, TTDev *d) 
     if (!it->plan || !it->workspace || !it->offsets || (nnz > 0 && !it->indices))
       return TT_ERR_INVALID_ARG;
     if (((uintptr_t)it->workspace & 255) != 0) return TT_ERR_WORKSPACE;
-    if (it->workspace_bytes < layout(sh, nnz, num_bags, nullptr, nullptr)) return TT_ERR_WORKSPACE;
-    layout(sh, nnz, num_bags, (char *)it->workspace, it->plan);
+    const bool mfma = ttk_mfma_selected(sh, it->table->core[1], it->table->core[2]);
+    if (it->workspace_bytes < layout(sh, mfma, nnz, num_bags, nullptr, nullptr)) return TT_ERR_WORKSPACE;
+    layout(sh, mfma, nnz, num_bags, (char *)it->workspace, it->plan);
     for (int k = 0; k < 3; ++k) { it->plan->n[k] = it->table->n[k]; it->plan->d[k] = it->table->d[k]; }
     for (int k = 0; k < 4; ++k) it->plan->r[k] = it->table->r[k];
     it->plan->workspace = it->workspace;
@@ -165,6 +168,12 @@ tt_status prepare_item(BatchOp op, const tt_batch_item *it, float lr, TTDev *d) 
   } else {
     if (!cores_present(it->table)) return TT_ERR_INVALID_ARG;
     if (it->plan && !plan_matches(it->plan, it->table, nnz, num_bags)) return TT_ERR_INVALID_ARG;
+    // a workspace laid out for the matrix-core kernels has no per-prefix partial buffer: the plain-ALU
+    // backward (cores that are not 16-byte aligned) cannot run on it
+    if (it->plan && !it->plan->gagg && (op == OP_BACKWARD || op == OP_BACKWARD_SGD)) return TT_ERR_WORKSPACE;
+    if (it->plan && !it->plan->hbuf && (op == OP_BACKWARD || op == OP_BACKWARD_SGD) &&
+        !ttk_mfma_selected(sh, it->table->core[1], it->table->core[2]))
+      return TT_ERR_WORKSPACE;
     if (op == OP_FORWARD) {
       if (!it->offsets || (num_bags > 0 && !it->out)) return TT_ERR_INVALID_ARG;
       if (!it->plan && nnz > 0 && !it->indices) return TT_ERR_INVALID_ARG;
@@ -265,7 +274,7 @@ extern "C" {
 size_t tt_workspace_bytes(const tt_table *table, int64_t nnz, int64_t num_bags) {
   TTShape sh;
   if (!derive_shape(table, &sh) || !batch_ok(nnz, num_bags)) return 0;
-  return layout(sh, nnz, num_bags, nullptr, nullptr);
+  return layout(sh, ttk_mfma_selected(sh, table->core[1], table->core[2]), nnz, num_bags, nullptr, nullptr);
 }
 
 tt_status tt_index_reorder(const tt_table *table, const int64_t *indices, const int64_t *offsets,

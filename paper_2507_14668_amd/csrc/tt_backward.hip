@@ -326,7 +326,9 @@ static SegParams seg_params(const TTBatch &b, int kind, int chunk) {
   for (int t = 0; t < b.T; ++t) {
     const TTDev &d = b.host[t];
     const float *src = kind == SEG_GAGG ? d.grad_out : (kind == SEG_DG3 ? d.plan.t3buf : d.plan.t1buf);
-    const float *out = kind == SEG_GAGG ? d.plan.gagg : (kind == SEG_DG3 ? d.dg[2] : d.dg[0]);
+    // the buffer the final stores go to: with the fused update, the core itself
+    const float *out = kind == SEG_GAGG ? d.plan.gagg
+                                        : (kind == SEG_DG3 ? (d.fused ? d.g[2] : d.dg[2]) : (d.fused ? d.g[0] : d.dg[0]));
     vec4 = vec4 && ((uintptr_t)src % 16) == 0 && ((uintptr_t)out % 16) == 0;
     const long long cnt = kind == SEG_GAGG ? d.nnz : (kind == SEG_DG3 ? d.plan.max_rows : d.plan.max_prefixes);
     const long long nseg = (kind == SEG_GAGG || d.fused) ? 0 : (kind == SEG_DG3 ? d.sh.n3 : d.sh.n1);

@@ -26,6 +26,8 @@
 //
 // MFMA operand layout (D = A[16x4] * B[4x16] + C): lane l supplies A[m = l%16][k = l/16] and
 // B[k = l/16][n = l%16] and holds C[m = 4*(l/16) + v][n = l%16] in component v.
+#include <mutex>
+
 #include "tt_internal.h"
 
 namespace {
@@ -82,14 +84,6 @@ k_bwd_mfma(TTArg<BATCHED> a) {
   const int fused = d.fused;
   const float lr = d.lr;
   float *dg2 = fused ? const_cast<float *>(d.g[1]) : d.dg[1];
-#ifdef TT_DBG_TIMING
-  float *__restrict__ dbg = d.plan.hbuf;
-  const long long wall0 = wall_clock64();
-  long long tph[8] = {0, 0, 0, 0, 0, 0, 0, 0}, tlast = clock64();
-#define TT_TICK(k) { long long tn = clock64(); tph[k] += tn - tlast; tlast = tn; }
-#else
-#define TT_TICK(k)
-#endif
   using G = BwdGeom<R1, R2, D2>;
   constexpr int GPT = (32 * R1) / NTHR;      // core-0 tile elements per thread
   constexpr int T3_SPLIT = 4 / G::NTH;       // T3 wavefront classes that alternate over the row quads
@@ -302,9 +296,7 @@ k_bwd_mfma(TTArg<BATCHED> a) {
   for (int cs = seg0; cs < seg1; cs += TT_MP) {
     const int cnt = (seg1 - cs) < TT_MP ? (seg1 - cs) : TT_MP;
     const int mo = (cs - seg0) % META;  // this chunk's offset in s_q / s_i1 / s_u0 / s_nr
-    TT_TICK(0)
     __syncthreads();  // this chunk's staging is visible; previous chunk's T1 partials are consumed
-    TT_TICK(1)
 
     const float *As = lds + par * G::A_FLOATS, *AsT = As + G::OFF_AST;
     const bool more = cs + TT_MP < seg1, refill = mo + TT_MP == META;
@@ -346,7 +338,6 @@ k_bwd_mfma(TTArg<BATCHED> a) {
     // load is waited for while the row phase's stores are in flight.
     if (more && !refill) stage_chunk(par ^ 1, mo + TT_MP, cnt_next);
     __syncthreads();
-    TT_TICK(2)
 
     // ---- T3 and H over the distinct rows of the chunk, one quad (<= 4 rows of a prefix) at a time
     // Wavefronts 0-3 own one 16x16 tile of H each and walk every quad; wavefronts 4-7 own an r2 tile
@@ -442,9 +433,7 @@ k_bwd_mfma(TTArg<BATCHED> a) {
              });
       }
     }
-    TT_TICK(3)
     __syncthreads();
-    TT_TICK(4)
     // first row batch of the NEXT chunk: requested now, landed after the next F1, so that the T1 /
     // dG2 / F1 MFMAs in between cover its latency
     if (more && !refill) issue_batch(0, par ^ 1, mo + TT_MP);
@@ -487,7 +476,6 @@ k_bwd_mfma(TTArg<BATCHED> a) {
         for (int nt = 0; nt < 2; ++nt) acc2[mt][nt] = MFMA(a[mt], b[nt], acc2[mt][nt]);
     }
     __syncthreads();
-    TT_TICK(5)
     // fold the four K-partials of T1 in pair order and store one contribution per prefix
     for (int e4 = threadIdx.x; e4 < 32 * R1 / 4; e4 += NTHR) {
       const int e = 4 * e4, row = e / R1, p = row >> 2;
@@ -512,7 +500,6 @@ k_bwd_mfma(TTArg<BATCHED> a) {
       issue_batch(0, par ^ 1, 0);
     }
     par ^= 1;
-    TT_TICK(6)
   }
 
   // dG2[r1 = 16*mt + 4*lq + v][i2][c = 32*wave + 16*nt + lm], complete for this i2 and strip
@@ -525,18 +512,6 @@ k_bwd_mfma(TTArg<BATCHED> a) {
         float *dst = dg2 + (size_t)(16 * mt + 4 * lq + v) * sh.n2 * G::S2 + strip_col + 32 * wave + 16 * nt + lm;
         *dst = (fused && split == 1) ? fmaf(-lr, acc2[mt][nt][v], *dst) : acc2[mt][nt][v];
       }
-#ifdef TT_DBG_TIMING
-  __builtin_amdgcn_s_waitcnt(0);
-  if (lane == 0) {
-    TT_TICK(7)
-    float *o = dbg + (size_t)(blockIdx.x * 8 + wave) * 12;
-    for (int k = 0; k < 8; ++k) o[k] = (float)tph[k];
-    o[8] = (float)(seg1 - seg0);
-    o[9] = (float)(wall0 & 0xFFFFFF);
-    o[10] = (float)(wall_clock64() & 0xFFFFFF);
-    o[11] = 0.f;
-  }
-#endif
 }
 
 // Sums the partial core-1 gradients of a split table in part order and stores the gradient, or
@@ -577,15 +552,16 @@ template <int R1, int R2, int D2>
 tt_status launch(const TTBatch &b, hipStream_t s) {
   using G = BwdGeom<R1, R2, D2>;
   const size_t lds = G::LDS_FLOATS * sizeof(float);
+  // once per process and kernel instantiation; calls may come from several host threads
+  static std::once_flag once;
   static bool configured = false;
-  if (!configured) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_bwd_mfma<false, R1, R2, D2>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess ||
-        hipFuncSetAttribute(reinterpret_cast<const void *>(&k_bwd_mfma<true, R1, R2, D2>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-      return TT_ERR_HIP;
-    configured = true;
-  }
+  std::call_once(once, [&] {
+    configured = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_bwd_mfma<false, R1, R2, D2>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess &&
+                 hipFuncSetAttribute(reinterpret_cast<const void *>(&k_bwd_mfma<true, R1, R2, D2>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess;
+  });
+  if (!configured) return TT_ERR_HIP;
   const long long blocks = tt_batch_max(b, [](const TTDev &d) {
     return (long long)d.sh.n2 * G::NSTRIP * d.bwd_split; });
   TTProfScope prof(&b.host[0].plan, TT_KERNEL_BWD_CONTRACT, s);

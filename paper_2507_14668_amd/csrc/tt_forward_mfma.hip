@@ -14,6 +14,8 @@
 // Operand layout of __builtin_amdgcn_mfma_f32_16x16x4f32 (D = A[16x4] * B[4x16] + C):
 //   lane l supplies A[m = l%16][k = l/16] and B[k = l/16][n = l%16];
 //   lane l holds C[m = 4*(l/16) + v][n = l%16] in component v of its float4.
+#include <mutex>
+
 #include "tt_internal.h"
 
 namespace {
@@ -205,15 +207,16 @@ template <int R1, int R2, int D2>
 tt_status launch(const TTBatch &b, hipStream_t s) {
   using G = FwdGeom<R1, R2, D2>;
   const size_t lds = G::LDS_FLOATS * sizeof(float);
+  // once per process and kernel instantiation; calls may come from several host threads
+  static std::once_flag once;
   static bool configured = false;
-  if (!configured) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fwd_mfma<false, R1, R2, D2>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess ||
-        hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fwd_mfma<true, R1, R2, D2>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-      return TT_ERR_HIP;
-    configured = true;
-  }
+  std::call_once(once, [&] {
+    configured = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fwd_mfma<false, R1, R2, D2>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess &&
+                 hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fwd_mfma<true, R1, R2, D2>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess;
+  });
+  if (!configured) return TT_ERR_HIP;
   // upper bound of the chunk count: every i2 adds at most one partly filled chunk
   long long blocks = tt_batch_max(b, [](const TTDev &d) {
     return (long long)(d.plan.max_prefixes / TT_MP + d.sh.n2) * G::NSTRIP; });

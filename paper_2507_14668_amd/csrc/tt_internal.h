@@ -132,14 +132,10 @@ int ttk_mfma_strips(const TTShape &sh);
 int ttk_bwd_split(const TTShape &sh);
 #define TT_BWD_MAX_SPLIT 8
 tt_status ttk_backward_mfma(const TTBatch &b, hipStream_t s);
-// true unless the environment variable TT_EMB_NO_MFMA is set (keeps the plain-ALU kernels
-// selectable for comparison runs)
-bool tt_mfma_enabled();
-// the matrix-core kernels serve a table when they are enabled, support its shape and cores 1 and 2
-// are 16-byte aligned (they read core-1 rows and core-2 slices as float4)
+// the matrix-core kernels serve a table when they support its shape and cores 1 and 2 are 16-byte
+// aligned (they read core-1 rows and core-2 slices as float4)
 static inline bool ttk_mfma_selected(const TTShape &sh, const float *core1, const float *core2) {
-  return tt_mfma_enabled() && ttk_forward_mfma_supported(sh) && ((uintptr_t)core1 % 16) == 0 &&
-         ((uintptr_t)core2 % 16) == 0;
+  return ttk_forward_mfma_supported(sh) && ((uintptr_t)core1 % 16) == 0 && ((uintptr_t)core2 % 16) == 0;
 }
 // a batch takes the matrix-core kernels only if every table of it does
 static inline bool ttk_batch_mfma(const TTBatch &b) {

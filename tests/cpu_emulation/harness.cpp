@@ -117,6 +117,15 @@ int main(int argc, char **argv) {
       CK(tt_emb_bag_backward(&B.t, planned ? &plan : nullptr, B.idx.data(), B.off.data(), B.nnz, B.bags, B.grad.data(), dc, nullptr));
       CK(tt_core_sgd_update(&B.t, planned ? &plan : nullptr, dc, lr, nullptr));
       for (int k = 0; k < 3; ++k) R.core[k] = B.core[k];
+      if (planned) {  // fused backward + update on fresh cores (shifted off their alignment like the others)
+        for (int k = 0; k < 3; ++k) B.core[k] = B.core0[k];
+        CK(tt_emb_bag_backward_sgd(&B.t, &plan, B.idx.data(), B.off.data(), B.nnz, B.bags, B.grad.data(), lr, nullptr));
+        for (int k = 0; k < 3; ++k)
+          if (memcmp(B.core[k].data(), R.core[k].data(), B.core[k].size() * sizeof(float)) != 0) {
+            fprintf(stderr, "FAIL fused update differs from backward + update (table %d core %d)\n", t, k);
+            return 3;
+          }
+      }
       free(ws);
       fprintf(stderr, "single table %d done\n", t);
     }

@@ -52,6 +52,9 @@ void wave_mfma_16x16x4(float a, float b, float *c4);
   emu::launch(grid, block, lds, #kernel, [=]() { kernel(__VA_ARGS__); })
 
 static inline hipError_t hipGetLastError() { return hipSuccess; }
+static inline hipError_t hipGetDevice(int *dev) { *dev = 0; return hipSuccess; }
+#define HIP_SYMBOL(x) (&(x))
+static inline hipError_t hipGetSymbolAddress(void **p, const void *symbol) { *p = const_cast<void *>(symbol); return hipSuccess; }
 static inline hipError_t hipFuncSetAttribute(const void *, int, int) { return hipSuccess; }
 static inline hipError_t hipMemcpyAsync(void *d, const void *s, size_t n, int, hipStream_t) { memcpy(d, s, n); return hipSuccess; }
 static inline hipError_t hipStreamSynchronize(hipStream_t) { return hipSuccess; }

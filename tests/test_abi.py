@@ -27,12 +27,48 @@ def test_library_exports_every_declared_symbol():
     assert binding.strerror(0) == "ok" and "workspace" in binding.strerror(binding.TT_ERR_WORKSPACE)
 
 
-def test_struct_mirrors_match_header_sizes():
+def _header_struct_fields(name):
+    """(field, array length or 0) of every member of `typedef struct { ... } name;` in the header."""
+    text = open(os.path.join(ROOT, "include", "tt_emb.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    body = re.search(r"typedef struct \{([^}]*)\} %s;" % name, text).group(1)
+    fields = []
+    for decl in body.split(";"):
+        decl = decl.strip()
+        if not decl:
+            continue
+        for part in decl.split(","):
+            m = re.search(r"(\w+)\s*(?:\[(\d+)\])?\s*$", part.strip())
+            fields.append((m.group(1), int(m.group(2) or 0)))
+    return fields
+
+
+def test_struct_mirrors_match_header_layout(tmp_path):
+    """The ctypes mirrors of the public structs are pinned to the header: a C program that includes
+    include/tt_emb.h prints sizeof and offsetof of every member (names parsed from the header), and
+    the ctypes classes must have the same members at the same offsets."""
+    import subprocess
     from paper_2507_14668_amd import binding
-    # tt_table: int64 + 3*int32 + 3*int32 + 4*int32 + 3 pointers = 8 + 40 + 24 = 72 bytes
-    assert ctypes.sizeof(binding.CTable) == 72
-    # tt_plan: 4*int64 + 10*int32 (+pad) + 18 + 7 + 3 pointers + size_t
-    assert ctypes.sizeof(binding.CPlan) == 32 + 40 + 8 * (20 + 8 + 3) + 8
+    pairs = (("tt_table", binding.CTable), ("tt_plan", binding.CPlan), ("tt_batch_item", binding.CBatchItem))
+    lines = ["#include <stdio.h>", "#include <stddef.h>", '#include "tt_emb.h"', "int main(void) {"]
+    for cname, _ in pairs:
+        lines.append('printf("%s sizeof %%zu\\n", sizeof(%s));' % (cname, cname))
+        for field, _n in _header_struct_fields(cname):
+            lines.append('printf("%s %s %%zu\\n", offsetof(%s, %s));' % (cname, field, cname, field))
+    lines.append("return 0; }")
+    src, exe = tmp_path / "layout.c", tmp_path / "layout"
+    src.write_text("\n".join(lines))
+    subprocess.run(["gcc", "-std=c99", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)], check=True)
+    got = {}
+    for ln in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.splitlines():
+        cname, field, off = ln.split()
+        got[(cname, field)] = int(off)
+    for cname, cls in pairs:
+        assert ctypes.sizeof(cls) == got[(cname, "sizeof")], cname
+        header_fields = [f for f, _ in _header_struct_fields(cname)]
+        assert [f for f, _ in cls._fields_] == header_fields, cname
+        for field in header_fields:
+            assert getattr(cls, field).offset == got[(cname, field)], (cname, field)
 
 
 def test_workspace_query_and_host_validation_without_gpu():
