@@ -69,43 +69,46 @@ def test_config3_4_reduced_batch_definition_mode(g, ora, permute):
         g.assert_grads_close(shape, dg, ref_dg, what="cfg4 dG naive=%s" % naive)
 
 
-@pytest.mark.parametrize("tab", [0, 7])
-def test_config3_4_full_size(g, ora, tab):
+def full_table_check(g, ora, cfg, tab, what, permute=None, naive=False):
+    """One table at its full batch size, in bench.py's launch configuration: plan bit for bit against
+    the integer oracle; complete outputs, gradients, updated cores and the fused update against the
+    oracle's dedup mode (itself pinned to definition mode in the CPU suite); Euler's identity."""
     import paper_2507_14668_amd as tt
-    print("case cfg3/4 full table %d" % tab, flush=True)
-    cfg = wl.get_config(4)
     shape, cores = cfg.tables[tab], wl.make_cores(cfg, tab)
-    idx, off = wl.make_batch(cfg, tab)
+    idx, off = wl.make_batch(cfg, tab, permute_rows=permute)
     grad = wl.make_grad(cfg, tab)
     table = g.gpu_table(shape, cores)
     plan, out, dg = gpu_step(g, table, idx, off, grad)
-    print("  nnz=%d counts=%s" % (len(idx), plan.counts()[0]), flush=True)
+    print("case %s table %d rows=%d n=%s nnz=%d counts=%s" % (what, tab, shape.num_rows, shape.n, len(idx), plan.counts()[0]),
+          flush=True)
+    g.assert_plan_equals_oracle(ora, shape, plan, idx, off)
     ref_out = ora.forward(shape, cores, idx, off, dedup=True)
-    g.assert_close_rows(out.cpu().numpy(), ref_out, g.FWD_RTOL, shape.dim, "cfg3 forward")
-    ref_dg = ora.backward(shape, cores, idx, off, grad, dedup=True)
-    g.assert_grads_close(shape, dg, ref_dg, what="cfg4 dG")
+    g.assert_close_rows(out.cpu().numpy(), ref_out, g.FWD_RTOL, shape.dim, "forward")
+    ref_dg = ora.backward(shape, cores, idx, off, grad, dedup=True, max_threads_=8)
+    g.assert_grads_close(shape, dg, ref_dg, what="dG")
     euler_check(shape, cores, out, dg, grad)
-    # naive arms at full size: forward against the oracle, backward (atomics) against the oracle
-    _, out_n, dg_n = gpu_step(g, table, idx, off, grad, naive=True)
-    g.assert_close_rows(out_n.cpu().numpy(), ref_out, g.FWD_RTOL, shape.dim, "cfg3 forward naive")
-    g.assert_grads_close(shape, dg_n, ref_dg, what="cfg4 dG naive")
-    # update with lr = 0.01
+    if naive:  # naive arms at full size: forward against the oracle, backward (atomics) against the oracle
+        _, out_n, dg_n = gpu_step(g, table, idx, off, grad, naive=True)
+        g.assert_close_rows(out_n.cpu().numpy(), ref_out, g.FWD_RTOL, shape.dim, "forward naive")
+        g.assert_grads_close(shape, dg_n, ref_dg, what="dG naive")
     ref_new = ora.sgd(cores, ref_dg, cfg.lr)
     tt.tt_core_sgd_update(table, plan, dg, cfg.lr)
     torch.cuda.synchronize()
-    g.assert_grads_close(shape, table.cores, ref_new, what="cfg4 updated G")
-    fused_update_check(g, shape, cores, plan, idx, off, grad, cfg.lr, table, ref_new, "cfg4")
+    g.assert_grads_close(shape, table.cores, ref_new, what="updated G")
+    fused_update_check(g, shape, cores, plan, idx, off, grad, cfg.lr, table, ref_new, what)
+    g.report_worst("%s table %d " % (what, tab))
 
 
-def test_config3_4_other_tables_euler_identity(g):
-    cfg = wl.get_config(4)
-    for tab in (1, 2, 3, 4, 5, 6):
-        print("case cfg3/4 euler table %d" % tab, flush=True)
-        shape, cores = cfg.tables[tab], wl.make_cores(cfg, tab)
-        idx, off = wl.make_batch(cfg, tab)
-        grad = wl.make_grad(cfg, tab)
-        _, out, dg = gpu_step(g, g.gpu_table(shape, cores), idx, off, grad)
-        euler_check(shape, cores, out, dg, grad)
+@pytest.mark.parametrize("tab", range(8))
+def test_config3_4_full_size(g, ora, tab):
+    """All 8 tables of configs 3/4 (config 3 = the forward part, config 4 = backward + update); the
+    naive arms (no plan; per-lookup chain, float atomics) on the first and the last table."""
+    full_table_check(g, ora, wl.get_config(4), tab, "cfg3/4", naive=tab in (0, 7))
+
+
+def test_config3_4_full_size_permuted_rows(g, ora):
+    """The permuted-row variant (Zipf rank -> random row: three times as many distinct prefixes)."""
+    full_table_check(g, ora, wl.get_config(4), 1, "cfg3/4 permuted", permute=True)
 
 
 def cfg5_tables():
@@ -115,27 +118,16 @@ def cfg5_tables():
     return cfg, [int(order[0]), int(order[len(order) // 2]), int(order[-1])]
 
 
-def test_config5_full_size_small_mid_large_tables(g, ora):
-    import paper_2507_14668_amd as tt
+@pytest.mark.parametrize("tab", range(26))
+def test_config5_full_size(g, ora, tab):
+    """Every one of the 26 tables bench.py times (row counts 1e3 .. 4e7: every backward split factor
+    the benchmark uses, one and two rounds of workgroups, both radix-sort launch structures)."""
+    full_table_check(g, ora, wl.get_config(5), tab, "cfg5")
+
+
+def test_config5_full_size_permuted_rows_largest_table(g, ora):
     cfg, tabs = cfg5_tables()
-    for tab in tabs:
-        shape, cores = cfg.tables[tab], wl.make_cores(cfg, tab)
-        print("case cfg5 table %d rows=%d n=%s" % (tab, shape.num_rows, shape.n), flush=True)
-        idx, off = wl.make_batch(cfg, tab)
-        grad = wl.make_grad(cfg, tab)
-        table = g.gpu_table(shape, cores)
-        plan, out, dg = gpu_step(g, table, idx, off, grad)
-        print("  counts=%s" % (plan.counts()[0],), flush=True)
-        ref_out = ora.forward(shape, cores, idx, off, dedup=True)
-        g.assert_close_rows(out.cpu().numpy(), ref_out, g.FWD_RTOL, shape.dim, "cfg5 forward")
-        ref_dg = ora.backward(shape, cores, idx, off, grad, dedup=True, max_threads_=8)
-        g.assert_grads_close(shape, dg, ref_dg, what="cfg5 dG")
-        euler_check(shape, cores, out, dg, grad)
-        ref_new = ora.sgd(cores, ref_dg, cfg.lr)
-        tt.tt_core_sgd_update(table, plan, dg, cfg.lr)
-        torch.cuda.synchronize()
-        g.assert_grads_close(shape, table.cores, ref_new, what="cfg5 updated G")
-        fused_update_check(g, shape, cores, plan, idx, off, grad, cfg.lr, table, ref_new, "cfg5")
+    full_table_check(g, ora, cfg, tabs[-1], "cfg5 permuted", permute=True)
 
 
 def test_config5_definition_mode_sample_of_bags(g, ora):

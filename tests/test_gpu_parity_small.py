@@ -23,24 +23,7 @@ def run_all(g, ora, shape, cores, idx, off, grad, lr=0.01, check_plan=True, rema
     o_idx = idx if remap is None else np.where((idx >= 0) & (idx < shape.num_rows), remap[np.clip(idx, 0, shape.num_rows - 1)], -1)
     plan = tt.tt_index_reorder(table, d_idx, d_off, remap=d_remap)
     if check_plan:
-        ref = ora.reorder_plan(shape, idx, off, remap=remap)
-        got = plan.arrays()
-        nv = ref["num_valid"]
-        assert got["num_valid"] == nv and got["U_r"] == len(ref["uniq_row"]) and got["U_p"] == len(ref["uniq_pref"])
-        for key in ("perm", "sorted_row", "bag_of_sorted"):
-            assert np.array_equal(got[key][:nv], ref[key]), key
-        for key in ("uniq_row", "row_seg", "lookup2row", "uniq_pref", "pref_seg", "row2pref"):
-            assert np.array_equal(got[key], ref[key]), key
-        # groupings: stable by i3 / i2, ranges consistent
-        i3 = ref["uniq_row"] % shape.n[2]
-        assert np.array_equal(got["rows_by_i3"], np.argsort(i3, kind="stable"))
-        assert np.array_equal(got["i3_of_sorted"], np.sort(i3))
-        assert np.array_equal(got["i3_seg"], np.searchsorted(np.sort(i3), np.arange(shape.n[2] + 1)))
-        i2 = ref["uniq_pref"] % shape.n[1]
-        assert np.array_equal(got["prefs_by_i2"], np.argsort(i2, kind="stable"))
-        assert np.array_equal(got["i2_seg"], np.searchsorted(np.sort(i2), np.arange(shape.n[1] + 1)))
-        i1 = ref["uniq_pref"] // shape.n[1]
-        assert np.array_equal(got["i1_seg"], np.searchsorted(i1, np.arange(shape.n[0] + 1)))
+        g.assert_plan_equals_oracle(ora, shape, plan, idx, off, remap=remap)
     ref_out = ora.forward(shape, cores, np.where(o_idx < 0, shape.num_rows, o_idx) if remap is not None else idx, off)
     out_plan = tt.tt_emb_bag_forward(table, plan, d_idx, d_off)
     g.assert_close_rows(out_plan.cpu().numpy(), ref_out, g.FWD_RTOL, shape.dim, "forward(plan)")
@@ -102,6 +85,66 @@ def test_matrix_core_shapes(g, ora, seed, n, r, nb, ml):
     shape, cores, idx, off, grad = wl.small_random_problem(seed, n=n, d=(4, 8, 4), r=r, num_bags=nb,
                                                           max_len=ml, sigma=0.2)
     run_all(g, ora, shape, cores, idx, off, grad)
+
+
+@pytest.mark.parametrize("rank,n2,split", [
+    (64, 43, 2), (64, 42, 3), (64, 32, 4), (64, 25, 5), (64, 21, 6), (64, 18, 7), (64, 16, 8),
+    (32, 100, 2), (32, 80, 3), (32, 64, 4), (32, 50, 5), (32, 42, 6), (32, 36, 7), (32, 32, 8),
+])
+def test_every_backward_split_factor(g, ora, rank, n2, split):
+    """Tables with few core-1 slices deal the 8-prefix chunks of one (i2, strip) to 2..8 workgroups
+    whose partial core-1 gradients a second kernel adds up: one case per factor and rank, with
+    enough prefixes per i2 (up to 40) that parts get several chunks, one chunk, or none."""
+    strips = 2 if rank == 64 else 1
+    assert min(8, 256 // (n2 * strips)) == split and n2 * strips < 128
+    print("case bwd split rank=%d n2=%d split=%d" % (rank, n2, split), flush=True)
+    shape, cores, idx, off, grad = wl.small_random_problem(900 + rank + n2, n=(40, n2, 4), d=(4, 8, 4),
+                                                          r=(1, rank, rank, 1), num_bags=2500, max_len=3, sigma=0.2)
+    import paper_2507_14668_amd as tt
+    table = g.gpu_table(shape, cores)
+    d_idx, d_off, d_grad = g.to_dev(idx, torch.int64), g.to_dev(off, torch.int64), g.to_dev(grad, torch.float32)
+    plan = tt.tt_index_reorder(table, d_idx, d_off)
+    g.assert_plan_equals_oracle(ora, shape, plan, idx, off)
+    out = tt.tt_emb_bag_forward(table, plan, d_idx, d_off)
+    g.assert_close_rows(out.cpu().numpy(), ora.forward(shape, cores, idx, off, dedup=True), g.FWD_RTOL, shape.dim, "forward")
+    dg = tt.tt_emb_bag_backward(table, plan, d_idx, d_off, d_grad)
+    ref_dg = ora.backward(shape, cores, idx, off, grad, dedup=True)
+    g.assert_grads_close(shape, dg, ref_dg, what="dG")
+    tt.tt_core_sgd_update(table, plan, dg, 0.01)
+    fused = g.gpu_table(shape, cores)
+    tt.tt_emb_bag_backward_sgd(fused, plan, d_idx, d_off, d_grad, 0.01)
+    torch.cuda.synchronize()
+    g.assert_grads_close(shape, fused.cores, ora.sgd(cores, ref_dg, 0.01), what="fused updated G")
+    for k in range(3):
+        assert torch.equal(fused.cores[k], table.cores[k]), "fused update differs from backward + update (core %d)" % k
+    g.report_worst("split %d rank %d " % (split, rank))
+
+
+def test_more_than_a_million_lookups(g, ora):
+    """1.2 M lookups: the radix sort runs with more than 64 tiles (separate bin-scan launch) and the
+    distinct-row pass with more than 1024 tiles (separate tile-sum scan launch).  Plan bit for bit,
+    outputs and gradients against the dedup-mode oracle."""
+    import paper_2507_14668_amd as tt
+    print("case 1.2M lookups", flush=True)
+    cfg = wl.get_config(1)
+    shape, cores = cfg.tables[0], wl.make_cores(cfg, 0)
+    rng = np.random.default_rng(77)
+    nb = 300_000
+    lens = rng.integers(0, 9, size=nb)
+    off = np.zeros(nb + 1, dtype=np.int64)
+    np.cumsum(lens, out=off[1:])
+    idx = rng.integers(0, shape.num_rows, size=int(off[-1]), dtype=np.int64)
+    assert len(idx) > 1024 * 1024
+    grad = rng.standard_normal(nb * shape.dim).astype(np.float32)
+    table = g.gpu_table(shape, cores)
+    d_idx, d_off = g.to_dev(idx, torch.int64), g.to_dev(off, torch.int64)
+    plan = tt.tt_index_reorder(table, d_idx, d_off)
+    g.assert_plan_equals_oracle(ora, shape, plan, idx, off)
+    out = tt.tt_emb_bag_forward(table, plan, d_idx, d_off)
+    g.assert_close_rows(out.cpu().numpy(), ora.forward(shape, cores, idx, off, dedup=True), g.FWD_RTOL, shape.dim, "forward")
+    dg = tt.tt_emb_bag_backward(table, plan, d_idx, d_off, g.to_dev(grad, torch.float32))
+    g.assert_grads_close(shape, dg, ora.backward(shape, cores, idx, off, grad, dedup=True), what="dG")
+    g.report_worst("1.2M ")
 
 
 def test_padded_table_and_remap(g, ora):
@@ -211,6 +254,19 @@ def test_unaligned_core_and_gradient_buffers_take_the_scalar_paths(g, ora):
     tt.tt_emb_bag_backward(table, plan, d_idx, d_off, d_g, dcores=dviews)
     ref_dg = ora.backward(shape, cores, idx, off, grad)
     g.assert_grads_close(shape, dviews, ref_dg, what="unaligned dG")
+    # the fused backward + update writes into the (unaligned) cores themselves
+    tt.tt_core_sgd_update(table, plan, dviews, 0.01)
+    fviews = []
+    for c in cores:
+        buf = torch.empty(len(c) + 1, dtype=torch.float32, device="cuda")
+        buf[1:].copy_(torch.from_numpy(np.asarray(c, dtype=np.float32)))
+        fviews.append(buf[1:])
+    ftable = tt.Table(shape.num_rows, shape.n, shape.d, shape.r, fviews)
+    tt.tt_emb_bag_backward_sgd(ftable, plan, d_idx, d_off, d_g, 0.01)
+    torch.cuda.synchronize()
+    for k in range(3):
+        assert torch.equal(fviews[k], views[k]), "unaligned fused update differs from backward + update (core %d)" % k
+    g.assert_grads_close(shape, fviews, ora.sgd(cores, ref_dg, 0.01), what="unaligned fused updated G")
     # aligned cores (matrix-core kernels, split workgroups) with an unaligned core-1 gradient buffer
     table2 = g.gpu_table(shape, cores)
     plan2 = tt.tt_index_reorder(table2, d_idx, d_off)
