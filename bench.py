@@ -46,6 +46,9 @@ def parse_args():
                     help="backward writes the core gradients and a separate call applies them "
                          "(default: the fused backward+update call)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-configs", dest="other_configs", action="store_false",
+                    help="with the default workload, skip the shorter runs of configs 3 and 4 (plan and naive "
+                         "arms) that are reported as `other_configs` in the same line")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain device copy of known size (256 MiB read + 256 MiB written, five "
                          "times): the reference that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -55,38 +58,24 @@ def parse_args():
     return ap.parse_args()
 
 
-def main():
-    args = parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
-              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
-        sys.exit(2)
+def measure(args, workload, arm, steps, warmup, batches, prof_kernels, streams):
+    """One workload and arm: `warmup` + `steps` steps on `streams` stream pairs -> throughput; then, for
+    every kernel in `prof_kernels` (planned arm), the same steps on ONE stream pair with that kernel
+    bracketed by HIP events -> its roofline entry.  Returns the result dict of the JSON line (the first
+    entry of prof_kernels is `roofline`, all of them are in `kernel_rooflines`)."""
     import numpy as np
     import torch
 
     import paper_2507_14668_amd as tt
     import tt_workloads as wl
-    from paper_2507_14668_amd import binding
+    from paper_2507_14668_amd import binding  # noqa: F401
 
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    if args.copy_calibration:
-        n = 64 * 1024 * 1024
-        src = torch.arange(n, dtype=torch.float32, device="cuda")
-        dst = torch.empty_like(src)
-        torch.cuda.synchronize()
-        for _ in range(5):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        print(json.dumps({"copy_calibration": True, "launches": 5, "bytes_read_per_launch": 4 * n,
-                          "bytes_written_per_launch": 4 * n}))
-        return
-    tt.load_library()
-    cfg_id = int(args.workload[3:])
+    cfg_id = int(workload[3:])
     cfg = wl.get_config(cfg_id)
     do_fwd = True
     do_bwd = cfg_id != 3
     ntab = len(cfg.tables) if args.tables <= 0 else min(args.tables, len(cfg.tables))
-    nbatch = max(2, args.batches + (args.batches % 2))  # even, so batch b always uses plan buffer b%2
+    nbatch = max(2, batches + (batches % 2))  # even, so batch b always uses plan buffer b%2
 
     # ---- inputs, resident in HBM ------------------------------------------------------------
     t_gen = time.time()
@@ -112,7 +101,7 @@ def main():
                                 # workload statistics used only to count algorithmic work
                                 u_r=int(np.unique(seen).size), u_p=int(np.unique(seen // shape.n[2]).size)))
         max_nnz = max(x["nnz"] for x in batches)
-        ws = [tt.alloc_workspace(table, max_nnz, cfg.batch) for _ in range(2)] if args.arm == "plan" else None
+        ws = [tt.alloc_workspace(table, max_nnz, cfg.batch) for _ in range(2)] if arm == "plan" else None
         tabs.append(dict(shape=shape, table=table, batches=batches, ws=ws, plans=[None, None],
                          remap=None if remap is None else torch.from_numpy(remap).cuda(),
                          out=torch.empty((cfg.batch, shape.dim), dtype=torch.float32, device="cuda"),
@@ -120,12 +109,12 @@ def main():
     torch.cuda.synchronize()
     t_gen = time.time() - t_gen
 
-    prof_name = args.prof_kernel
-    if prof_name == "auto":
-        prof_name = "bwd_contract" if do_bwd else "fwd_contract"
-    prof = tt.Prof(prof_name, (args.steps + 1) * ntab * 4) if args.arm == "plan" else None
-
-    planned = args.arm == "plan"
+    planned = arm == "plan"
+    prof_kernels = [("bwd_contract" if do_bwd else "fwd_contract") if k == "auto" else k for k in prof_kernels]
+    if not planned:
+        prof_kernels = []
+    profs = {k: tt.Prof(k, (steps + 1) * ntab * 4) for k in prof_kernels}
+    cur = {"name": prof_kernels[0] if prof_kernels else None}  # the kernel the next bracketed region selects
 
     def run_region(ns, warmup, steps, bracket, use_graph=False):
         """`warmup` untimed and `steps` timed steps with `ns` stream pairs: table t computes on
@@ -153,7 +142,7 @@ def main():
                     T["plans"][buf] = tt.tt_index_reorder(T["table"], x["idx"], x["off"], remap=T["remap"],
                                                           workspace=T["ws"][buf], stream=rs[k])
                     if timing[0]:
-                        prof.attach(T["plans"][buf])
+                        profs[cur["name"]].attach(T["plans"][buf])
                 if events:
                     ready[k][buf].record(rs[k])
 
@@ -198,7 +187,7 @@ def main():
                     T["plans"][nxt] = tt.tt_index_reorder(T["table"], x["idx"], x["off"], remap=T["remap"],
                                                           workspace=T["ws"][nxt], stream=rs[k])
                     if timing[0]:
-                        prof.attach(T["plans"][nxt])
+                        profs[cur["name"]].attach(T["plans"][nxt])
                 ready[k][nxt].record(rs[k])
                 cs[k].wait_event(ready[k][buf])
             for T in groups[k]:
@@ -261,10 +250,11 @@ def main():
             b += 1
         torch.cuda.synchronize()
         lookups = 0
+        prof_name = cur["name"]
         if planned and bracket:
             timing[0] = True
             for T in tabs:
-                prof.attach(T["plans"][b % 2])
+                profs[prof_name].attach(T["plans"][b % 2])
         t0 = time.perf_counter()
         for _ in range(steps):
             step(b)
@@ -275,7 +265,7 @@ def main():
         dt = time.perf_counter() - t0
         res = dict(dt=dt, t_enqueue=t_enqueue, lookups=lookups, last_b=b, roofline=None)
         if planned and bracket:
-            kernel_ms, launches = prof.collect()
+            kernel_ms, launches = profs[prof_name].collect()
             for T in tabs:  # later regions must not record into the same event pool
                 for pl in T["plans"]:
                     if pl is not None:
@@ -289,7 +279,7 @@ def main():
             if launches > 0 and kernel_ms > 0:
                 achieved = work / (kernel_ms * 1e-3) / scale
                 res["roofline"] = {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
-                                   "frac": achieved / peak, "traffic": read_traffic(args.workload, prof_name),
+                                   "frac": achieved / peak, "traffic": read_traffic(workload, prof_name),
                                    "kernel": prof_name, "launches": int(launches),
                                    "avg_launch_us": 1e3 * kernel_ms / launches,
                                    "algorithmic_work_per_launch": work / launches,
@@ -301,15 +291,21 @@ def main():
     # contention, so the roofline of the dominant kernel is then taken from a second timed pass of
     # the same K steps on ONE pair, where the bracketed kernel has the chip to itself (this is also
     # the condition under which a rocprofv3 kernel trace, which serialises dispatches, sees it).
-    ns = max(1, min(args.streams, ntab))
-    solo_main = ns == 1 and not args.graph
-    main_region = run_region(ns, args.warmup, args.steps, bracket=solo_main, use_graph=args.graph)
-    solo_region = main_region if solo_main else (run_region(1, 1, args.steps, bracket=True) if planned else None)
+    ns = max(1, min(streams, ntab))
+    solo_main = ns == 1 and not args.graph and len(prof_kernels) == 1
+    main_region = run_region(ns, warmup, steps, bracket=solo_main and bool(prof_kernels), use_graph=args.graph)
     dt, t_enqueue, lookups, b = main_region["dt"], main_region["t_enqueue"], main_region["lookups"], main_region["last_b"]
-    roofline = solo_region["roofline"] if solo_region else None
-    if roofline is not None and not solo_main:
-        roofline["measured_in"] = "second timed pass of the same %d steps on 1 stream pair (%.3f ms/step)" % (
-            args.steps, 1e3 * solo_region["dt"] / args.steps)
+    kernel_rooflines = {}
+    solo_region = None
+    for name in prof_kernels:
+        cur["name"] = name
+        solo_region = main_region if solo_main else run_region(1, 1, steps, bracket=True)
+        r = solo_region["roofline"]
+        if r is not None and not solo_main:
+            r["measured_in"] = "second timed pass of the same %d steps on 1 stream pair (%.3f ms/step)" % (
+                steps, 1e3 * solo_region["dt"] / steps)
+        kernel_rooflines[name] = r
+    roofline = kernel_rooflines[prof_kernels[0]] if prof_kernels else None
 
     status_bad = 0
     counts = []
@@ -326,28 +322,29 @@ def main():
         phases += " (update fused into bwd)"
     result = {
         "metric": "TT embedding lookups/sec fwd+bwd (1 GPU)", "value": value, "unit": "lookups/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": 1e3 * dt / args.steps, "higher_is_better": True, "scaling": "weak",
+        "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": 1e3 * dt / steps, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s: %d TT tables, D=%d, ranks (1,%d,%d,1), batch %d %s bags per table, "
                                "Zipf(alpha=%g)%s, %s, %s arm" %
-                               (args.workload, ntab, cfg.tables[0].dim, cfg.tables[0].r[1], cfg.tables[0].r[2],
+                               (workload, ntab, cfg.tables[0].dim, cfg.tables[0].r[1], cfg.tables[0].r[2],
                                 cfg.batch, "multi-hot" if cfg.multi_hot else "one-hot", cfg.alpha,
                                 (" + row permutation" if (args.permute or cfg.permute_rows) else "") +
                                 (" + offline index bijection" if args.bijection else ""),
-                                phases, args.arm),
-                   "lookups_per_step": lookups // max(1, args.steps), "tables": ntab,
+                                phases, arm),
+                   "lookups_per_step": lookups // max(1, steps), "tables": ntab,
                    "overlap_second_stream": (not args.no_overlap) and planned, "stream_pairs": ns,
                    "hip_graph_replay": bool(args.graph), "host_enqueue_threads": args.host_threads,
-                   "host_enqueue_ms_per_step": round(1e3 * t_enqueue / args.steps, 3),
+                   "host_enqueue_ms_per_step": round(1e3 * t_enqueue / steps, 3),
                    "input_generation_s": round(t_gen, 1)},
         "roofline": roofline,
         "cpu_baseline": None,
+        "kernel_rooflines": {k: v for k, v in kernel_rooflines.items() if v is not None},
     }
     if planned:  # whole-step roofline: algorithmic work of one step against the published peaks
         flops = bytes_ = 0.0
-        first = main_region["last_b"] - args.steps
-        for k in range(args.steps):
+        first = main_region["last_b"] - steps
+        for k in range(steps):
             for T in tabs:
                 x = T["batches"][(first + k) % nbatch]
                 flops += kernel_work("fwd_contract", T["shape"], x, cfg.batch) + x["nnz"] * T["shape"].dim
@@ -355,13 +352,71 @@ def main():
                 if do_bwd:
                     flops += kernel_work("bwd_contract", T["shape"], x, cfg.batch) + x["nnz"] * T["shape"].dim
                     bytes_ += 4.0 * cfg.batch * T["shape"].dim  # output gradients
-        t_flop, t_hbm = flops / args.steps / (PEAK_FP32_TFLOPS * 1e12), bytes_ / args.steps / (PEAK_HBM_GBS * 1e9)
+        t_flop, t_hbm = flops / steps / (PEAK_FP32_TFLOPS * 1e12), bytes_ / steps / (PEAK_HBM_GBS * 1e9)
         result["config"]["step_bound_ms"] = {"fp32_mfma": round(1e3 * t_flop, 4), "hbm": round(1e3 * t_hbm, 4),
-                                             "frac_of_measured": round(max(t_flop, t_hbm) / (dt / args.steps), 4)}
+                                             "frac_of_measured": round(max(t_flop, t_hbm) / (dt / steps), 4)}
     if counts:
         result["config"]["distinct_rows_last_batch"] = int(sum(c[0] for c in counts))
         result["config"]["distinct_prefixes_last_batch"] = int(sum(c[1] for c in counts))
 
+    for T in tabs:  # release the device memory before the next workload is set up
+        T.clear()
+    for pr in profs.values():
+        pr.close()
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    return result
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    import paper_2507_14668_amd as tt
+    import tt_workloads as wl
+    from paper_2507_14668_amd import binding
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.copy_calibration:
+        n = 64 * 1024 * 1024
+        src = torch.arange(n, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": True, "launches": 5, "bytes_read_per_launch": 4 * n,
+                          "bytes_written_per_launch": 4 * n}))
+        return
+    tt.load_library()
+    headline_kernels = [args.prof_kernel] if args.prof_kernel != "auto" else ["auto"]
+    result = measure(args, args.workload, args.arm, args.steps, args.warmup, args.batches, headline_kernels, args.streams)
+    if args.other_configs and args.workload == "cfg5" and args.arm == "plan":
+        # the other configurations the target names, in the same line: fewer steps and batches (the
+        # naive arms take tens to hundreds of milliseconds per step)
+        other = {}
+        for wk, arm_, st_, kern in (("cfg3", "plan", 10, ["fwd_contract", "bag_sum"]), ("cfg3", "naive", 3, []),
+                                    ("cfg4", "plan", 10, ["bwd_contract", "grad_merge", "fwd_contract", "bag_sum"]),
+                                    ("cfg4", "naive", 2, [])):
+            r = measure(args, wk, arm_, st_, 2 if arm_ == "plan" else 1, 2, kern, args.streams)
+            entry = {"ms_per_step": r["ms_per_step"], "lookups_per_s": r["value"], "steps": st_,
+                     "workload": r["config"]["workload"]}
+            if "step_bound_ms" in r["config"]:
+                entry["step_bound_ms"] = r["config"]["step_bound_ms"]
+            if r.get("kernel_rooflines"):
+                entry["kernels"] = {k: {x: v[x] for x in ("bound", "achieved", "peak", "unit", "frac", "avg_launch_us")}
+                                    for k, v in r["kernel_rooflines"].items()}
+            other["%s_%s" % (wk, arm_)] = entry
+        result["other_configs"] = other
+    result.pop("kernel_rooflines", None)
+    cfg = __import__("tt_workloads").get_config(int(args.workload[3:]))
+    wl = __import__("tt_workloads")
+    np = __import__("numpy")
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, wl, np)
     print(json.dumps(result))
@@ -391,10 +446,12 @@ def kernel_work(kernel, shape, batch, num_bags):
         # per prefix: P12 recomputed (cheaper than 2 x 4 x P12 bytes of traffic), H x G2^T, G1^T x H;
         # per distinct row: P12^T x g and g x G3^T
         return u_p * 3 * f12 + u_r * 2 * f3
+    # streaming kernels: COMPULSORY bytes (every distinct row / every bag gradient once), not the bytes
+    # gathered: rows and gradients that are read several times come out of the caches
     if kernel == "bag_sum":
-        return 4.0 * nnz * dim + 4.0 * num_bags * dim + 4.0 * nnz + 8.0 * (num_bags + 1)
+        return 4.0 * u_r * dim + 4.0 * num_bags * dim + 4.0 * nnz + 8.0 * (num_bags + 1)
     if kernel == "grad_merge":
-        return 4.0 * nnz * dim + 4.0 * u_r * dim + 8.0 * nnz
+        return 4.0 * num_bags * dim + 4.0 * u_r * dim + 8.0 * nnz
     raise ValueError(kernel)
 
 
