@@ -216,6 +216,25 @@ tt_status tt_emb_bag_backward_sgd(const tt_table *table, const tt_plan *plan, co
                                   const float *grad_out, float lr, void *stream);
 
 /*
+ * Forward for callers that cannot allocate device memory or hand over a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  One call = index reorder +
+ * planned forward (the result is bitwise that of tt_index_reorder followed by tt_emb_bag_forward
+ * with the plan), with the plan's workspace in a static device array of TT_STATIC_SCRATCH_BYTES
+ * that the library's code object holds on every GPU it runs on until the process ends.  The call
+ * allocates and frees nothing.
+ *   indices, offsets, out  DEVICE, as in tt_emb_bag_forward; no remap.
+ * Returns TT_ERR_WORKSPACE when the batch needs more than TT_STATIC_SCRATCH_BYTES (at D = 128
+ * about 50 000 lookups).  All calls on one GPU share that GPU's array: calls that overlap on one
+ * GPU (different streams, or host threads without ordering) race; calls on one stream are safe.
+ * Nothing in the array has to be cleared between calls (the reorder initialises what it reads).
+ * The first call on a device looks the array's address up (hipGetSymbolAddress); make that call
+ * outside a stream capture.  Index errors are skipped silently (there is no plan to query).
+ */
+#define TT_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+tt_status tt_emb_bag_forward_static(const tt_table *table, const int64_t *indices, const int64_t *offsets,
+                                    int64_t nnz, int64_t num_bags, float *out, void *stream);
+
+/*
  * Batched calls: the same four operations for several tables with ONE launch per kernel, so that
  * small tables share the chip with large ones and the host enqueues dozens, not thousands, of
  * launches per step.  All tables of a call must share d[] and r[] (n[] may differ) and must all

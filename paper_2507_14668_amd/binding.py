@@ -24,7 +24,7 @@ TT_ERR_HIP = -5
 TT_ERR_UNAVAILABLE = -6
 
 EXPORTS = ("tt_workspace_bytes", "tt_index_reorder", "tt_emb_bag_forward", "tt_emb_bag_backward",
-           "tt_core_sgd_update", "tt_emb_bag_backward_sgd", "tt_plan_status", "tt_strerror", "tt_prof_create", "tt_prof_destroy",
+           "tt_core_sgd_update", "tt_emb_bag_backward_sgd", "tt_emb_bag_forward_static", "tt_plan_status", "tt_strerror", "tt_prof_create", "tt_prof_destroy",
            "tt_prof_collect", "tt_kernel_name", "tt_batch_desc_bytes", "tt_index_reorder_batched",
            "tt_emb_bag_forward_batched", "tt_emb_bag_backward_batched", "tt_core_sgd_update_batched")
 KERNELS = {"fwd_contract": 0, "bag_sum": 1, "grad_merge": 2, "bwd_contract": 3, "sort_scatter": 4, "sgd": 5}
@@ -90,6 +90,8 @@ def load_library():
         lib.tt_core_sgd_update.argtypes = [vp, vp, vp, f32, vp]
         lib.tt_emb_bag_backward_sgd.restype = ctypes.c_int
         lib.tt_emb_bag_backward_sgd.argtypes = [vp, vp, vp, vp, i64, i64, vp, f32, vp]
+        lib.tt_emb_bag_forward_static.restype = ctypes.c_int
+        lib.tt_emb_bag_forward_static.argtypes = [vp, vp, vp, i64, i64, vp, vp]
         lib.tt_plan_status.restype = ctypes.c_int
         lib.tt_plan_status.argtypes = [vp, vp, vp]
         lib.tt_prof_create.restype = vp
@@ -265,6 +267,19 @@ def tt_emb_bag_forward(table: Table, plan, indices, offsets, out=None, stream=No
     st = load_library().tt_emb_bag_forward(ctypes.byref(table.c), ctypes.byref(plan.c) if plan else None,
                                            _ptr(indices), _ptr(offsets), nnz, nb, _ptr(out), _stream(stream))
     _check(st, "tt_emb_bag_forward")
+    return out
+
+
+def tt_emb_bag_forward_static(table: Table, indices, offsets, out, stream=None):
+    """Reorder + planned forward in the library's static scratch: allocates nothing (`out` is required)."""
+    indices, offsets = _dev_i64(indices, "indices"), _dev_i64(offsets, "offsets")
+    _dev_f32(out, "out")
+    nnz, nb = indices.numel(), offsets.numel() - 1
+    if out.numel() != nb * table.dim:
+        raise ValueError("out must hold num_bags * D floats")
+    st = load_library().tt_emb_bag_forward_static(ctypes.byref(table.c), _ptr(indices), _ptr(offsets), nnz, nb,
+                                                  _ptr(out), _stream(stream))
+    _check(st, "tt_emb_bag_forward_static")
     return out
 
 

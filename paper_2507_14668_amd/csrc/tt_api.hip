@@ -6,7 +6,28 @@
 
 #include "tt_internal.h"
 
+// Scratch of tt_emb_bag_forward_static: one copy per GPU the library runs on, held until the process
+// ends.  In host code the array's name is only a handle for hipGetSymbolAddress; kernels and the
+// layout code get the device address looked up once per device.
+static __device__ __align__(256) unsigned char tt_static_scratch[TT_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+char *g_scratch_ptr[kMaxDevices];  // device address of tt_static_scratch on each device, once known
+
+char *static_scratch_base() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(tt_static_scratch)) != hipSuccess) return nullptr;
+    g_scratch_ptr[dev] = (char *)p;
+  }
+  return g_scratch_ptr[dev];
+}
 
 bool derive_shape(const tt_table *t, TTShape *sh) {
   if (!t) return false;
@@ -329,6 +350,29 @@ tt_status tt_core_sgd_update(const tt_table *table, const tt_plan *plan,
   it.table = table; it.plan = const_cast<tt_plan *>(plan);
   for (int k = 0; k < 3; ++k) it.dcore[k] = const_cast<float *>(dcore[k]);
   return run_single(OP_SGD, &it, lr, (hipStream_t)stream);
+}
+
+tt_status tt_emb_bag_forward_static(const tt_table *table, const int64_t *indices, const int64_t *offsets,
+                                    int64_t nnz, int64_t num_bags, float *out, void *stream) {
+  if (!table || !offsets || (nnz > 0 && !indices) || (num_bags > 0 && !out)) return TT_ERR_INVALID_ARG;
+  TTShape sh;
+  if (!derive_shape(table, &sh)) return TT_ERR_SHAPE;
+  if (!batch_ok(nnz, num_bags) || !cores_present(table)) return TT_ERR_INVALID_ARG;
+  const bool mfma = ttk_mfma_selected(sh, table->core[1], table->core[2]);
+  if (layout(sh, mfma, nnz, num_bags, nullptr, nullptr, true) > TT_STATIC_SCRATCH_BYTES) return TT_ERR_WORKSPACE;
+  char *base = static_scratch_base();
+  if (!base) return TT_ERR_HIP;
+  tt_plan plan;
+  layout(sh, mfma, nnz, num_bags, base, &plan, true);
+  for (int k = 0; k < 3; ++k) { plan.n[k] = table->n[k]; plan.d[k] = table->d[k]; }
+  for (int k = 0; k < 4; ++k) plan.r[k] = table->r[k];
+  plan.workspace = base;
+  plan.workspace_bytes = TT_STATIC_SCRATCH_BYTES;
+  TTDev d;
+  fill_dev(&d, sh, table, &plan, indices, offsets, nnz, num_bags, nullptr, out, nullptr, nullptr, 0.f, false);
+  const TTBatch b = {1, &d, nullptr};
+  const tt_status st = ttk_reorder(b, (hipStream_t)stream);
+  return st != TT_OK ? st : ttk_forward_plan(b, (hipStream_t)stream);
 }
 
 size_t tt_batch_desc_bytes(int num_tables) {
