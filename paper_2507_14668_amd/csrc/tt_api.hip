@@ -109,7 +109,7 @@ size_t layout(const TTShape &sh, bool mfma, int64_t nnz, int64_t num_bags, char 
     q.gagg = floats((size_t)max_rows * sh.D);
     q.hbuf = mfma ? nullptr : floats((size_t)max_pref * sh.P);
     const size_t strips = (size_t)ttk_mfma_strips(sh);
-    q.t3buf = floats((size_t)max_rows * sh.S3 * strips);
+    q.t3buf = floats((size_t)max_rows * sh.S3);
     q.t1buf = floats((size_t)max_pref * sh.S1 * strips);
     size_t part = (size_t)(tt_ceil_div(nnz, TT_SEG_MIN_CHUNK) + 1) * 2 * sh.D;
     size_t part3 = (size_t)(tt_ceil_div(max_rows, TT_SEG_MIN_CHUNK) + 1) * 2 * sh.S3;

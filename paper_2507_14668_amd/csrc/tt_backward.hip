@@ -91,7 +91,7 @@ __device__ __forceinline__ SegView seg_view(const TTDev &d, int kind) {
     v.out = d.plan.gagg; v.out_inner = d.sh.D; v.nseg = (int)d.plan.max_rows; v.dense = 0;
   } else if (kind == SEG_DG3) {  // core 2: per-row contributions of all rows sharing i3
     v.W = d.sh.S3; v.count_ptr = d.plan.counts + 0; v.seg_src = d.plan.i3_of_sorted; v.seg_div = 1;
-    v.gidx = d.plan.rows_by_i3; v.seg_off = d.plan.i3_seg; v.src = d.plan.t3buf; v.nsub = d.strips;
+    v.gidx = d.plan.rows_by_i3; v.seg_off = d.plan.i3_seg; v.src = d.plan.t3buf; v.nsub = 1;
     v.out = d.dg[2]; v.out_inner = d.sh.d3; v.nseg = d.sh.n3; v.dense = 1;
     if (d.fused) { v.out = const_cast<float *>(d.g[2]); v.dense = 0; v.fused = 1; }
   } else {  // core 0: per-prefix contributions of all prefixes sharing i1 (contiguous)

@@ -69,7 +69,7 @@ struct TTDev {
   float *out;
   int nnz, num_bags;
   int sort_tiles;          // radix tiles of the main lookup sort (hist row length)
-  int strips;              // contributions per row / prefix in t3buf / t1buf: 256-column strips (matrix-core path), else 1
+  int strips;              // contributions per prefix in t1buf: one per strip of the core-1 slice (matrix-core path), else 1
   float lr;
   int fused;               // backward applies G <- G - lr*dG where each gradient slice is completed
   int mfma;                // served by the matrix-core kernels (shape supported, operands aligned)
@@ -123,11 +123,11 @@ tt_status ttk_reorder(const TTBatch &b, hipStream_t s);
 tt_status ttk_forward_plan(const TTBatch &b, hipStream_t s);
 bool ttk_forward_mfma_supported(const TTShape &sh);
 tt_status ttk_forward_mfma(const TTBatch &b, hipStream_t s);
-// number of 256-column strips a core-1 slice is cut into by the matrix-core kernels (1 when the
-// shape is served by the plain-ALU kernels); t3buf / t1buf hold one contribution per strip
+// number of strips (16 values of r2, all j2) a core-1 slice is cut into by the backward matrix-core
+// kernel (1 when the shape is served by the plain-ALU kernels); t1buf holds one contribution per strip
 int ttk_mfma_strips(const TTShape &sh);
-// The backward matrix-core kernel has n2 * strips workgroups; a table with few core-1 slices
-// leaves most of the 256 CUs idle, so the chunks of one (i2, strip) are then dealt to `split`
+// The backward matrix-core kernel has n2 * strips workgroups, two per compute unit; a table with few
+// core-1 slices leaves most of the 256 CUs idle, so the chunks of one (i2, strip) are then dealt to `split`
 // workgroups that write partial core-1 gradients, summed in a fixed order by a second kernel.
 int ttk_bwd_split(const TTShape &sh);
 #define TT_BWD_MAX_SPLIT 8
