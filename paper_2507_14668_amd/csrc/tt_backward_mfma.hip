@@ -54,8 +54,7 @@ struct BwdGeom {
   static constexpr int D = 128, S1 = 4 * R1, S3 = R2 * 4;
   // LDS row strides.  A 64-lane read is served in two halves (lanes 0-31: lq = 0,1); the strides put
   // the 32 lanes of a half on 32 different banks for the access named first.
-  static constexpr int RS = R1 + 2;        // As  [32 (p,j1)][R1]   F1 A operand: row = lm, +lq
-  static constexpr int RT = 34;            // AsT [R1][32 (p,j1)]   dG2 A operand: row = lm, +lq
+  static constexpr int RS = R1 + 2;        // As  [32 (p,j1)][R1]   F1 A operand: row = lm, +lq (dG2 A operand: row = lq, +lm, 2-way)
   static constexpr int PS = 32 * RB + 16;  // P12 [p][cc = 32][r2l = 16]  F1 store / T3 B operand: 16*lq + lm
   static constexpr int HR = SC + 2;        // Hs  [32 (p,j1)][128 c]      T1 A operand: row = lm, +lq (dG2 B operand 2-way)
   static constexpr int GS = D + 8;         // gs  [32 rows][(cc, j3)]     T3 A operand: row = lm/4, 4*lq + lm%4
@@ -64,17 +63,17 @@ struct BwdGeom {
   static constexpr int KS1 = R1 / 4;       // k steps of F1
   static constexpr int NT1 = R1 / 16;      // r1 tiles
   static constexpr int T1_MT = NT1 == 4 ? 2 : 1;  // row tiles of T1 per wavefront
-  static constexpr int OFF_AST = 32 * RS;
-  static constexpr int OFF_P12 = OFF_AST + R1 * RT;
+  static constexpr int A_FLOATS = 32 * RS;        // one core-0 tile; two of them: current chunk / next chunk
+  static constexpr int OFF_P12 = 2 * A_FLOATS;
   static constexpr int OFF_HS = OFF_P12 + TT_MP * PS;
   static constexpr int OFF_GS = OFF_HS + 32 * HR;
   static constexpr int OFF_G3S = OFF_GS + NROW * GS;
-  static constexpr size_t LDS_FLOATS = (size_t)OFF_G3S + NROW * G3S;
+  static constexpr size_t LDS_FLOATS = (size_t)OFF_G3S + (NROW + 8) * G3S;  // spare rows: operand prefetch reads up to two groups of four rows ahead
   static constexpr int GPT = (32 * R1) / NTHR;  // core-0 tile elements per thread
   static_assert(R2 % RB == 0 && (R1 == 32 || R1 == 64) && TT_MP == 8, "shape");
   static_assert(R1 * SW <= TT_MP * PS + 32 * HR + NROW * GS, "the strip staging tile aliases the P12 / H / row areas");
   static_assert(LDS_FLOATS * 4 + 2048 <= 80 * 1024, "two workgroups per compute unit");
-  static_assert(OFF_P12 % 4 == 0 && OFF_GS % 4 == 0 && OFF_G3S % 4 == 0, "float4 accesses");
+  static_assert(OFF_P12 % 4 == 0 && OFF_GS % 4 == 0 && OFF_G3S % 4 == 0 && GS % 4 == 0, "float4 accesses");
 };
 
 template <bool BATCHED, int R1, int R2>
@@ -94,17 +93,24 @@ k_bwd_mfma(TTArg<BATCHED> a) {
   const float lr = d.lr;
   float *dg2 = fused ? const_cast<float *>(d.g[1]) : d.dg[1];
   extern __shared__ float lds[];
-  float *As = lds, *AsT = lds + G::OFF_AST, *P12s = lds + G::OFF_P12, *Hs = lds + G::OFF_HS;
+  float *P12s = lds + G::OFF_P12, *Hs = lds + G::OFF_HS;  // core-0 tiles: lds + par * A_FLOATS
   float *gsm = lds + G::OFF_GS, *g3sm = lds + G::OFF_G3S;
-  __shared__ __align__(16) int s_bitem[NROW / 4][4];  // quads of the current row batch: prefix, first row slot, rows, last
+  // per row slot of the current batch: x = prefix | rows of the item that starts here << 4 (0: none
+  // starts here) | item is the prefix's last << 8 | row is the prefix's last << 9; y = the row's slot
+  __shared__ __align__(8) int s_brow[NROW][2];
   __shared__ int s_q[META], s_i1[META], s_u0[META], s_nr[META];
 
   // workgroup = (i2, strip, part): with split > 1 the chunks of one (i2, strip) are dealt in
   // contiguous runs to `split` workgroups, each of which leaves a partial core-1 gradient
-  const int split = d.bwd_split;
-  if ((int)blockIdx.x >= sh.n2 * G::NSB * split) return;  // a table of the batch with fewer i2 values
-  const int part = blockIdx.x % split, wg = blockIdx.x / split;
-  const int i2 = wg / G::NSB, sblk = wg - i2 * G::NSB;
+  // Workgroup index = ((i2 / 8) * (strips * split) + (strip, part)) * 8 + i2 % 8.  Workgroups are
+  // dealt to the 8 XCDs round-robin, so all strips and parts of one i2 run on XCD i2 % 8, close in
+  // time, and find the merged gradients and plan entries of that i2's rows in its L2; and the
+  // i2 values are started in increasing order (with Zipf ranks as row numbers the hot prefixes, whose
+  // workgroups run longest, are the ones with small i2).
+  const int split = d.bwd_split, nsub = G::NSB * split;
+  const int i2 = (int)(blockIdx.x / (8 * nsub)) * 8 + (int)(blockIdx.x & 7), sub = (int)(blockIdx.x >> 3) % nsub;
+  if (i2 >= sh.n2) return;  // padding of the last group of 8, or a table of the batch with fewer i2 values
+  const int sblk = sub / split, part = sub - sblk * split;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int lm = lane & 15, lq = lane >> 4;
   // element (r1, c = (j2, r2l)) of the strip sits at strip_col + r1 * r1_stride + j2 * R2 + r2l
@@ -170,70 +176,81 @@ k_bwd_mfma(TTArg<BATCHED> a) {
       g1n[k] = g1[(size_t)(i1 >= 0 ? i1 : 0) * G::S1 + (row & 3) * R1 + r1];
     }
   };
-  auto stage_chunk = [&](int mo) __attribute__((always_inline)) {  // registers -> LDS, both operand layouts
+  auto stage_chunk = [&](int par, int mo) __attribute__((always_inline)) {  // registers -> core-0 tile `par`
+    float *As2 = lds + par * G::A_FLOATS;
 #pragma unroll
     for (int k = 0; k < G::GPT; ++k) {
       const int e = threadIdx.x + k * NTHR, row = e / R1, r1 = e - row * R1;
-      const float v = s_i1[mo + (row >> 2)] >= 0 ? g1n[k] : 0.f;  // zero rows for prefixes the chunk does not have
-      As[row * G::RS + r1] = v;
-      AsT[r1 * G::RT + row] = v;
+      As2[row * G::RS + r1] = s_i1[mo + (row >> 2)] >= 0 ? g1n[k] : 0.f;  // zero rows for prefixes the chunk does not have
     }
   };
 
-  // Row batches: 32 row slots x 8 threads.  Thread t serves row slot t/8: a float4 of the merged
-  // gradient row per 8 columns, and the strip's 16 rows of the core-2 slice (one float4 each).
-  int bi_p = 0, bi_ubase = 0, bi_nrow = 0, bi_last = 0;
+  // Row batches: the distinct rows of a chunk, prefix after prefix, are cut into batches of 32; an
+  // ITEM is a run of at most 4 rows of one prefix inside a batch (it starts at every fourth row of a
+  // prefix and at a batch boundary).  Thread t serves row slot t/8 of the batch: a float4 of the
+  // merged gradient row per 8 columns, and the strip's 16 rows of the core-2 slice (one float4 each).
+  int bi_x = 0, bi_y = 0;
   float4 rg[4], r3[2];
 #pragma unroll
   for (int k = 0; k < 4; ++k) rg[k] = make_float4(0.f, 0.f, 0.f, 0.f);
   r3[0] = r3[1] = make_float4(0.f, 0.f, 0.f, 0.f);
   int rvalid = 0;
-  auto chunk_items = [&](int mo) __attribute__((always_inline)) {  // row quads of the chunk
+  auto chunk_rows = [&](int mo) __attribute__((always_inline)) {  // distinct rows of the chunk
     int tot = 0;
 #pragma unroll
-    for (int k = 0; k < TT_MP; ++k) tot += (s_nr[mo + k] + 3) >> 2;
+    for (int k = 0; k < TT_MP; ++k) tot += s_nr[mo + k];
     return tot;
   };
-  auto issue_batch = [&](int b, int mo) __attribute__((always_inline)) {
-    // global -> registers for batch b of the chunk whose plan entries sit at offset `mo`
-    const int rr = threadIdx.x >> 3, sub = threadIdx.x & 7;
-    const int it = 8 * b + (rr >> 2), r = rr & 3;
-    int p = 0, before = 0, run = 0;  // prefix whose quads hold item `it`, quads before it
+  // The row of the table behind row slot `rr` of batch b (its i3 selects the core-2 slice): loaded
+  // one step before the batch's operands are requested, so that a batch costs one memory round
+  // trip, not two dependent ones.  Rows past the chunk's end read slot 0 (never used).
+  auto row_slot = [&](int R, int mo, int &p, int &before, int &run) __attribute__((always_inline)) {
+    p = 0; before = 0; run = 0;  // prefix that holds row R of the chunk, rows before that prefix, rows of the chunk
 #pragma unroll
     for (int k = 0; k < TT_MP; ++k) {
-      const int q4 = (s_nr[mo + k] + 3) >> 2;
-      if (run <= it) { p = k; before = run; }
-      run += q4;
+      if (run <= R) { p = k; before = run; }
+      run += s_nr[mo + k];
     }
+  };
+  auto fetch_row_id = [&](int b, int mo) __attribute__((always_inline)) {
+    int p, before, run;
+    const int R = NROW * b + (threadIdx.x >> 3);
+    row_slot(R, mo, p, before, run);
+    return uniq_row[R < run ? s_u0[mo + p] + (R - before) : 0];
+  };
+  auto issue_batch = [&](int b, int mo, int row_id) __attribute__((always_inline)) {
+    // global -> registers for batch b of the chunk whose plan entries sit at offset `mo`
+    const int rr = threadIdx.x >> 3, sub = threadIdx.x & 7;
+    const int R = NROW * b + rr;  // row of the chunk
+    int p, before, run;
+    row_slot(R, mo, p, before, run);
     rvalid = 0;
-    bi_p = 0; bi_ubase = 0; bi_nrow = 0; bi_last = 0;
-    if (it < run) {
-      const int nr = s_nr[mo + p], base = 4 * (it - before), r0 = base + r;
-      bi_p = p;
-      bi_ubase = s_u0[mo + p] + base;
-      bi_nrow = (nr - base) < 4 ? (nr - base) : 4;
-      bi_last = base + 4 >= nr;
-      if (r0 < nr) {
-        const int u = s_u0[mo + p] + r0;
-        const int i3 = uniq_row[u] % sh.n3;
-        const float4 *gp = reinterpret_cast<const float4 *>(gagg + (size_t)u * G::D);
-        // core 2 as stored, G3[r2][i3][0..3]: one float4 per r2 of the strip
-        const float4 *g3p = reinterpret_cast<const float4 *>(g3) + (size_t)(sblk * RB + sub) * sh.n3 + i3;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) rg[k] = gp[sub + 8 * k];
-#pragma unroll
-        for (int k = 0; k < 2; ++k) r3[k] = g3p[(size_t)8 * k * sh.n3];
-        rvalid = 1;
+    bi_x = 0; bi_y = 0;
+    if (R < run) {
+      const int nr = s_nr[mo + p], r0 = R - before, u = s_u0[mo + p] + r0;
+      int nrow = 0;
+      if ((r0 & 3) == 0 || rr == 0) {  // an item starts here
+        nrow = 4 - (r0 & 3);
+        nrow = nrow < nr - r0 ? nrow : nr - r0;
+        nrow = nrow < NROW - rr ? nrow : NROW - rr;
       }
+      bi_x = p | (nrow << 4) | ((r0 + nrow == nr) ? 256 : 0) | ((r0 + 1 == nr) ? 512 : 0);
+      bi_y = u;
+      const int i3 = row_id % sh.n3;
+      const float4 *gp = reinterpret_cast<const float4 *>(gagg + (size_t)u * G::D);
+      // core 2 as stored, G3[r2][i3][0..3]: one float4 per r2 of the strip
+      const float4 *g3p = reinterpret_cast<const float4 *>(g3) + (size_t)(sblk * RB + sub) * sh.n3 + i3;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) rg[k] = gp[sub + 8 * k];
+#pragma unroll
+      for (int k = 0; k < 2; ++k) r3[k] = g3p[(size_t)8 * k * sh.n3];
+      rvalid = 1;
     }
   };
   auto land_batch = [&]() __attribute__((always_inline)) {  // registers -> LDS
-    if ((threadIdx.x & 31) == 0) {
-      int *rec = s_bitem[threadIdx.x >> 5];
-      rec[0] = bi_p; rec[1] = bi_ubase; rec[2] = bi_nrow; rec[3] = bi_last;
-    }
+    const int rr = threadIdx.x >> 3, sub = threadIdx.x & 7;
+    if (sub == 0) { s_brow[rr][0] = bi_x; s_brow[rr][1] = bi_y; }
     if (rvalid) {
-      const int rr = threadIdx.x >> 3, sub = threadIdx.x & 7;
       float4 *gd = reinterpret_cast<float4 *>(gsm + rr * G::GS) + sub;
       float4 *g3d = reinterpret_cast<float4 *>(g3sm + rr * G::G3S) + sub;
 #pragma unroll
@@ -274,16 +291,21 @@ k_bwd_mfma(TTArg<BATCHED> a) {
     for (int e = threadIdx.x; e < 32 * G::HR; e += NTHR) Hs[e] = 0.f;
   }
 
-  stage_chunk(0);
-  issue_batch(0, 0);  // first row batch of the first chunk
+  stage_chunk(0, 0);
+  issue_batch(0, 0, fetch_row_id(0, 0));  // first row batch of the first chunk
+  int par = 0;        // core-0 tile of the current chunk
 
   for (int cs = seg0; cs < seg1; cs += TT_MP) {
     const int cnt = (seg1 - cs) < TT_MP ? (seg1 - cs) : TT_MP;
     const int mo = (cs - seg0) % META;  // this chunk's offset in s_q / s_i1 / s_u0 / s_nr
     const bool more = cs + TT_MP < seg1, refill = mo + TT_MP == META;
-    __syncthreads();  // this chunk's core-0 tiles are visible
-    const int total_items = chunk_items(mo);
-    if (more && !refill) fetch_chunk(mo + TT_MP);  // next chunk's core-0 rows, staged after this chunk's last reader
+    __syncthreads();  // this chunk's core-0 tile is visible; the previous chunk's readers of H and of the other tile are done
+    const float *As = lds + par * G::A_FLOATS;
+    const int total_rows = chunk_rows(mo);
+    if (more && !refill) fetch_chunk(mo + TT_MP);  // next chunk's core-0 rows, staged into the other tile after the row phase
+    // row ids for the second batch of this chunk and the first batch of the next one
+    int id_next_batch = fetch_row_id(1, mo);
+    const int id_next_chunk = (more && !refill) ? fetch_row_id(0, mo + TT_MP) : 0;
 
     // ---- F1: P12 of the chunk, this wavefront's 32 columns -> P12s[p][cc = (j1, j2)][r2l] ----------
     {
@@ -321,50 +343,116 @@ k_bwd_mfma(TTArg<BATCHED> a) {
     // wavefronts 2-3 form the T3 tile of every other quad.  The split is by output tile, so a prefix
     // with hundreds of rows is shared by all wavefronts and no partial sums are combined.
     {
-      const int nbatch = (total_items + 7) >> 3;
+      const int nbatch = (total_rows + NROW - 1) / NROW;
       f32x4 hacc = (f32x4){0.f, 0.f, 0.f, 0.f};
       for (int b = 0; b < nbatch; ++b) {
         // uniform: the next batch of a row-rich chunk is requested now and lands after this one
-        if (b + 1 < nbatch) issue_batch(b + 1, mo);
-        const int n = (total_items - 8 * b) < 8 ? (total_items - 8 * b) : 8;
-        // lane l keeps the record of batch slot l % 8; a slot's fields are read with readlane
-        const int4 rec = *reinterpret_cast<const int4 *>(s_bitem[lane & 7]);
+        if (b + 1 < nbatch) {
+          issue_batch(b + 1, mo, id_next_batch);
+          id_next_batch = fetch_row_id(b + 2, mo);
+        }
+        const int n = (total_rows - NROW * b) < NROW ? (total_rows - NROW * b) : NROW;
+        // lane l keeps the record of row slot l % 32; a slot's fields are read with readlane
+        const int2 rec = *reinterpret_cast<const int2 *>(s_brow[lane & (NROW - 1)]);
+        // The batch is a run of items (<= 4 rows of one prefix each): the item at row slot rr has
+        // `nrow` rows and the next one starts at rr + nrow.  Both loops below are written for few
+        // instructions per row -- with one or two wavefronts per SIMD the row phase is bound by
+        // instruction issue, not by the matrix cores.
         if (wave < 2) {  // H tile `wave`: M = cc, N = r2l, K = j3, one distinct row per MFMA
-          for (int j = 0; j < n; ++j) {
-            const int nrow = __builtin_amdgcn_readlane(rec.z, j), last = __builtin_amdgcn_readlane(rec.w, j);
-            const float *gq = gsm + (j * 4) * G::GS + (16 * wave + lm) * 4 + lq;
-            const float *g3q = g3sm + (j * 4) * G::G3S + lm * 4 + lq;
-            float x[4], y[4];
+          // The operands of the next item are requested before the MFMAs of the current one (an item's
+          // four row slots are always read; slots past its rows belong to later rows and are not used).
+          const float *gq = gsm + (16 * wave + lm) * 4 + lq;
+          const float *g3q = g3sm + lm * 4 + lq;
+          struct Ops { float x[4], y[4]; };
+          auto load_ops = [&](int r0) __attribute__((always_inline)) {
+            Ops o;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-              x[r] = gq[r * G::GS];
-              y[r] = g3q[r * G::G3S];
+              o.x[r] = gq[(r0 + r) * G::GS];
+              o.y[r] = g3q[(r0 + r) * G::G3S];
             }
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-              if (r < nrow) hacc = MFMA(x[r], y[r], hacc);
-            if (last) {  // last quad of the prefix: H[cc = 16*wave + 4*lq + v][r2l = lm]
-              const int p = __builtin_amdgcn_readlane(rec.x, j);
-#pragma unroll
-              for (int v = 0; v < 4; ++v) {
-                const int cc = 16 * wave + 4 * lq + v;  // (j1, j2)
-                Hs[(p * 4 + (cc >> 3)) * G::HR + (cc & 7) * RB + lm] = hacc[v];
+            return o;
+          };
+          auto compute = [&](int f, const Ops &o) __attribute__((always_inline)) {
+            const int nrow = (f >> 4) & 15;
+            hacc = MFMA(o.x[0], o.y[0], hacc);
+            if (nrow > 1) {  // uniform
+              hacc = MFMA(o.x[1], o.y[1], hacc);
+              if (nrow > 2) {
+                hacc = MFMA(o.x[2], o.y[2], hacc);
+                if (nrow > 3) hacc = MFMA(o.x[3], o.y[3], hacc);
               }
+            }
+            if (f & 256) {  // the prefix ends with this item: H[cc = 16*wave + 4*lq + v][r2l = lm]
+              float *hp = Hs + ((f & 15) * 4 + 2 * wave + (lq >> 1)) * G::HR + (4 * (lq & 1)) * RB + lm;
+#pragma unroll
+              for (int v = 0; v < 4; ++v) hp[v * RB] = hacc[v];  // cc = (j1 = 2*wave + lq/2, j2 = 4*(lq%2) + v)
               hacc = (f32x4){0.f, 0.f, 0.f, 0.f};
             }
+          };
+          int rr = 0, f = __builtin_amdgcn_readlane(rec.x, 0);
+          Ops oa = load_ops(0), ob;
+          while (true) {  // written out twice so that both operand sets stay in registers
+            int rn = rr + ((f >> 4) & 15);
+            int fn = __builtin_amdgcn_readlane(rec.x, rn & (NROW - 1));
+            ob = load_ops(rn);
+            compute(f, oa);
+            if (rn >= n) break;
+            rr = rn + ((fn >> 4) & 15);
+            f = __builtin_amdgcn_readlane(rec.x, rr & (NROW - 1));
+            oa = load_ops(rr);
+            compute(fn, ob);
+            if (rr >= n) break;
           }
-        } else {  // T3: M = (row, j3) = lm, N = r2l, K = cc
-          for (int j = wave - 2; j < n; j += 2) {
-            const int p = __builtin_amdgcn_readlane(rec.x, j), ubase = __builtin_amdgcn_readlane(rec.y, j),
-                      nrow = __builtin_amdgcn_readlane(rec.z, j);
-            const float *ga = gsm + (j * 4 + (lm >> 2)) * G::GS + (lm & 3) + lq * 4;  // + 16*ks: cc = 4*ks + lq
-            const float *pb = P12s + p * G::PS + lq * RB + lm;                        // + 64*ks
-            f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
+        } else {  // T3: M = (row, j3) = lm, N = r2l, K = cc; wavefront 2 takes the even items, 3 the odd ones
+          struct Ops3 { float a[8], b[8]; };
+          auto load_ops = [&](int rr, int f) __attribute__((always_inline)) {
+            const float *ga = gsm + (rr + (lm >> 2)) * G::GS + (lm & 3) + lq * 4;  // + 16*ks: cc = 4*ks + lq
+            const float *pb = P12s + (f & 15) * G::PS + lq * RB + lm;               // + 64*ks
+            Ops3 o;
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) acc = MFMA(ga[16 * ks], pb[4 * RB * ks], acc);
-            if (lq < nrow)
+            for (int ks = 0; ks < 8; ++ks) {
+              o.a[ks] = ga[16 * ks];
+              o.b[ks] = pb[4 * RB * ks];
+            }
+            return o;
+          };
+          auto compute = [&](int rr, int f, const Ops3 &o) __attribute__((always_inline)) {
+            f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f}, accb = (f32x4){0.f, 0.f, 0.f, 0.f};  // two chains of four
+#pragma unroll
+            for (int ks = 0; ks < 8; ks += 2) {
+              acc = MFMA(o.a[ks], o.b[ks], acc);
+              accb = MFMA(o.a[ks + 1], o.b[ks + 1], accb);
+            }
+            const int ubase = __builtin_amdgcn_readlane(rec.y, rr);
+            if (lq < ((f >> 4) & 15))
               *reinterpret_cast<float4 *>(t3buf + (size_t)(ubase + lq) * G::S3 + (sblk * RB + lm) * 4) =
-                  make_float4(acc[0], acc[1], acc[2], acc[3]);
+                  make_float4(acc[0] + accb[0], acc[1] + accb[1], acc[2] + accb[2], acc[3] + accb[3]);
+          };
+          // (row slot, record) of this wavefront's next item at or after row slot rr, skipping `skip` items
+          auto next_item = [&](int &rr, int &f, int skip) __attribute__((always_inline)) {
+            f = __builtin_amdgcn_readlane(rec.x, rr & (NROW - 1));
+            for (int k = 0; k < skip && rr < n; ++k) {
+              rr += (f >> 4) & 15;
+              f = __builtin_amdgcn_readlane(rec.x, rr & (NROW - 1));
+            }
+          };
+          int rr = 0, f;
+          next_item(rr, f, wave - 2);
+          if (rr < n) {
+            Ops3 oa = load_ops(rr, f), ob;
+            while (true) {  // written out twice so that both operand sets stay in registers
+              int rn = rr, fn;
+              next_item(rn, fn, 2);
+              if (rn < n) ob = load_ops(rn, fn);
+              compute(rr, f, oa);
+              if (rn >= n) break;
+              rr = rn;
+              next_item(rr, f, 2);
+              if (rr < n) oa = load_ops(rr, f);
+              compute(rn, fn, ob);
+              if (rr >= n) break;
+            }
           }
         }
         if (b + 1 < nbatch) {
@@ -377,7 +465,10 @@ k_bwd_mfma(TTArg<BATCHED> a) {
     __syncthreads();  // H of the chunk is complete; P12 and the row areas are free
     // first row batch of the NEXT chunk: requested now, landed after the next F1, so that the T1 /
     // dG2 / F1 MFMAs in between cover its latency
-    if (more && !refill) issue_batch(0, mo + TT_MP);
+    if (more && !refill) {
+      issue_batch(0, mo + TT_MP, id_next_chunk);
+      stage_chunk(par ^ 1, mo + TT_MP);  // the other core-0 tile was last read by the previous chunk
+    }
 
     // ---- T1: this wavefront's tile(s) [16 (p,j1)] x [16 r1], K = the strip's 128 columns ------------
     {
@@ -409,7 +500,7 @@ k_bwd_mfma(TTArg<BATCHED> a) {
     for (int ks = 0; ks < 8; ++ks) {
       float av[G::NT1], bv[2];
 #pragma unroll
-      for (int mt = 0; mt < G::NT1; ++mt) av[mt] = AsT[(16 * mt + lm) * G::RT + 4 * ks + lq];
+      for (int mt = 0; mt < G::NT1; ++mt) av[mt] = As[(4 * ks + lq) * G::RS + 16 * mt + lm];
 #pragma unroll
       for (int nt = 0; nt < 2; ++nt) bv[nt] = Hs[(4 * ks + lq) * G::HR + 32 * wave + 16 * nt + lm];
 #pragma unroll
@@ -417,30 +508,44 @@ k_bwd_mfma(TTArg<BATCHED> a) {
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt) acc2[mt][nt] = MFMA(av[mt], bv[nt], acc2[mt][nt]);
     }
-    if (more) {
-      __syncthreads();  // every reader of this chunk's core-0 tiles, H and plan entries is done
-      if (refill) {  // uniform: the staged plan entries are used up, fetch the next 64
-        fetch_meta(cs + TT_MP);
-        __syncthreads();
-        fetch_chunk(0);
-        stage_chunk(0);
-        issue_batch(0, 0);
-      } else {
-        stage_chunk(mo + TT_MP);
-      }
+    if (more && refill) {  // uniform: the staged plan entries are used up, fetch the next 64
+      __syncthreads();  // every reader of the plan entries is done
+      fetch_meta(cs + TT_MP);
+      __syncthreads();
+      fetch_chunk(0);
+      stage_chunk(par ^ 1, 0);
+      issue_batch(0, 0, fetch_row_id(0, 0));
     }
+    par ^= 1;
   }
 
-  // dG2[r1 = 16*mt + 4*lq + v][i2][c = 32*wave + 16*nt + lm], complete for this i2 and strip
+  // dG2[r1 = 16*mt + 4*lq + v][i2][c = 32*wave + 16*nt + lm], complete for this i2 and strip.  With
+  // the fused update every old core element is requested before the first store (the core may alias
+  // nothing here, but the compiler cannot know: load / store pairs would each wait for memory).
+  float *dbase = dg2 + (size_t)(4 * lq) * r1_stride + strip_col + (2 * wave) * R2 + lm;
+  if (fused && split == 1) {
+    float old[G::NT1][2][4];
 #pragma unroll
-  for (int mt = 0; mt < G::NT1; ++mt)
+    for (int mt = 0; mt < G::NT1; ++mt)
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt)
+      for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        float *dst = dg2 + (size_t)(16 * mt + 4 * lq + v) * r1_stride + strip_col + (2 * wave + nt) * R2 + lm;
-        *dst = (fused && split == 1) ? fmaf(-lr, acc2[mt][nt][v], *dst) : acc2[mt][nt][v];
-      }
+        for (int v = 0; v < 4; ++v) old[mt][nt][v] = dbase[(size_t)(16 * mt + v) * r1_stride + nt * R2];
+#pragma unroll
+    for (int mt = 0; mt < G::NT1; ++mt)
+#pragma unroll
+      for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+          dbase[(size_t)(16 * mt + v) * r1_stride + nt * R2] = fmaf(-lr, acc2[mt][nt][v], old[mt][nt][v]);
+  } else {
+#pragma unroll
+    for (int mt = 0; mt < G::NT1; ++mt)
+#pragma unroll
+      for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) dbase[(size_t)(16 * mt + v) * r1_stride + nt * R2] = acc2[mt][nt][v];
+  }
 }
 
 // Sums the partial core-1 gradients of a split table in part order and stores the gradient, or
@@ -492,7 +597,7 @@ tt_status launch(const TTBatch &b, hipStream_t s) {
   });
   if (!configured) return TT_ERR_HIP;
   const long long blocks = tt_batch_max(b, [](const TTDev &d) {
-    return (long long)d.sh.n2 * G::NSB * d.bwd_split; });
+    return (long long)((d.sh.n2 + 7) & ~7) * G::NSB * d.bwd_split; });
   TTProfScope prof(&b.host[0].plan, TT_KERNEL_BWD_CONTRACT, s);
   if (b.dev)
     hipLaunchKernelGGL((k_bwd_mfma<true, R1, R2>), dim3((unsigned)blocks, (unsigned)b.T),
@@ -514,14 +619,20 @@ int ttk_mfma_strips(const TTShape &sh) {
   return ttk_forward_mfma_supported(sh) ? sh.R2 / RB : 1;
 }
 
+#ifndef TT_BWD_SPLIT_BELOW
+#define TT_BWD_SPLIT_BELOW 256
+#endif
+#ifndef TT_BWD_SPLIT_TARGET
+#define TT_BWD_SPLIT_TARGET 512
+#endif
 int ttk_bwd_split(const TTShape &sh) {
   if (!ttk_forward_mfma_supported(sh)) return 1;
   // two workgroups fit on each of the 256 compute units: a table with fewer than 256 (i2, strip)
   // pairs deals the chunks of each pair to several workgroups
   const int wgs = sh.n2 * ttk_mfma_strips(sh);
-  if (wgs >= 256) return 1;
-  const int s = 512 / wgs;
-  return s > TT_BWD_MAX_SPLIT ? TT_BWD_MAX_SPLIT : s;
+  if (wgs >= TT_BWD_SPLIT_BELOW) return 1;
+  const int s = TT_BWD_SPLIT_TARGET / wgs;
+  return s > TT_BWD_MAX_SPLIT ? TT_BWD_MAX_SPLIT : (s < 1 ? 1 : s);
 }
 
 tt_status ttk_backward_mfma(const TTBatch &b, hipStream_t s) {

@@ -110,6 +110,10 @@ def _run(emu, shape, cores, idx, off, grad, lr):
     # rows looked up hundreds of times: segments of the gradient merge that span whole workgroups of stage 1
     ("mfma_r64_hot_rows", (2, 1, 2), (4, 8, 4), (1, 64, 64, 1), 800, 4),
     ("plain_hot_rows", (1, 2, 2), (2, 3, 2), (1, 3, 5, 1), 2500, 3),
+    # more than 64 prefixes under one i2 (the staged plan entries are refilled) and prefixes with more
+    # than 32 distinct rows (row batches that cut a prefix's rows at any position)
+    ("mfma_r32_refill", (75, 1, 3), (4, 8, 4), (1, 32, 32, 1), 400, 3),
+    ("mfma_r64_row_batches", (2, 2, 45), (4, 8, 4), (1, 64, 64, 1), 300, 4),
 ])
 def test_emulated_kernels_match_oracle(emu, ora, name, n, d, r, nb, ml):
     import gpu_util as g

@@ -78,6 +78,10 @@ def test_small_shapes(g, ora, seed, n, d, r, nb, ml):
     (62, (40, 3, 6), (1, 32, 32, 1), 2000, 8),    # > 16 prefixes per i2: several chunks
     (63, (3, 2, 50), (1, 64, 64, 1), 1500, 5),    # many rows per prefix, two column strips
     (64, (37, 5, 4), (1, 64, 64, 1), 900, 3),
+    (66, (150, 2, 3), (1, 32, 32, 1), 1500, 3),   # > 64 prefixes per i2: staged plan entries are refilled
+    (67, (150, 1, 5), (1, 64, 64, 1), 2500, 3),
+    (68, (3, 2, 90), (1, 64, 64, 1), 1500, 5),    # up to 90 distinct rows per prefix: several row batches
+    (69, (2, 3, 70), (1, 32, 32, 1), 1200, 4),
 ])
 def test_matrix_core_shapes(g, ora, seed, n, r, nb, ml):
     """Shapes served by the MFMA kernels (d = 4x8x4, ranks 32 or 64) on small tables."""
