@@ -12,6 +12,7 @@ struct dim3 {
   unsigned x, y, z;
   dim3(unsigned x_ = 1, unsigned y_ = 1, unsigned z_ = 1) : x(x_), y(y_), z(z_) {}
 };
+struct alignas(8) float2 { float x, y; };
 struct alignas(16) float4 { float x, y, z, w; };
 static inline float4 make_float4(float x, float y, float z, float w) { return float4{x, y, z, w}; }
 struct alignas(16) int4 { int x, y, z, w; };
@@ -54,6 +55,8 @@ void wave_mfma_16x16x4(float a, float b, float *c4);
 
 static inline hipError_t hipGetLastError() { return hipSuccess; }
 static inline hipError_t hipGetDevice(int *dev) { *dev = 0; return hipSuccess; }
+enum { hipDeviceAttributeMultiprocessorCount = 1 };
+static inline hipError_t hipDeviceGetAttribute(int *v, int, int) { *v = 4; return hipSuccess; }  // few "compute units": the work queues are exercised
 #define HIP_SYMBOL(x) (&(x))
 static inline hipError_t hipGetSymbolAddress(void **p, const void *symbol) { *p = const_cast<void *>(symbol); return hipSuccess; }
 static inline hipError_t hipFuncSetAttribute(const void *, int, int) { return hipSuccess; }
@@ -86,6 +89,7 @@ static inline void __builtin_amdgcn_wave_barrier() { emu::wave_exchange(0, -1); 
 static inline long long clock64() { return 0; }
 
 static inline int atomicAdd(int *p, int v) { return __atomic_fetch_add(p, v, __ATOMIC_RELAXED); }
+static inline void __threadfence() { __atomic_thread_fence(__ATOMIC_SEQ_CST); }
 static inline int atomicOr(int *p, int v) { return __atomic_fetch_or(p, v, __ATOMIC_RELAXED); }
 static inline float atomicAdd(float *p, float v) {
   uint32_t *u = reinterpret_cast<uint32_t *>(p);
