@@ -105,16 +105,11 @@ typedef struct {
   int32_t *prefs_by_i2;   /* [U_p] prefix slots stably sorted by i2                       */
   int32_t *i2_seg;        /* [n[1]+1] range in prefs_by_i2 of each i2                     */
   int32_t *i1_seg;        /* [n[0]+1] prefix-slot range of each i1                        */
-  int32_t *i2_chunk_off;  /* [n[1]+1] running count of 8-prefix chunks per i2 (the unit of
-                             work of the matrix-core kernels); total in counts[5]          */
-  int32_t *chunk_i2;      /* [chunks][4] per 8-prefix chunk: i2, position of its first prefix in  */
-                          /* prefs_by_i2 order, number of prefixes, 0                              */
   int32_t *pref_meta;     /* [max_prefixes][4] per prefix in i2 order: i1, first distinct-row
                              slot, distinct rows, prefix slot (one 16-byte load per prefix for
                              the matrix-core kernels)                                        */
   int32_t *counts;        /* [16] counts[0]=U_r, [1]=U_p, [2]=valid lookups, [3]=nnz,
-                             [4]=status bits (1: index out of range, 2: bad offsets),
-                             [5]=number of 8-prefix chunks                                */
+                             [4]=status bits (1: index out of range, 2: bad offsets)      */
   /* -- float scratch used by forward / backward (contents are transient) --------------- */
   float *rowbuf;          /* [max_rows][D] reconstructed distinct rows                    */
   float *gagg;            /* [max_rows][D] output gradients merged per distinct row       */

@@ -44,7 +44,7 @@ class CTable(ctypes.Structure):
 _I32P = ctypes.c_void_p
 _PLAN_INT_ARRAYS = ("sorted_row", "perm", "bag_of_sorted", "slot_of_sorted", "lookup2row", "uniq_row",
                     "row_seg", "row2pref", "uniq_pref", "pref_seg", "rows_by_i3", "i3_of_sorted",
-                    "i3_seg", "prefs_by_i2", "i2_seg", "i1_seg", "i2_chunk_off", "chunk_i2", "pref_meta", "counts")
+                    "i3_seg", "prefs_by_i2", "i2_seg", "i1_seg", "pref_meta", "counts")
 _PLAN_FLOAT_ARRAYS = ("rowbuf", "gagg", "hbuf", "t3buf", "t1buf", "partial", "dg2part")
 
 

@@ -51,6 +51,8 @@ bool derive_shape(const tt_table *t, TTShape *sh) {
   sh->P = (int)P;
   sh->R2p = sh->R2 | 1;
   sh->sentinel = (int)cap;
+  tt_div_constants(sh->n3, &sh->mul3, &sh->sh3);
+  tt_div_constants(sh->n2, &sh->mul2, &sh->sh2);
   sh->num_rows = t->num_rows;
   // the per-prefix kernels keep one slice of every operand in LDS (64 KB static budget)
   const long long lds_floats = (long long)sh->S1 + (long long)sh->d1 * sh->d2 * sh->R2p + sh->P +
@@ -100,8 +102,6 @@ size_t layout(const TTShape &sh, bool mfma, int64_t nnz, int64_t num_bags, char 
   q.prefs_by_i2 = ints(max_pref);
   q.i2_seg = ints(sh.n2 + 1);
   q.i1_seg = ints(sh.n1 + 1);
-  q.i2_chunk_off = ints(sh.n2 + 1);
-  q.chunk_i2 = ints(4 * (max_pref / TT_MP + sh.n2 + 1) + 4);  // 4 ints per chunk; every i2 adds at most one partly filled chunk
   q.pref_meta = ints(4 * max_pref + 4);
   q.counts = ints(16);
   q.rowbuf = floats((size_t)max_rows * sh.D);

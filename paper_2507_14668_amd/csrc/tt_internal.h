@@ -19,6 +19,9 @@ struct TTShape {
   int P;    // d1*d2*R2   floats of a prefix product G1[i1] x G2[i2]
   int R2p;  // padded LDS row stride for [.][R2] tiles (odd, avoids bank conflicts)
   int sentinel;       // n1*n2*n3, sort key of an invalid lookup
+  // exact division of a non-negative int by n3 / n2 without a divide: q = (x * mul) >> (31 + sh)
+  // with mul = ceil(2^(31+sh) / n), sh = bit length of n - 1 (valid for every x < 2^31)
+  unsigned mul3, sh3, mul2, sh2;
   long long num_rows;
 };
 
@@ -41,6 +44,13 @@ struct TTShape {
 #define TT_SEG_UNROLL 8      // gathers a lane group keeps in flight
 
 static inline int tt_ceil_div(long long a, long long b) { return (int)((a + b - 1) / b); }
+
+static inline void tt_div_constants(int n, unsigned *mul, unsigned *sh) {
+  unsigned l = 0;
+  while ((1ll << l) < n) ++l;  // bit length of n - 1
+  *sh = l;
+  *mul = (unsigned)((((unsigned long long)1 << (31 + l)) + (unsigned long long)n - 1) / (unsigned long long)n);
+}
 
 // Sort scratch carved from plan->sort_tmp (all int32 arrays).
 struct TTSortTmp {
@@ -189,6 +199,9 @@ static inline tt_status tt_launch_status() {
 
 // ---- device helpers -----------------------------------------------------------------------
 #ifdef __HIPCC__
+__device__ __forceinline__ int tt_div(int x, unsigned mul, unsigned sh) {
+  return (int)(((unsigned long long)(unsigned)x * mul) >> (31 + sh));
+}
 __device__ __forceinline__ int tt_wave_incl_scan(int v) {
   const int lane = threadIdx.x & (TT_WAVE - 1);
 #pragma unroll
