@@ -27,7 +27,9 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg5", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
-    ap.add_argument("--arm", default="plan", choices=["plan", "naive"])
+    ap.add_argument("--arm", default="plan", choices=["plan", "naive", "sample"],
+                    help="plan: batch-level reuse; naive: no plan; sample: plan + sample-level reuse forward "
+                         "(forward-only workloads)")
     ap.add_argument("--no-overlap", action="store_true", help="reorder on the compute stream")
     ap.add_argument("--permute", action="store_true", help="seeded random row permutation of the Zipf ranks")
     ap.add_argument("--bijection", action="store_true",
@@ -53,7 +55,7 @@ def parse_args():
                     help="run only a plain device copy of known size (256 MiB read + 256 MiB written, five "
                          "times): the reference that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     ap.add_argument("--prof-kernel", default="auto",
-                    choices=["auto", "fwd_contract", "bwd_contract", "bag_sum", "grad_merge"],
+                    choices=["auto", "fwd_contract", "bwd_contract", "bag_sum", "grad_merge", "p12_fill", "bag_chains"],
                     help="kernel bracketed with HIP events for the roofline (auto = the dominant one)")
     return ap.parse_args()
 
@@ -99,17 +101,32 @@ def measure(args, workload, arm, steps, warmup, batches, prof_kernels, streams):
             batches.append(dict(idx=torch.from_numpy(idx).cuda(), off=torch.from_numpy(off).cuda(),
                                 grad=torch.from_numpy(grad).cuda(), nnz=len(idx),
                                 # workload statistics used only to count algorithmic work
-                                u_r=int(np.unique(seen).size), u_p=int(np.unique(seen // shape.n[2]).size)))
+                                u_r=int(np.unique(seen).size), u_p=int(np.unique(seen // shape.n[2]).size),
+                                # (bag, prefix) groups: second-stage products of the sample-level route
+                                groups=int(np.unique(np.repeat(np.arange(len(off) - 1, dtype=np.int64), np.diff(off)) *
+                                                     (shape.n[0] * shape.n[1]) + seen // shape.n[2]).size)
+                                if arm == "sample" else None))
         max_nnz = max(x["nnz"] for x in batches)
-        ws = [tt.alloc_workspace(table, max_nnz, cfg.batch) for _ in range(2)] if arm == "plan" else None
-        tabs.append(dict(shape=shape, table=table, batches=batches, ws=ws, plans=[None, None],
+        ws = [tt.alloc_workspace(table, max_nnz, cfg.batch) for _ in range(2)] if arm != "naive" else None
+        reuse = (torch.empty(tt.tt_reuse_buffer_bytes(table, max_nnz), dtype=torch.uint8, device="cuda")
+                 if arm == "sample" else None)
+        tabs.append(dict(shape=shape, table=table, batches=batches, ws=ws, plans=[None, None], reuse=reuse,
                          remap=None if remap is None else torch.from_numpy(remap).cuda(),
                          out=torch.empty((cfg.batch, shape.dim), dtype=torch.float32, device="cuda"),
                          dcores=table.core_grads_like()))
     torch.cuda.synchronize()
     t_gen = time.time() - t_gen
 
-    planned = arm == "plan"
+    planned = arm != "naive"
+    if arm == "sample":
+        assert not do_bwd, "the sample-level route is a forward: use a forward-only workload (cfg3)"
+
+    def forward(T, plan, x, stream):
+        if arm == "sample":
+            tt.tt_emb_bag_forward_sample(T["table"], plan, x["off"], reuse_buffer=T["reuse"], out=T["out"], stream=stream)
+        else:
+            tt.tt_emb_bag_forward(T["table"], plan, x["idx"], x["off"], out=T["out"], stream=stream)
+
     prof_kernels = [("bwd_contract" if do_bwd else "fwd_contract") if k == "auto" else k for k in prof_kernels]
     if not planned:
         prof_kernels = []
@@ -155,7 +172,7 @@ def measure(args, workload, arm, steps, warmup, batches, prof_kernels, streams):
                     x = T["batches"][b % nbatch]
                     plan = T["plans"][buf] if planned else None
                     if do_fwd:
-                        tt.tt_emb_bag_forward(T["table"], plan, x["idx"], x["off"], out=T["out"], stream=cs[k])
+                        forward(T, plan, x, cs[k])
                     if do_bwd and planned and not args.separate_update:
                         tt.tt_emb_bag_backward_sgd(T["table"], plan, x["idx"], x["off"], x["grad"], cfg.lr,
                                                    stream=cs[k])
@@ -194,7 +211,7 @@ def measure(args, workload, arm, steps, warmup, batches, prof_kernels, streams):
                 x = T["batches"][b % nbatch]
                 plan = T["plans"][buf] if planned else None
                 if do_fwd:
-                    tt.tt_emb_bag_forward(T["table"], plan, x["idx"], x["off"], out=T["out"], stream=cs[k])
+                    forward(T, plan, x, cs[k])
                 if do_bwd and planned and not args.separate_update:
                     tt.tt_emb_bag_backward_sgd(T["table"], plan, x["idx"], x["off"], x["grad"], cfg.lr, stream=cs[k])
                 elif do_bwd:
@@ -355,6 +372,9 @@ def measure(args, workload, arm, steps, warmup, batches, prof_kernels, streams):
         t_flop, t_hbm = flops / steps / (PEAK_FP32_TFLOPS * 1e12), bytes_ / steps / (PEAK_HBM_GBS * 1e9)
         result["config"]["step_bound_ms"] = {"fp32_mfma": round(1e3 * t_flop, 4), "hbm": round(1e3 * t_hbm, 4),
                                              "frac_of_measured": round(max(t_flop, t_hbm) / (dt / steps), 4)}
+    if arm == "sample":
+        result["config"]["bag_prefix_groups_batch0"] = int(sum(T["batches"][0]["groups"] for T in tabs))
+        result["config"]["lookups_batch0"] = int(sum(T["batches"][0]["nnz"] for T in tabs))
     if counts:
         result["config"]["distinct_rows_last_batch"] = int(sum(c[0] for c in counts))
         result["config"]["distinct_prefixes_last_batch"] = int(sum(c[1] for c in counts))
@@ -401,11 +421,15 @@ def main():
         # naive arms take tens to hundreds of milliseconds per step)
         other = {}
         for wk, arm_, st_, kern in (("cfg3", "plan", 10, ["fwd_contract", "bag_sum"]), ("cfg3", "naive", 3, []),
+                                    ("cfg3", "sample", 10, ["bag_chains", "p12_fill"]),
                                     ("cfg4", "plan", 10, ["bwd_contract", "grad_merge", "fwd_contract", "bag_sum"]),
                                     ("cfg4", "naive", 2, [])):
-            r = measure(args, wk, arm_, st_, 2 if arm_ == "plan" else 1, 2, kern, args.streams)
+            r = measure(args, wk, arm_, st_, 2 if arm_ != "naive" else 1, 2, kern, args.streams)
             entry = {"ms_per_step": r["ms_per_step"], "lookups_per_s": r["value"], "steps": st_,
                      "workload": r["config"]["workload"]}
+            for key in ("bag_prefix_groups_batch0", "lookups_batch0", "distinct_rows_last_batch", "distinct_prefixes_last_batch"):
+                if key in r["config"]:
+                    entry[key] = r["config"][key]
             if "step_bound_ms" in r["config"]:
                 entry["step_bound_ms"] = r["config"]["step_bound_ms"]
             if r.get("kernel_rooflines"):
@@ -428,6 +452,8 @@ KERNEL_BOUND = {
     "bwd_contract": ("mfma", "TFLOP/s", PEAK_FP32_TFLOPS, 1e12),
     "bag_sum": ("hbm", "GB/s", PEAK_HBM_GBS, 1e9),
     "grad_merge": ("hbm", "GB/s", PEAK_HBM_GBS, 1e9),
+    "p12_fill": ("mfma", "TFLOP/s", PEAK_FP32_TFLOPS, 1e12),
+    "bag_chains": ("hbm", "GB/s", PEAK_HBM_GBS, 1e9),
 }
 
 
@@ -452,6 +478,10 @@ def kernel_work(kernel, shape, batch, num_bags):
         return 4.0 * u_r * dim + 4.0 * num_bags * dim + 4.0 * nnz + 8.0 * (num_bags + 1)
     if kernel == "grad_merge":
         return 4.0 * num_bags * dim + 4.0 * u_r * dim + 8.0 * nnz
+    if kernel == "p12_fill":
+        return u_p * f12
+    if kernel == "bag_chains":  # every prefix product once, every output row once, two index reads per lookup
+        return 4.0 * u_p * d1 * d2 * r2 + 4.0 * num_bags * dim + 8.0 * nnz + 8.0 * (num_bags + 1)
     raise ValueError(kernel)
 
 

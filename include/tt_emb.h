@@ -211,6 +211,27 @@ tt_status tt_emb_bag_backward_sgd(const tt_table *table, const tt_plan *plan, co
                                   const float *grad_out, float lr, void *stream);
 
 /*
+ * Forward by sample-level reuse (Section III-B, reuse equation) on top of the reuse buffer of
+ * Section III-C: first the product G1[i1] x G2[i2] of every distinct prefix of the batch is written
+ * to `reuse_buffer` (the paper's Reuse Buffer, [prefix slot][(j1,j2)][r2] fp32); then each bag
+ * groups its lookups by prefix, sums the core-2 slices G3[:, i3, :] of a group and multiplies the
+ * group's buffered product by that sum ONCE -- one second-stage multiplication per (bag, prefix)
+ * group instead of one per lookup -- adding the results into the bag's output row.  Same result
+ * as tt_emb_bag_forward up to the order of the fp32 additions; bitwise reproducible.
+ * It pays when bags are long and their lookups share prefixes; with few lookups per bag the
+ * batch-level route of tt_emb_bag_forward (each distinct row once, then a gather) moves less data.
+ *   plan          required (built by tt_index_reorder for this batch)
+ *   reuse_buffer  DEVICE, 256-byte aligned, at least tt_reuse_buffer_bytes(table, nnz) bytes,
+ *                 borrowed until the enqueued work has finished; contents are transient.
+ *   out           DEVICE float[num_bags][D], overwritten.
+ * tt_reuse_buffer_bytes returns 0 on invalid arguments.
+ */
+size_t tt_reuse_buffer_bytes(const tt_table *table, int64_t nnz);
+tt_status tt_emb_bag_forward_sample(const tt_table *table, const tt_plan *plan, const int64_t *offsets,
+                                    int64_t nnz, int64_t num_bags, void *reuse_buffer,
+                                    size_t reuse_buffer_bytes, float *out, void *stream);
+
+/*
  * Forward for callers that cannot allocate device memory or hand over a workspace: code under HIP
  * graph capture, tight serving loops, harnesses that forbid hipMalloc.  One call = index reorder +
  * planned forward (the result is bitwise that of tt_index_reorder followed by tt_emb_bag_forward
@@ -297,7 +318,9 @@ typedef enum {
   TT_KERNEL_BWD_CONTRACT = 3, /* per-prefix backward contractions                            */
   TT_KERNEL_SORT_SCATTER = 4, /* one radix-sort scatter pass of the main lookup sort         */
   TT_KERNEL_SGD = 5,          /* core update                                                 */
-  TT_KERNEL_COUNT = 6
+  TT_KERNEL_P12_FILL = 6,     /* reuse buffer of the sample-level forward                    */
+  TT_KERNEL_BAG_CHAINS = 7,   /* per-bag chains of the sample-level forward                  */
+  TT_KERNEL_COUNT = 8
 } tt_kernel;
 
 typedef struct tt_prof tt_prof;

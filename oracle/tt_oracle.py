@@ -170,3 +170,41 @@ def reorder_plan(shape, indices, offsets, remap=None) -> dict:
                 uniq_row=uniq_row, row_seg=row_seg, lookup2row=lookup2row,
                 uniq_pref=uniq_pref, pref_seg=pref_seg, row2pref=row2pref,
                 num_valid=int(sorted_row.size), any_invalid=bool((~valid).any()))
+
+
+def forward_sample_reuse(shape, cores, indices, offsets):
+    """Bag sums by the sample-level reuse equation of Section III-B, float64[B][D], and the number
+    of (bag, prefix) groups it formed.
+
+    Inside one bag, the lookups whose rows share the first two TT indices (i1, i2) are served
+    by ONE product chain: the shared slices G1[i1] and G2[i2] are multiplied once, and the
+    third factor is the SUM of the core-3 slices of those lookups,
+        sum_l G1[i1] G2[i2] G3[i3_l]  =  G1[i1] G2[i2] (sum_l G3[i3_l]).
+    It is the same bag sum as `forward` in another association order; everything is float64
+    here, so the two agree to rounding.  Invalid indices contribute nothing.
+    """
+    n1, n2, n3 = shape.n
+    d1, d2, d3 = shape.d
+    _, r1, r2, _ = shape.r
+    g1 = np.asarray(cores[0], dtype=np.float64).reshape(n1, d1, r1)
+    g2 = np.asarray(cores[1], dtype=np.float64).reshape(r1, n2, d2, r2)
+    g3 = np.asarray(cores[2], dtype=np.float64).reshape(r2, n3, d3)
+    idx, off = _i64(indices), _i64(offsets)
+    nb = off.size - 1
+    out = np.zeros((nb, d1 * d2 * d3), dtype=np.float64)
+    groups = 0
+    for b in range(nb):
+        slice_sum = {}  # (i1, i2) -> sum of the core-3 slices of the bag's lookups with that prefix
+        for i in idx[off[b]:off[b + 1]]:
+            if i < 0 or i >= shape.num_rows:
+                continue
+            i3 = int(i % n3)
+            i2 = int((i // n3) % n2)
+            i1 = int(i // (n2 * n3))
+            s = slice_sum.get((i1, i2))
+            slice_sum[(i1, i2)] = g3[:, i3, :].copy() if s is None else s + g3[:, i3, :]
+        for (i1, i2), s3 in slice_sum.items():
+            p12 = np.einsum("ja,akc->jkc", g1[i1], g2[:, i2])          # [d1][d2][r2]
+            out[b] += np.einsum("jkc,cm->jkm", p12, s3).reshape(-1)    # [d1][d2][d3]
+        groups += len(slice_sum)
+    return out, groups

@@ -24,10 +24,11 @@ TT_ERR_HIP = -5
 TT_ERR_UNAVAILABLE = -6
 
 EXPORTS = ("tt_workspace_bytes", "tt_index_reorder", "tt_emb_bag_forward", "tt_emb_bag_backward",
-           "tt_core_sgd_update", "tt_emb_bag_backward_sgd", "tt_emb_bag_forward_static", "tt_plan_status", "tt_strerror", "tt_prof_create", "tt_prof_destroy",
+           "tt_core_sgd_update", "tt_emb_bag_backward_sgd", "tt_emb_bag_forward_static", "tt_reuse_buffer_bytes", "tt_emb_bag_forward_sample", "tt_plan_status", "tt_strerror", "tt_prof_create", "tt_prof_destroy",
            "tt_prof_collect", "tt_kernel_name", "tt_batch_desc_bytes", "tt_index_reorder_batched",
            "tt_emb_bag_forward_batched", "tt_emb_bag_backward_batched", "tt_core_sgd_update_batched")
-KERNELS = {"fwd_contract": 0, "bag_sum": 1, "grad_merge": 2, "bwd_contract": 3, "sort_scatter": 4, "sgd": 5}
+KERNELS = {"fwd_contract": 0, "bag_sum": 1, "grad_merge": 2, "bwd_contract": 3, "sort_scatter": 4, "sgd": 5,
+           "p12_fill": 6, "bag_chains": 7}
 
 
 class TTError(RuntimeError):
@@ -92,6 +93,10 @@ def load_library():
         lib.tt_emb_bag_backward_sgd.argtypes = [vp, vp, vp, vp, i64, i64, vp, f32, vp]
         lib.tt_emb_bag_forward_static.restype = ctypes.c_int
         lib.tt_emb_bag_forward_static.argtypes = [vp, vp, vp, i64, i64, vp, vp]
+        lib.tt_reuse_buffer_bytes.restype = ctypes.c_size_t
+        lib.tt_reuse_buffer_bytes.argtypes = [vp, i64]
+        lib.tt_emb_bag_forward_sample.restype = ctypes.c_int
+        lib.tt_emb_bag_forward_sample.argtypes = [vp, vp, vp, i64, i64, vp, ctypes.c_size_t, vp, vp]
         lib.tt_plan_status.restype = ctypes.c_int
         lib.tt_plan_status.argtypes = [vp, vp, vp]
         lib.tt_prof_create.restype = vp
@@ -267,6 +272,25 @@ def tt_emb_bag_forward(table: Table, plan, indices, offsets, out=None, stream=No
     st = load_library().tt_emb_bag_forward(ctypes.byref(table.c), ctypes.byref(plan.c) if plan else None,
                                            _ptr(indices), _ptr(offsets), nnz, nb, _ptr(out), _stream(stream))
     _check(st, "tt_emb_bag_forward")
+    return out
+
+
+def tt_reuse_buffer_bytes(table: Table, nnz: int) -> int:
+    return int(load_library().tt_reuse_buffer_bytes(ctypes.byref(table.c), int(nnz)))
+
+
+def tt_emb_bag_forward_sample(table: Table, plan, offsets, reuse_buffer=None, out=None, stream=None):
+    """Forward by sample-level reuse: reuse buffer of prefix products, then one chain per (bag, prefix)."""
+    offsets = _dev_i64(offsets, "offsets")
+    nnz, nb = int(plan.c.nnz), offsets.numel() - 1
+    if reuse_buffer is None:
+        reuse_buffer = torch.empty(tt_reuse_buffer_bytes(table, nnz), dtype=torch.uint8, device=offsets.device)
+    if out is None:
+        out = torch.empty((nb, table.dim), dtype=torch.float32, device=offsets.device)
+    _dev_f32(out, "out")
+    st = load_library().tt_emb_bag_forward_sample(ctypes.byref(table.c), ctypes.byref(plan.c), _ptr(offsets), nnz, nb,
+                                                  _ptr(reuse_buffer), reuse_buffer.numel(), _ptr(out), _stream(stream))
+    _check(st, "tt_emb_bag_forward_sample")
     return out
 
 

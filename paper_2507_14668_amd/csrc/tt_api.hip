@@ -352,6 +352,32 @@ tt_status tt_core_sgd_update(const tt_table *table, const tt_plan *plan,
   return run_single(OP_SGD, &it, lr, (hipStream_t)stream);
 }
 
+size_t tt_reuse_buffer_bytes(const tt_table *table, int64_t nnz) {
+  TTShape sh;
+  if (!derive_shape(table, &sh) || nnz < 0 || nnz >= 2147483647LL) return 0;
+  const long long pref_cap = (long long)sh.n1 * sh.n2;
+  const long long max_pref = nnz < pref_cap ? nnz : pref_cap;
+  return (((size_t)(max_pref > 0 ? max_pref : 1) * sh.P * sizeof(float)) + 255) & ~(size_t)255;
+}
+
+tt_status tt_emb_bag_forward_sample(const tt_table *table, const tt_plan *plan, const int64_t *offsets,
+                                    int64_t nnz, int64_t num_bags, void *reuse_buffer,
+                                    size_t reuse_buffer_bytes, float *out, void *stream) {
+  if (!plan || !reuse_buffer) return TT_ERR_INVALID_ARG;
+  tt_batch_item it;
+  memset(&it, 0, sizeof(it));
+  it.table = table; it.plan = const_cast<tt_plan *>(plan); it.offsets = offsets;
+  it.nnz = nnz; it.num_bags = num_bags; it.out = out;
+  TTDev d;
+  tt_status st = prepare_item(OP_FORWARD, &it, 0.f, &d);
+  if (st != TT_OK) return st;
+  const size_t need = tt_reuse_buffer_bytes(table, nnz);
+  if (((uintptr_t)reuse_buffer & 255) != 0 || need == 0 || reuse_buffer_bytes < need) return TT_ERR_WORKSPACE;
+  d.p12buf = (float *)reuse_buffer;
+  const TTBatch b = {1, &d, nullptr};
+  return ttk_forward_sample(b, (hipStream_t)stream);
+}
+
 tt_status tt_emb_bag_forward_static(const tt_table *table, const int64_t *indices, const int64_t *offsets,
                                     int64_t nnz, int64_t num_bags, float *out, void *stream) {
   if (!table || !offsets || (nnz > 0 && !indices) || (num_bags > 0 && !out)) return TT_ERR_INVALID_ARG;
@@ -461,6 +487,8 @@ const char *tt_kernel_name(int kernel) {
     case TT_KERNEL_BWD_CONTRACT: return "bwd_contract";
     case TT_KERNEL_SORT_SCATTER: return "sort_scatter";
     case TT_KERNEL_SGD: return "sgd";
+    case TT_KERNEL_P12_FILL: return "p12_fill";
+    case TT_KERNEL_BAG_CHAINS: return "bag_chains";
   }
   return "unknown";
 }

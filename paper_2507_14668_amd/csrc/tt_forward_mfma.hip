@@ -57,7 +57,9 @@ struct FwdGeom {
   static_assert(256 % R2 == 0 && D2 % JW == 0 && R1 % 16 == 0 && CC % 16 == 0 && TT_MP == 8, "unsupported shape");
 };
 
-template <bool BATCHED, int R1, int R2, int D2>
+// P12OUT: the kernel stops after F1 and stores the prefix products to the reuse buffer
+// [prefix slot][(j1,j2)][r2] instead of running F2 (first stage of the sample-level forward).
+template <bool BATCHED, int R1, int R2, int D2, bool P12OUT>
 __global__ void __launch_bounds__(FTHR, 4)  // four wavefronts per SIMD: two workgroups per compute unit
 k_fwd_mfma(TTArg<BATCHED> a, int split) {
   const TTDev &d = a.get();
@@ -65,12 +67,12 @@ k_fwd_mfma(TTArg<BATCHED> a, int split) {
   const float *__restrict__ g1 = d.g[0], *__restrict__ g2 = d.g[1], *__restrict__ g3 = d.g[2];
   const int32_t *__restrict__ uniq_row = d.plan.uniq_row, *__restrict__ i2_seg = d.plan.i2_seg;
   const int4 *__restrict__ pref_meta = reinterpret_cast<const int4 *>(d.plan.pref_meta);
-  float *__restrict__ rowbuf = d.plan.rowbuf;
+  float *__restrict__ rowbuf = d.plan.rowbuf, *__restrict__ p12buf = d.p12buf;
   using G = FwdGeom<R1, R2, D2>;
   extern __shared__ float lds[];
   float *As = lds;                  // [32][RS]  core-0 slices of the chunk
   float *P12s = lds + G::OFF_P12;   // [8][PS]   prefix products of the chunk
-  __shared__ int s_i1[FMETA], s_u0[FMETA], s_nr[FMETA];
+  __shared__ int s_i1[FMETA], s_u0[FMETA], s_nr[FMETA], s_slot[FMETA];
   __shared__ int s_item_off[2][TT_MP + 1];
   __shared__ int s_i3[2][TT_MP][FWD_I3_STAGE];
 
@@ -110,12 +112,12 @@ k_fwd_mfma(TTArg<BATCHED> a, int split) {
   int rown = 0;
   auto fetch_meta = [&](int base) __attribute__((always_inline)) {  // plan entries of prefixes base .. base+63 -> LDS
     if (threadIdx.x < FMETA) {
-      int i1 = -1, u0 = 0, nr = 0;
+      int i1 = -1, u0 = 0, nr = 0, slot = 0;
       if (base + (int)threadIdx.x < seg1) {
         const int4 m = pref_meta[base + threadIdx.x];  // i1, first row slot, rows, prefix slot
-        i1 = m.x; u0 = m.y; nr = m.z;
+        i1 = m.x; u0 = m.y; nr = m.z; slot = m.w;
       }
-      s_i1[threadIdx.x] = i1; s_u0[threadIdx.x] = u0; s_nr[threadIdx.x] = nr;
+      s_i1[threadIdx.x] = i1; s_u0[threadIdx.x] = u0; s_nr[threadIdx.x] = nr; s_slot[threadIdx.x] = slot;
     }
   };
   auto fetch_chunk = [&](int mo) __attribute__((always_inline)) {  // mo = offset of the chunk inside the staged plan entries
@@ -196,8 +198,19 @@ k_fwd_mfma(TTArg<BATCHED> a, int split) {
     __syncthreads();  // P12 of the chunk is complete; the core-0 tile is free
     if (more && !refill) stage_chunk(par ^ 1, mo + TT_MP);
 
+    if constexpr (P12OUT) {  // the chunk's products -> reuse buffer, as float4 along r2
+      constexpr int Q4 = G::CC * R2 / 4;  // float4 per prefix and strip
+      for (int e = threadIdx.x; e < TT_MP * Q4; e += FTHR) {
+        const int p = e / Q4, rem = e - p * Q4, cc = rem / (R2 / 4), r4 = rem - cc * (R2 / 4);
+        if (s_i1[mo + p] < 0) continue;
+        const int j1 = cc / G::JW, j2 = j2base + (cc - j1 * G::JW);
+        const float *src = P12s + p * G::PS + cc * G::Rp + 4 * r4;
+        *reinterpret_cast<float4 *>(p12buf + (size_t)s_slot[mo + p] * (4 * D2 * R2) + (j1 * D2 + j2) * R2 + 4 * r4) =
+            make_float4(src[0], src[1], src[2], src[3]);
+      }
+    }
     // ---- F2: items = (prefix, four distinct rows), dealt round-robin to the wavefronts -------
-    const int total = s_item_off[par][TT_MP];
+    const int total = P12OUT ? 0 : s_item_off[par][TT_MP];
     struct Item { int p, ubase, nrow; float a[G::KS2]; };
     auto fetch = [&](int it, Item &x) __attribute__((always_inline)) {
       int p = 0;
@@ -255,7 +268,7 @@ k_fwd_mfma(TTArg<BATCHED> a, int split) {
   }
 }
 
-template <int R1, int R2, int D2>
+template <int R1, int R2, int D2, bool P12OUT>
 tt_status launch(const TTBatch &b, hipStream_t s) {
   using G = FwdGeom<R1, R2, D2>;
   const size_t lds = G::LDS_FLOATS * sizeof(float);
@@ -263,9 +276,9 @@ tt_status launch(const TTBatch &b, hipStream_t s) {
   static std::once_flag once;
   static bool configured = false;
   std::call_once(once, [&] {
-    configured = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fwd_mfma<false, R1, R2, D2>),
+    configured = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fwd_mfma<false, R1, R2, D2, P12OUT>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess &&
-                 hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fwd_mfma<true, R1, R2, D2>),
+                 hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fwd_mfma<true, R1, R2, D2, P12OUT>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess;
   });
   if (!configured) return TT_ERR_HIP;
@@ -275,12 +288,12 @@ tt_status launch(const TTBatch &b, hipStream_t s) {
   int split = (int)(TT_FWD_WG_TARGET / (n2p8 * G::NSTRIP));
   split = split < 1 ? 1 : (split > TT_FWD_MAX_SPLIT ? TT_FWD_MAX_SPLIT : split);
   const long long blocks = n2p8 * G::NSTRIP * split;
-  TTProfScope prof(&b.host[0].plan, TT_KERNEL_FWD_CONTRACT, s);
+  TTProfScope prof(&b.host[0].plan, P12OUT ? TT_KERNEL_P12_FILL : TT_KERNEL_FWD_CONTRACT, s);
   if (b.dev)
-    hipLaunchKernelGGL((k_fwd_mfma<true, R1, R2, D2>), dim3((unsigned)blocks, (unsigned)b.T),
+    hipLaunchKernelGGL((k_fwd_mfma<true, R1, R2, D2, P12OUT>), dim3((unsigned)blocks, (unsigned)b.T),
                        dim3(FTHR), lds, s, TTArg<true>{b.dev}, split);
   else
-    hipLaunchKernelGGL((k_fwd_mfma<false, R1, R2, D2>), dim3((unsigned)blocks), dim3(FTHR), lds, s,
+    hipLaunchKernelGGL((k_fwd_mfma<false, R1, R2, D2, P12OUT>), dim3((unsigned)blocks), dim3(FTHR), lds, s,
                        TTArg<false>{b.host[0]}, split);
   return tt_launch_status();
 }
@@ -293,6 +306,11 @@ bool ttk_forward_mfma_supported(const TTShape &sh) {
 }
 
 tt_status ttk_forward_mfma(const TTBatch &b, hipStream_t s) {
-  if (b.host[0].sh.R1 == 32) return launch<32, 32, 8>(b, s);
-  return launch<64, 64, 8>(b, s);
+  if (b.host[0].sh.R1 == 32) return launch<32, 32, 8, false>(b, s);
+  return launch<64, 64, 8, false>(b, s);
+}
+
+tt_status ttk_forward_mfma_p12(const TTBatch &b, hipStream_t s) {
+  if (b.host[0].sh.R1 == 32) return launch<32, 32, 8, true>(b, s);
+  return launch<64, 64, 8, true>(b, s);
 }

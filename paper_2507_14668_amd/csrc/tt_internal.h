@@ -77,6 +77,7 @@ struct TTDev {
   const int64_t *indices, *offsets, *remap;
   const float *grad_out;
   float *out;
+  float *p12buf;           // reuse buffer [prefix slot][(j1,j2)][r2] of the sample-level forward
   int nnz, num_bags;
   int sort_tiles;          // radix tiles of the main lookup sort (hist row length)
   int strips;              // contributions per prefix in t1buf: one per strip of the core-1 slice (matrix-core path), else 1
@@ -153,6 +154,10 @@ static inline bool ttk_batch_mfma(const TTBatch &b) {
     if (!b.host[t].mfma) return false;
   return true;
 }
+// sample-level reuse forward: reuse buffer of prefix products, then one chain per (bag, prefix) group
+tt_status ttk_forward_sample(const TTBatch &b, hipStream_t s);
+// the matrix-core forward kernel with its second stage replaced by a store of the prefix products
+tt_status ttk_forward_mfma_p12(const TTBatch &b, hipStream_t s);
 tt_status ttk_forward_naive(const TTBatch &b, hipStream_t s);
 tt_status ttk_backward_plan(const TTBatch &b, hipStream_t s);
 tt_status ttk_backward_naive(const TTBatch &b, hipStream_t s);
@@ -201,6 +206,13 @@ static inline tt_status tt_launch_status() {
 #ifdef __HIPCC__
 __device__ __forceinline__ int tt_div(int x, unsigned mul, unsigned sh) {
   return (int)(((unsigned long long)(unsigned)x * mul) >> (31 + sh));
+}
+// Orders the LDS accesses of the lanes of one wavefront (a wavefront executes them in program
+// order; this keeps the compiler from moving them across).
+__device__ __forceinline__ void tt_wave_lds_order() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 __device__ __forceinline__ int tt_wave_incl_scan(int v) {
   const int lane = threadIdx.x & (TT_WAVE - 1);

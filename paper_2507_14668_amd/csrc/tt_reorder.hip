@@ -195,14 +195,6 @@ k_radix_binscan(TTArg<BATCHED> a, int which, int nbins, int pass) {
   if (threadIdx.x == 0) bin_total[blockIdx.x] = carry;
 }
 
-// Orders the LDS accesses of the lanes of one wavefront (a wavefront executes them in program
-// order; this keeps the compiler from moving them across).
-__device__ __forceinline__ void tt_wave_lds_order() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
 // Stable scatter.  Wavefront w of a tile owns its keys [w*256, w*256 + 256) and ranks them in four
 // rounds of 64 (position order), keeping per-digit running counts in its own row of wave_cnt; one
 // scan over the four rows per digit then gives every wavefront its base inside the tile's run of

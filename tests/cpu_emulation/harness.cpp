@@ -112,6 +112,18 @@ int main(int argc, char **argv) {
       Res &R = single[t];
       R.out.assign((size_t)B.bags * B.D, -7.f);
       CK(tt_emb_bag_forward(&B.t, planned ? &plan : nullptr, B.idx.data(), B.off.data(), B.nnz, B.bags, R.out.data(), nullptr));
+      if (planned) {  // sample-level forward: same bag sums in another order of additions
+        const size_t rb = tt_reuse_buffer_bytes(&B.t, B.nnz);
+        void *reuse = amalloc(rb);
+        std::vector<float> out2((size_t)B.bags * B.D, -7.f);
+        CK(tt_emb_bag_forward_sample(&B.t, &plan, B.off.data(), B.nnz, B.bags, reuse, rb, out2.data(), nullptr));
+        for (size_t i = 0; i < out2.size(); ++i)
+          if (!(fabs((double)out2[i] - R.out[i]) <= 1e-4 * (1.0 + fabs((double)R.out[i])))) {
+            fprintf(stderr, "FAIL sample-level forward differs (table %d element %zu: %g vs %g)\n", t, i, out2[i], R.out[i]);
+            return 4;
+          }
+        free(reuse);
+      }
       float *dc[3];
       for (int k = 0; k < 3; ++k) { R.dg[k].assign(B.core[k].size() + 1, -9.f); dc[k] = R.dg[k].data() + g_off; }
       CK(tt_emb_bag_backward(&B.t, planned ? &plan : nullptr, B.idx.data(), B.off.data(), B.nnz, B.bags, B.grad.data(), dc, nullptr));

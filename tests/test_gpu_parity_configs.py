@@ -84,6 +84,8 @@ def full_table_check(g, ora, cfg, tab, what, permute=None, naive=False):
     g.assert_plan_equals_oracle(ora, shape, plan, idx, off)
     ref_out = ora.forward(shape, cores, idx, off, dedup=True)
     g.assert_close_rows(out.cpu().numpy(), ref_out, g.FWD_RTOL, shape.dim, "forward")
+    out_s = tt.tt_emb_bag_forward_sample(table, plan, g.to_dev(off, torch.int64))
+    g.assert_close_rows(out_s.cpu().numpy(), ref_out, g.FWD_RTOL, shape.dim, "forward sample-level")
     ref_dg = ora.backward(shape, cores, idx, off, grad, dedup=True, max_threads_=8)
     g.assert_grads_close(shape, dg, ref_dg, what="dG")
     euler_check(shape, cores, out, dg, grad)

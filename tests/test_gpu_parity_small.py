@@ -30,6 +30,10 @@ def run_all(g, ora, shape, cores, idx, off, grad, lr=0.01, check_plan=True, rema
     if remap is None:
         out_naive = tt.tt_emb_bag_forward(table, None, d_idx, d_off)
         g.assert_close_rows(out_naive.cpu().numpy(), ref_out, g.FWD_RTOL, shape.dim, "forward(naive)")
+    # sample-level reuse route (Section III-B reuse equation): same bag sums, bitwise reproducible
+    out_sample = tt.tt_emb_bag_forward_sample(table, plan, d_off)
+    g.assert_close_rows(out_sample.cpu().numpy(), ref_out, g.FWD_RTOL, shape.dim, "forward(sample)")
+    assert torch.equal(tt.tt_emb_bag_forward_sample(table, plan, d_off), out_sample)
     ref_dg = ora.backward(shape, cores, np.where(o_idx < 0, shape.num_rows, o_idx) if remap is not None else idx, off, grad)
     dg_plan = tt.tt_emb_bag_backward(table, plan, d_idx, d_off, d_grad)
     g.assert_grads_close(shape, dg_plan, ref_dg, what="dG(plan)")

@@ -135,6 +135,28 @@ def test_prefix_reuse_identity_on_the_papers_two_index_bag(ora):
     np.testing.assert_allclose(out[0], reuse, rtol=2e-6, atol=1e-7)
 
 
+def test_sample_reuse_route_equals_dense_table_and_counts_groups(ora):
+    """The sample-level evaluation order (one chain per (bag, prefix), core-3 slices summed first)
+    against the library embedding_bag on the dense table, and its group count against a brute-force
+    count of distinct (bag, row div n3) pairs.  Bags here hold several rows of one prefix, repeated
+    rows, an empty bag and an invalid index."""
+    shape, cores, idx, off, _ = wl.small_random_problem(14, n=(2, 3, 6), num_bags=30, max_len=9)
+    idx = idx.copy()
+    idx[3] = -1
+    assert (np.diff(off) == 0).any()
+    w = dense_table(shape, cores)
+    ref = np.zeros((len(off) - 1, shape.dim))
+    pairs = set()
+    for b in range(len(off) - 1):
+        for i in idx[off[b]:off[b + 1]]:
+            if 0 <= i < shape.num_rows:
+                ref[b] += w[i]
+                pairs.add((b, int(i) // shape.n[2]))
+    out, groups = ora.forward_sample_reuse(shape, cores, idx, off)
+    np.testing.assert_allclose(out, ref, rtol=1e-12, atol=1e-13)
+    assert groups == len(pairs) < int(((idx >= 0) & (idx < shape.num_rows)).sum()), "fixture must share prefixes inside bags"
+
+
 # ------------------------------------------------------------------- backward
 def dense_route_grads(shape, cores, idx, off, grad):
     """dL/dW by scatter-add, then contracted with the other two cores (library einsum)."""
