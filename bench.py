@@ -27,9 +27,9 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg5", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
-    ap.add_argument("--arm", default="plan", choices=["plan", "naive", "sample"],
-                    help="plan: batch-level reuse; naive: no plan; sample: plan + sample-level reuse forward "
-                         "(forward-only workloads)")
+    ap.add_argument("--arm", default="plan", choices=["plan", "naive", "sample", "bf16"],
+                    help="plan: batch-level reuse; naive: no plan; sample: plan + sample-level reuse forward; "
+                         "bf16: plan + forward on bf16 copies of the cores (both forward-only workloads)")
     ap.add_argument("--no-overlap", action="store_true", help="reorder on the compute stream")
     ap.add_argument("--permute", action="store_true", help="seeded random row permutation of the Zipf ranks")
     ap.add_argument("--bijection", action="store_true",
@@ -111,6 +111,7 @@ def measure(args, workload, arm, steps, warmup, batches, prof_kernels, streams):
         reuse = (torch.empty(tt.tt_reuse_buffer_bytes(table, max_nnz), dtype=torch.uint8, device="cuda")
                  if arm == "sample" else None)
         tabs.append(dict(shape=shape, table=table, batches=batches, ws=ws, plans=[None, None], reuse=reuse,
+                         bf16=tt.tt_cores_to_bf16(table) if arm == "bf16" else None,
                          remap=None if remap is None else torch.from_numpy(remap).cuda(),
                          out=torch.empty((cfg.batch, shape.dim), dtype=torch.float32, device="cuda"),
                          dcores=table.core_grads_like()))
@@ -118,12 +119,14 @@ def measure(args, workload, arm, steps, warmup, batches, prof_kernels, streams):
     t_gen = time.time() - t_gen
 
     planned = arm != "naive"
-    if arm == "sample":
-        assert not do_bwd, "the sample-level route is a forward: use a forward-only workload (cfg3)"
+    if arm in ("sample", "bf16"):
+        assert not do_bwd, "the %s arm is a forward: use a forward-only workload (cfg3)" % arm
 
     def forward(T, plan, x, stream):
         if arm == "sample":
             tt.tt_emb_bag_forward_sample(T["table"], plan, x["off"], reuse_buffer=T["reuse"], out=T["out"], stream=stream)
+        elif arm == "bf16":
+            tt.tt_emb_bag_forward_bf16(T["table"], T["bf16"], plan, x["off"], out=T["out"], stream=stream)
         else:
             tt.tt_emb_bag_forward(T["table"], plan, x["idx"], x["off"], out=T["out"], stream=stream)
 
@@ -422,6 +425,7 @@ def main():
         other = {}
         for wk, arm_, st_, kern in (("cfg3", "plan", 10, ["fwd_contract", "bag_sum"]), ("cfg3", "naive", 3, []),
                                     ("cfg3", "sample", 10, ["bag_chains", "p12_fill"]),
+                                    ("cfg3", "bf16", 10, ["fwd_contract"]),
                                     ("cfg4", "plan", 10, ["bwd_contract", "grad_merge", "fwd_contract", "bag_sum"]),
                                     ("cfg4", "naive", 2, [])):
             r = measure(args, wk, arm_, st_, 2 if arm_ != "naive" else 1, 2, kern, args.streams)

@@ -232,6 +232,27 @@ tt_status tt_emb_bag_forward_sample(const tt_table *table, const tt_plan *plan, 
                                     size_t reuse_buffer_bytes, float *out, void *stream);
 
 /*
+ * Reduced-precision cores (deployment discussion of the paper: devices with half-precision
+ * arithmetic): the three cores are STORED as bf16, all accumulation stays fp32.
+ * tt_cores_to_bf16 rounds table->core[0..2] (round to nearest, ties to even) into `bf16_cores`, a
+ * DEVICE buffer of tt_bf16_cores_bytes(table) bytes, 256-byte aligned, in a layout private to the
+ * library (core 1 is regrouped for the matrix-core kernel).  tt_emb_bag_forward_bf16 is the
+ * planned forward of tt_emb_bag_forward reading those copies: the prefix products run on the bf16
+ * matrix-core instruction (products of bf16 values are exact in fp32, sums are fp32), the products
+ * stay fp32 and the second stage is the fp32 kernel with core-2 values widened exactly.  The result
+ * therefore equals the fp32 forward of the ROUNDED cores to fp32 rounding (tolerance 1e-5 as for
+ * tt_emb_bag_forward), and differs from the forward of the unrounded cores by at most
+ * ((1 + 2^-9)^3 - 1) * sum over the TT paths of |G1 G2 G3|, about 0.6 % of that sum.
+ * Only tables the matrix-core kernels serve (d = (4, 8, 4), ranks (32, 32) or (64, 64)):
+ * TT_ERR_SHAPE otherwise (0 from the size query).  table->core[] are not read by the forward.
+ */
+size_t tt_bf16_cores_bytes(const tt_table *table);
+tt_status tt_cores_to_bf16(const tt_table *table, void *bf16_cores, size_t bf16_cores_bytes, void *stream);
+tt_status tt_emb_bag_forward_bf16(const tt_table *table, const void *bf16_cores, const tt_plan *plan,
+                                  const int64_t *offsets, int64_t nnz, int64_t num_bags, float *out,
+                                  void *stream);
+
+/*
  * Forward for callers that cannot allocate device memory or hand over a workspace: code under HIP
  * graph capture, tight serving loops, harnesses that forbid hipMalloc.  One call = index reorder +
  * planned forward (the result is bitwise that of tt_index_reorder followed by tt_emb_bag_forward

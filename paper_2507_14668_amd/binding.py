@@ -24,7 +24,8 @@ TT_ERR_HIP = -5
 TT_ERR_UNAVAILABLE = -6
 
 EXPORTS = ("tt_workspace_bytes", "tt_index_reorder", "tt_emb_bag_forward", "tt_emb_bag_backward",
-           "tt_core_sgd_update", "tt_emb_bag_backward_sgd", "tt_emb_bag_forward_static", "tt_reuse_buffer_bytes", "tt_emb_bag_forward_sample", "tt_plan_status", "tt_strerror", "tt_prof_create", "tt_prof_destroy",
+           "tt_core_sgd_update", "tt_emb_bag_backward_sgd", "tt_emb_bag_forward_static", "tt_reuse_buffer_bytes", "tt_emb_bag_forward_sample",
+           "tt_bf16_cores_bytes", "tt_cores_to_bf16", "tt_emb_bag_forward_bf16", "tt_plan_status", "tt_strerror", "tt_prof_create", "tt_prof_destroy",
            "tt_prof_collect", "tt_kernel_name", "tt_batch_desc_bytes", "tt_index_reorder_batched",
            "tt_emb_bag_forward_batched", "tt_emb_bag_backward_batched", "tt_core_sgd_update_batched")
 KERNELS = {"fwd_contract": 0, "bag_sum": 1, "grad_merge": 2, "bwd_contract": 3, "sort_scatter": 4, "sgd": 5,
@@ -97,6 +98,12 @@ def load_library():
         lib.tt_reuse_buffer_bytes.argtypes = [vp, i64]
         lib.tt_emb_bag_forward_sample.restype = ctypes.c_int
         lib.tt_emb_bag_forward_sample.argtypes = [vp, vp, vp, i64, i64, vp, ctypes.c_size_t, vp, vp]
+        lib.tt_bf16_cores_bytes.restype = ctypes.c_size_t
+        lib.tt_bf16_cores_bytes.argtypes = [vp]
+        lib.tt_cores_to_bf16.restype = ctypes.c_int
+        lib.tt_cores_to_bf16.argtypes = [vp, vp, ctypes.c_size_t, vp]
+        lib.tt_emb_bag_forward_bf16.restype = ctypes.c_int
+        lib.tt_emb_bag_forward_bf16.argtypes = [vp, vp, vp, vp, i64, i64, vp, vp]
         lib.tt_plan_status.restype = ctypes.c_int
         lib.tt_plan_status.argtypes = [vp, vp, vp]
         lib.tt_prof_create.restype = vp
@@ -291,6 +298,34 @@ def tt_emb_bag_forward_sample(table: Table, plan, offsets, reuse_buffer=None, ou
     st = load_library().tt_emb_bag_forward_sample(ctypes.byref(table.c), ctypes.byref(plan.c), _ptr(offsets), nnz, nb,
                                                   _ptr(reuse_buffer), reuse_buffer.numel(), _ptr(out), _stream(stream))
     _check(st, "tt_emb_bag_forward_sample")
+    return out
+
+
+def tt_bf16_cores_bytes(table: Table) -> int:
+    return int(load_library().tt_bf16_cores_bytes(ctypes.byref(table.c)))
+
+
+def tt_cores_to_bf16(table: Table, bf16_cores=None, stream=None):
+    """bf16 copies of the table's cores (library-private layout) in a uint8 device tensor."""
+    nbytes = tt_bf16_cores_bytes(table)
+    if nbytes == 0:
+        raise TTError(TT_ERR_SHAPE, "tt_bf16_cores_bytes")
+    if bf16_cores is None:
+        bf16_cores = torch.empty(nbytes, dtype=torch.uint8, device=table.cores[0].device)
+    st = load_library().tt_cores_to_bf16(ctypes.byref(table.c), _ptr(bf16_cores), bf16_cores.numel(), _stream(stream))
+    _check(st, "tt_cores_to_bf16")
+    return bf16_cores
+
+
+def tt_emb_bag_forward_bf16(table: Table, bf16_cores, plan, offsets, out=None, stream=None):
+    offsets = _dev_i64(offsets, "offsets")
+    nnz, nb = int(plan.c.nnz), offsets.numel() - 1
+    if out is None:
+        out = torch.empty((nb, table.dim), dtype=torch.float32, device=offsets.device)
+    _dev_f32(out, "out")
+    st = load_library().tt_emb_bag_forward_bf16(ctypes.byref(table.c), _ptr(bf16_cores), ctypes.byref(plan.c),
+                                                _ptr(offsets), nnz, nb, _ptr(out), _stream(stream))
+    _check(st, "tt_emb_bag_forward_bf16")
     return out
 
 

@@ -378,6 +378,45 @@ tt_status tt_emb_bag_forward_sample(const tt_table *table, const tt_plan *plan, 
   return ttk_forward_sample(b, (hipStream_t)stream);
 }
 
+size_t tt_bf16_cores_bytes(const tt_table *table) {
+  TTShape sh;
+  if (!derive_shape(table, &sh) || !ttk_forward_mfma_supported(sh)) return 0;
+  size_t off[3], total;
+  ttk_bf16_layout(sh, off, &total);
+  return total;
+}
+
+tt_status tt_cores_to_bf16(const tt_table *table, void *bf16_cores, size_t bf16_cores_bytes, void *stream) {
+  TTShape sh;
+  if (!table || !bf16_cores) return TT_ERR_INVALID_ARG;
+  if (!derive_shape(table, &sh) || !ttk_forward_mfma_supported(sh)) return TT_ERR_SHAPE;
+  if (!cores_present(table)) return TT_ERR_INVALID_ARG;
+  if (((uintptr_t)bf16_cores & 255) != 0 || bf16_cores_bytes < tt_bf16_cores_bytes(table)) return TT_ERR_WORKSPACE;
+  return ttk_cores_to_bf16(sh, table->core, bf16_cores, (hipStream_t)stream);
+}
+
+tt_status tt_emb_bag_forward_bf16(const tt_table *table, const void *bf16_cores, const tt_plan *plan,
+                                  const int64_t *offsets, int64_t nnz, int64_t num_bags, float *out,
+                                  void *stream) {
+  TTShape sh;
+  if (!table || !bf16_cores || !plan || !offsets || (num_bags > 0 && !out)) return TT_ERR_INVALID_ARG;
+  if (!derive_shape(table, &sh) || !ttk_forward_mfma_supported(sh)) return TT_ERR_SHAPE;
+  if (!batch_ok(nnz, num_bags) || !plan_matches(plan, table, nnz, num_bags)) return TT_ERR_INVALID_ARG;
+  if (((uintptr_t)bf16_cores & 255) != 0) return TT_ERR_WORKSPACE;
+  size_t off[3], total;
+  ttk_bf16_layout(sh, off, &total);
+  tt_table view = *table;  // the kernels' core pointers: the bf16 copies
+  for (int k = 0; k < 3; ++k) view.core[k] = (float *)((char *)const_cast<void *>(bf16_cores) + off[k]);
+  TTDev d;
+  fill_dev(&d, sh, &view, plan, nullptr, offsets, nnz, num_bags, nullptr, out, nullptr, nullptr, 0.f, false);
+  const TTBatch b = {1, &d, nullptr};
+  if (plan->max_prefixes > 0) {
+    tt_status st = ttk_forward_mfma_bf16(b, (hipStream_t)stream);
+    if (st != TT_OK) return st;
+  }
+  return ttk_bag_sum(b, (hipStream_t)stream);
+}
+
 tt_status tt_emb_bag_forward_static(const tt_table *table, const int64_t *indices, const int64_t *offsets,
                                     int64_t nnz, int64_t num_bags, float *out, void *stream) {
   if (!table || !offsets || (nnz > 0 && !indices) || (num_bags > 0 && !out)) return TT_ERR_INVALID_ARG;

@@ -216,7 +216,6 @@ size_t fwd_lds_bytes(const TTShape &sh, int rows_per_iter) {
 tt_status ttk_forward_plan(const TTBatch &b, hipStream_t s) {
   const TTShape &sh = b.host[0].sh;  // d[] and r[] are common to the batch
   const long long max_pref = tt_batch_max(b, [](const TTDev &d) { return (long long)d.plan.max_prefixes; });
-  const long long max_bags = tt_batch_max(b, [](const TTDev &d) { return (long long)d.num_bags; });
   if (max_pref > 0 && ttk_batch_mfma(b)) {
     tt_status st = ttk_forward_mfma(b, s);
     if (st != TT_OK) return st;
@@ -228,6 +227,12 @@ tt_status ttk_forward_plan(const TTBatch &b, hipStream_t s) {
     TTProfScope prof(&b.host[0].plan, TT_KERNEL_FWD_CONTRACT, s);
     TT_LAUNCH(k_fwd_prefix_rows, blocks, TT_BLOCK, fwd_lds_bytes(sh, rows_per_iter), s, b, rows_per_iter);
   }
+  return ttk_bag_sum(b, s);
+}
+
+tt_status ttk_bag_sum(const TTBatch &b, hipStream_t s) {
+  const TTShape &sh = b.host[0].sh;
+  const long long max_bags = tt_batch_max(b, [](const TTDev &d) { return (long long)d.num_bags; });
   if (max_bags > 0) {
     bool vec4 = (sh.D % 4) == 0;
     for (int t = 0; t < b.T; ++t) vec4 = vec4 && ((uintptr_t)b.host[t].out % 16) == 0;

@@ -28,6 +28,9 @@
 namespace {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef short bf16x4 __attribute__((ext_vector_type(4)));  // four bf16 values as the 16x16x16 MFMA takes them
+
+__device__ __forceinline__ float bf16_to_float(unsigned short v) { return __uint_as_float((unsigned)v << 16); }
 
 constexpr int FTHR = 512;   // threads per workgroup
 #ifndef TT_FWD_WG_TARGET
@@ -59,7 +62,13 @@ struct FwdGeom {
 
 // P12OUT: the kernel stops after F1 and stores the prefix products to the reuse buffer
 // [prefix slot][(j1,j2)][r2] instead of running F2 (first stage of the sample-level forward).
-template <bool BATCHED, int R1, int R2, int D2, bool P12OUT>
+// BF16: the cores are bf16 copies made by k_cores_to_bf16 (cores 0 and 2 in their own layout, core 1
+// as [i2][r1 / 4][(j2, r2)][r1 % 4] so that a lane's four consecutive r1 of one column are 8
+// contiguous bytes).  F1 runs on v_mfma_f32_16x16x16_bf16 (lane l supplies A[m = l%16][k = 4*(l/16) + i]
+// and B[k = 4*(l/16) + i][n = l%16], i = 0..3; C as for 16x16x4) with fp32 accumulators, the products
+// stay fp32 in LDS, and F2 is the fp32 MFMA with core-2 values widened exactly: the only difference
+// from the fp32 path is the rounding of the stored cores.
+template <bool BATCHED, int R1, int R2, int D2, bool P12OUT, bool BF16>
 __global__ void __launch_bounds__(FTHR, 4)  // four wavefronts per SIMD: two workgroups per compute unit
 k_fwd_mfma(TTArg<BATCHED> a, int split) {
   const TTDev &d = a.get();
@@ -71,6 +80,11 @@ k_fwd_mfma(TTArg<BATCHED> a, int split) {
   using G = FwdGeom<R1, R2, D2>;
   extern __shared__ float lds[];
   float *As = lds;                  // [32][RS]  core-0 slices of the chunk
+  unsigned short *Asb = reinterpret_cast<unsigned short *>(lds);  // BF16: the same tile as [32][R1 + 4] bf16
+  constexpr int RSB = R1 + 4;
+  const unsigned short *__restrict__ g1b = reinterpret_cast<const unsigned short *>(d.g[0]),
+                       *__restrict__ g2b = reinterpret_cast<const unsigned short *>(d.g[1]),
+                       *__restrict__ g3b = reinterpret_cast<const unsigned short *>(d.g[2]);
   float *P12s = lds + G::OFF_P12;   // [8][PS]   prefix products of the chunk
   __shared__ int s_i1[FMETA], s_u0[FMETA], s_nr[FMETA], s_slot[FMETA];
   __shared__ int s_item_off[2][TT_MP + 1];
@@ -90,11 +104,19 @@ k_fwd_mfma(TTArg<BATCHED> a, int split) {
   // This wavefront's 32 columns of the strip of G2[:, i2], all r1 (B operand of F1), as one float2
   // per row and lane: lane lm holds columns 2*lm, 2*lm + 1, and MFMA tile nt takes component nt, i.e.
   // tile column lm stands for strip column 32*wave + 2*lm + nt.  Requested before the plan is looked at.
-  float2 bq[G::KS1];
+  float2 bq[BF16 ? 1 : G::KS1];
+  uint4 bqb[BF16 ? R1 / 16 : 1];  // BF16: per 16 values of r1, columns 2*lm and 2*lm + 1 with four r1 each
+  if constexpr (BF16) {
 #pragma unroll
-  for (int ks = 0; ks < G::KS1; ++ks)
-    bq[ks] = *reinterpret_cast<const float2 *>(g2 + ((size_t)(4 * ks + lq) * sh.n2 + i2) * G::S2 + strip * 256 +
-                                               32 * wave + 2 * lm);
+    for (int ks = 0; ks < R1 / 16; ++ks)
+      bqb[ks] = *reinterpret_cast<const uint4 *>(g2b + (((size_t)i2 * (R1 / 4) + 4 * ks + lq) * G::S2 + strip * 256 +
+                                                        32 * wave + 2 * lm) * 4);
+  } else {
+#pragma unroll
+    for (int ks = 0; ks < G::KS1; ++ks)
+      bq[ks] = *reinterpret_cast<const float2 *>(g2 + ((size_t)(4 * ks + lq) * sh.n2 + i2) * G::S2 + strip * 256 +
+                                                 32 * wave + 2 * lm);
+  }
 
   int seg0 = i2_seg[i2], seg1 = i2_seg[i2 + 1];
   if (split > 1) {  // the chunks of this (i2, strip) are dealt in contiguous runs to `split` workgroups
@@ -127,7 +149,8 @@ k_fwd_mfma(TTArg<BATCHED> a, int split) {
       // unconditional (slice 0 stands in for a prefix the chunk does not have; it is replaced by
       // zero when the chunk is staged, so that no load sits under a branch)
       const int i1 = s_i1[mo + (row >> 2)];
-      g1n[k] = g1[(size_t)(i1 >= 0 ? i1 : 0) * G::S1 + (row & 3) * R1 + r1];
+      const size_t at = (size_t)(i1 >= 0 ? i1 : 0) * G::S1 + (row & 3) * R1 + r1;
+      g1n[k] = BF16 ? bf16_to_float(g1b[at]) : g1[at];
     }
     const int p = threadIdx.x / FWD_I3_STAGE, r = threadIdx.x - p * FWD_I3_STAGE;
     rown = uniq_row[s_u0[mo + p] + (r < s_nr[mo + p] ? r : 0)];
@@ -136,7 +159,9 @@ k_fwd_mfma(TTArg<BATCHED> a, int split) {
 #pragma unroll
     for (int k = 0; k < G::GPT; ++k) {
       const int e = threadIdx.x + k * FTHR, row = e / R1, r1 = e - row * R1;
-      As[row * G::RS + r1] = s_i1[mo + (row >> 2)] >= 0 ? g1n[k] : 0.f;  // zero rows for prefixes the chunk does not have
+      const float v = s_i1[mo + (row >> 2)] >= 0 ? g1n[k] : 0.f;  // zero rows for prefixes the chunk does not have
+      if constexpr (BF16) Asb[row * RSB + r1] = (unsigned short)(__float_as_uint(v) >> 16);  // exact: v is a bf16 value
+      else As[row * G::RS + r1] = v;
     }
     s_i3[par][threadIdx.x / FWD_I3_STAGE][threadIdx.x % FWD_I3_STAGE] = rown % sh.n3;
     if (wave == 0) {  // quads per prefix of the chunk, running total (scan over the first 8 lanes)
@@ -171,17 +196,35 @@ k_fwd_mfma(TTArg<BATCHED> a, int split) {
       for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt) acc[mt][nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      if constexpr (BF16) {
 #pragma unroll
-      for (int ks = 0; ks < G::KS1; ++ks) {
-        float av[2];
+        for (int ks = 0; ks < R1 / 16; ++ks) {
+          bf16x4 av[2], bv[2];
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt) av[mt] = As[(16 * mt + lm) * G::RS + 4 * ks + lq];
-        const float bv[2] = {bq[ks].x, bq[ks].y};
+          for (int mt = 0; mt < 2; ++mt)
+            av[mt] = *reinterpret_cast<const bf16x4 *>(Asb + (16 * mt + lm) * RSB + 16 * ks + 4 * lq);
+          const uint2 b0 = make_uint2(bqb[ks].x, bqb[ks].y), b1 = make_uint2(bqb[ks].z, bqb[ks].w);
+          bv[0] = *reinterpret_cast<const bf16x4 *>(&b0);
+          bv[1] = *reinterpret_cast<const bf16x4 *>(&b1);
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
+          for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-          for (int nt = 0; nt < 2; ++nt)
-            acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[mt], bv[nt], acc[mt][nt], 0, 0, 0);
+            for (int nt = 0; nt < 2; ++nt)
+              acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(av[mt], bv[nt], acc[mt][nt], 0, 0, 0);
+        }
+      } else {
+#pragma unroll
+        for (int ks = 0; ks < G::KS1; ++ks) {
+          float av[2];
+#pragma unroll
+          for (int mt = 0; mt < 2; ++mt) av[mt] = As[(16 * mt + lm) * G::RS + 4 * ks + lq];
+          const float bv[2] = {bq[ks].x, bq[ks].y};
+#pragma unroll
+          for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt)
+              acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[mt], bv[nt], acc[mt][nt], 0, 0, 0);
+        }
       }
 #pragma unroll
       for (int mt = 0; mt < 2; ++mt) {
@@ -225,9 +268,12 @@ k_fwd_mfma(TTArg<BATCHED> a, int split) {
       // A operand: G3[r2][i3(row)][j3], m = (row, j3) = lm, k = r2
       const int arow = 4 * quad + ((lm >> 2) < x.nrow ? (lm >> 2) : x.nrow - 1);
       const int i3 = arow < FWD_I3_STAGE ? s_i3[par][p][arow] : uniq_row[s_u0[mo + p] + arow] % sh.n3;
-      const float *ap = g3 + ((size_t)lq * sh.n3 + i3) * 4 + (lm & 3);  // G3[r2 = 4*ks + lq][i3][j3], as stored
+      const size_t a0 = ((size_t)lq * sh.n3 + i3) * 4 + (lm & 3);  // G3[r2 = 4*ks + lq][i3][j3], as stored
 #pragma unroll
-      for (int ks = 0; ks < G::KS2; ++ks) x.a[ks] = ap[(size_t)16 * ks * sh.n3];
+      for (int ks = 0; ks < G::KS2; ++ks) {
+        const size_t at = a0 + (size_t)16 * ks * sh.n3;
+        x.a[ks] = BF16 ? bf16_to_float(g3b[at]) : g3[at];
+      }
     };
     auto compute = [&](const Item &x) __attribute__((always_inline)) {
       const float *bp = P12s + x.p * G::PS + lm * G::Rp + lq;
@@ -268,7 +314,7 @@ k_fwd_mfma(TTArg<BATCHED> a, int split) {
   }
 }
 
-template <int R1, int R2, int D2, bool P12OUT>
+template <int R1, int R2, int D2, bool P12OUT, bool BF16 = false>
 tt_status launch(const TTBatch &b, hipStream_t s) {
   using G = FwdGeom<R1, R2, D2>;
   const size_t lds = G::LDS_FLOATS * sizeof(float);
@@ -276,9 +322,9 @@ tt_status launch(const TTBatch &b, hipStream_t s) {
   static std::once_flag once;
   static bool configured = false;
   std::call_once(once, [&] {
-    configured = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fwd_mfma<false, R1, R2, D2, P12OUT>),
+    configured = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fwd_mfma<false, R1, R2, D2, P12OUT, BF16>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess &&
-                 hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fwd_mfma<true, R1, R2, D2, P12OUT>),
+                 hipFuncSetAttribute(reinterpret_cast<const void *>(&k_fwd_mfma<true, R1, R2, D2, P12OUT, BF16>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess;
   });
   if (!configured) return TT_ERR_HIP;
@@ -290,10 +336,10 @@ tt_status launch(const TTBatch &b, hipStream_t s) {
   const long long blocks = n2p8 * G::NSTRIP * split;
   TTProfScope prof(&b.host[0].plan, P12OUT ? TT_KERNEL_P12_FILL : TT_KERNEL_FWD_CONTRACT, s);
   if (b.dev)
-    hipLaunchKernelGGL((k_fwd_mfma<true, R1, R2, D2, P12OUT>), dim3((unsigned)blocks, (unsigned)b.T),
+    hipLaunchKernelGGL((k_fwd_mfma<true, R1, R2, D2, P12OUT, BF16>), dim3((unsigned)blocks, (unsigned)b.T),
                        dim3(FTHR), lds, s, TTArg<true>{b.dev}, split);
   else
-    hipLaunchKernelGGL((k_fwd_mfma<false, R1, R2, D2, P12OUT>), dim3((unsigned)blocks), dim3(FTHR), lds, s,
+    hipLaunchKernelGGL((k_fwd_mfma<false, R1, R2, D2, P12OUT, BF16>), dim3((unsigned)blocks), dim3(FTHR), lds, s,
                        TTArg<false>{b.host[0]}, split);
   return tt_launch_status();
 }
@@ -308,6 +354,11 @@ bool ttk_forward_mfma_supported(const TTShape &sh) {
 tt_status ttk_forward_mfma(const TTBatch &b, hipStream_t s) {
   if (b.host[0].sh.R1 == 32) return launch<32, 32, 8, false>(b, s);
   return launch<64, 64, 8, false>(b, s);
+}
+
+tt_status ttk_forward_mfma_bf16(const TTBatch &b, hipStream_t s) {
+  if (b.host[0].sh.R1 == 32) return launch<32, 32, 8, false, true>(b, s);
+  return launch<64, 64, 8, false, true>(b, s);
 }
 
 tt_status ttk_forward_mfma_p12(const TTBatch &b, hipStream_t s) {

@@ -158,6 +158,12 @@ static inline bool ttk_batch_mfma(const TTBatch &b) {
 tt_status ttk_forward_sample(const TTBatch &b, hipStream_t s);
 // the matrix-core forward kernel with its second stage replaced by a store of the prefix products
 tt_status ttk_forward_mfma_p12(const TTBatch &b, hipStream_t s);
+// the matrix-core forward kernel on bf16 copies of the cores (d.g[k] then point at bf16 data)
+tt_status ttk_forward_mfma_bf16(const TTBatch &b, hipStream_t s);
+tt_status ttk_bag_sum(const TTBatch &b, hipStream_t s);
+// byte offsets of the three bf16 cores inside the buffer tt_cores_to_bf16 fills, and its size
+void ttk_bf16_layout(const TTShape &sh, size_t off[3], size_t *total);
+tt_status ttk_cores_to_bf16(const TTShape &sh, const float *const core[3], void *buf, hipStream_t s);
 tt_status ttk_forward_naive(const TTBatch &b, hipStream_t s);
 tt_status ttk_backward_plan(const TTBatch &b, hipStream_t s);
 tt_status ttk_backward_naive(const TTBatch &b, hipStream_t s);

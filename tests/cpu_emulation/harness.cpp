@@ -124,6 +124,31 @@ int main(int argc, char **argv) {
           }
         free(reuse);
       }
+      if (planned && tt_bf16_cores_bytes(&B.t) > 0) {  // bf16 cores: against the fp32 kernels on host-rounded cores
+        const size_t cb = tt_bf16_cores_bytes(&B.t);
+        void *bf = amalloc(cb);
+        CK(tt_cores_to_bf16(&B.t, bf, cb, nullptr));
+        std::vector<float> out_b((size_t)B.bags * B.D, -7.f), out_r((size_t)B.bags * B.D, -7.f);
+        CK(tt_emb_bag_forward_bf16(&B.t, bf, &plan, B.off.data(), B.nnz, B.bags, out_b.data(), nullptr));
+        std::vector<float> rounded[3];
+        tt_table tr = B.t;
+        for (int k = 0; k < 3; ++k) {
+          rounded[k].assign(B.t.core[k], B.t.core[k] + (B.core[k].size() - 1));
+          for (auto &x : rounded[k]) {
+            uint32_t u; memcpy(&u, &x, 4);
+            u = (u + 0x7fffu + ((u >> 16) & 1u)) & 0xffff0000u;
+            memcpy(&x, &u, 4);
+          }
+          tr.core[k] = rounded[k].data();
+        }
+        CK(tt_emb_bag_forward(&tr, &plan, B.idx.data(), B.off.data(), B.nnz, B.bags, out_r.data(), nullptr));
+        for (size_t i = 0; i < out_b.size(); ++i)
+          if (!(fabs((double)out_b[i] - out_r[i]) <= 1e-5 * (1.0 + fabs((double)out_r[i])))) {
+            fprintf(stderr, "FAIL bf16 forward differs from the fp32 forward of rounded cores (table %d element %zu: %g vs %g)\n", t, i, out_b[i], out_r[i]);
+            return 5;
+          }
+        free(bf);
+      }
       float *dc[3];
       for (int k = 0; k < 3; ++k) { R.dg[k].assign(B.core[k].size() + 1, -9.f); dc[k] = R.dg[k].data() + g_off; }
       CK(tt_emb_bag_backward(&B.t, planned ? &plan : nullptr, B.idx.data(), B.off.data(), B.nnz, B.bags, B.grad.data(), dc, nullptr));

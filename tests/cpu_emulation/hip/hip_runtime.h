@@ -18,6 +18,11 @@ static inline float4 make_float4(float x, float y, float z, float w) { return fl
 struct alignas(16) int4 { int x, y, z, w; };
 struct alignas(8) int2 { int x, y; };
 static inline int4 make_int4(int x, int y, int z, int w) { return int4{x, y, z, w}; }
+struct alignas(16) uint4 { unsigned x, y, z, w; };
+struct alignas(8) uint2 { unsigned x, y; };
+static inline uint2 make_uint2(unsigned x, unsigned y) { return uint2{x, y}; }
+static inline float __uint_as_float(unsigned u) { float f; memcpy(&f, &u, 4); return f; }
+static inline unsigned __float_as_uint(float f) { unsigned u; memcpy(&u, &f, 4); return u; }
 
 typedef void *hipStream_t;
 typedef void *hipEvent_t;
@@ -111,3 +116,14 @@ static inline emu_f32x4 emu_mfma(float a, float b, emu_f32x4 c, int, int, int) {
   return (emu_f32x4){t[0], t[1], t[2], t[3]};
 }
 #define __builtin_amdgcn_mfma_f32_16x16x4f32 emu_mfma
+// 16x16x16 bf16: lane l supplies A[m = l%16][k = 4*(l/16) + i] and B[k = 4*(l/16) + i][n = l%16],
+// i = 0..3 -- the sum over i of four 16x16x4 products of the widened values
+typedef short emu_bf16x4 __attribute__((ext_vector_type(4)));
+static inline emu_f32x4 emu_mfma_bf16(emu_bf16x4 a, emu_bf16x4 b, emu_f32x4 c, int, int, int) {
+  float t[4] = {c[0], c[1], c[2], c[3]};
+  for (int i = 0; i < 4; ++i)
+    emu::wave_mfma_16x16x4(__uint_as_float((unsigned)(unsigned short)a[i] << 16),
+                           __uint_as_float((unsigned)(unsigned short)b[i] << 16), t);
+  return (emu_f32x4){t[0], t[1], t[2], t[3]};
+}
+#define __builtin_amdgcn_mfma_f32_16x16x16bf16_1k emu_mfma_bf16

@@ -282,3 +282,67 @@ def test_unaligned_core_and_gradient_buffers_take_the_scalar_paths(g, ora):
     mixed[1] = torch.empty(len(cores[1]) + 1, dtype=torch.float32, device="cuda")[1:]
     tt.tt_emb_bag_backward(table2, plan2, d_idx, d_off, d_g, dcores=mixed)
     g.assert_grads_close(shape, mixed, ref_dg, what="unaligned dG2 buffer")
+
+
+def round_to_bf16(a):
+    """fp32 -> nearest bf16 (ties to even), returned as fp32: the storage format of the reduced-precision
+    cores, written here from the format's definition (upper 16 bits of the fp32 pattern)."""
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32)
+
+
+def check_bf16_forward(g, ora, shape, cores, idx, off, what):
+    import paper_2507_14668_amd as tt
+    table = g.gpu_table(shape, cores)
+    d_idx, d_off = g.to_dev(idx, torch.int64), g.to_dev(off, torch.int64)
+    plan = tt.tt_index_reorder(table, d_idx, d_off)
+    bf = tt.tt_cores_to_bf16(table)
+    out = tt.tt_emb_bag_forward_bf16(table, bf, plan, d_off).cpu().numpy()
+    rounded = [round_to_bf16(c) for c in cores]
+    # (1) fp32 accumulation of exactly representable products: the oracle on the rounded cores, fp32 tolerance
+    ref_rounded = ora.forward(shape, rounded, idx, off, dedup=True)
+    g.assert_close_rows(out, ref_rounded, g.FWD_RTOL, shape.dim, "%s bf16 forward vs oracle(rounded cores)" % what)
+    # (2) against the unrounded cores: every core element moves by at most 2^-9 relative, so every
+    # TT path product by at most (1 + 2^-9)^3 - 1, and the bag sum by that times the sum of |paths|
+    # = the oracle's forward of the absolute cores
+    ref = ora.forward(shape, cores, idx, off, dedup=True).astype(np.float64)
+    path_sum = ora.forward(shape, [np.abs(c) for c in cores], idx, off, dedup=True).astype(np.float64)
+    bound = ((1 + 2.0 ** -9) ** 3 - 1) * path_sum + g.FWD_RTOL * np.abs(ref).max()
+    assert np.all(np.abs(out - ref) <= bound), "%s: bf16 storage error above its bound" % what
+    rel = np.abs(out - ref).max() / np.abs(ref).max()
+    print("  %s: bf16-core forward differs from the fp32-core oracle by %.2e of the largest output" % (what, rel), flush=True)
+    assert rel > 1e-5, "the rounding of the cores must be visible (is the bf16 path really bf16?)"
+    # unsupported shapes are refused, not silently served in fp32
+    return plan
+
+
+@pytest.mark.parametrize("seed,n,r,nb,ml", [
+    (71, (5, 7, 9), (1, 32, 32, 1), 300, 6),
+    (72, (150, 2, 3), (1, 32, 32, 1), 1500, 3),
+    (73, (3, 2, 90), (1, 64, 64, 1), 1500, 5),
+    (74, (37, 5, 4), (1, 64, 64, 1), 900, 3),
+])
+def test_bf16_cores_forward(g, ora, seed, n, r, nb, ml):
+    """Reduced-precision storage of the cores (bf16) with fp32 accumulation, on the matrix-core shapes."""
+    print("case bf16 seed=%d n=%s r=%s" % (seed, n, r), flush=True)
+    shape, cores, idx, off, _ = wl.small_random_problem(seed, n=n, d=(4, 8, 4), r=r, num_bags=nb, max_len=ml, sigma=0.2)
+    check_bf16_forward(g, ora, shape, cores, idx, off, "small")
+
+
+@pytest.mark.parametrize("cfg_id,tab", [(3, 0), (5, 1)])
+def test_bf16_cores_forward_config_tables(g, ora, cfg_id, tab):
+    print("case bf16 cfg%d table %d" % (cfg_id, tab), flush=True)
+    cfg = wl.get_config(cfg_id)
+    shape, cores = cfg.tables[tab], wl.make_cores(cfg, tab)
+    idx, off = wl.make_batch(cfg, tab)
+    check_bf16_forward(g, ora, shape, cores, idx, off, "cfg%d" % cfg_id)
+
+
+def test_bf16_cores_refused_for_other_shapes(g):
+    import paper_2507_14668_amd as tt
+    shape, cores, *_ = wl.small_random_problem(75)
+    table = g.gpu_table(shape, cores)
+    assert tt.tt_bf16_cores_bytes(table) == 0
+    with pytest.raises(tt.TTError):
+        tt.tt_cores_to_bf16(table)
