@@ -314,6 +314,29 @@ tt_status tt_core_sgd_update_batched(int num_tables, tt_batch_item *items, float
                                      size_t desc_bytes, void *stream);
 
 /*
+ * Index-graph edges of one batch (Section III-G, index-graph generation algorithm): the weighted
+ * co-occurrence graph the offline index bijection is built from.  Offline preprocessing, not part
+ * of a training step.
+ *   node of a lookup = max(rank[index], hot_thresh) - hot_thresh, with rank[] the frequency rank
+ *   of every row (0 = most frequent); node 0 (all hot rows) is dropped.  Every bag contributes one
+ *   pair (u < v) per two of its distinct nodes; a bag with more than max_group (<= 64) distinct
+ *   nodes keeps its max_group smallest ones, and only the first 256 lookups of a bag are looked at.
+ *   Equal pairs are merged; weight = number of bags that hold both ends.
+ *   indices, offsets  DEVICE, as in tt_index_reorder (invalid indices are skipped)
+ *   rank              DEVICE int32[num_rows]
+ *   workspace         DEVICE, 256-byte aligned, tt_index_graph_workspace_bytes(num_bags, max_pairs)
+ *   edge_u/v/w        DEVICE int32[max_pairs] each: the edges, sorted by (u, v), weights in edge_w
+ *   counts            DEVICE int32[4]: [0] pairs before merging, [1] edges, [2] 1 if the batch has
+ *                     more than max_pairs pairs (then no edge is produced)
+ * The result is unique (integer work, stable sorts).
+ */
+size_t tt_index_graph_workspace_bytes(int64_t num_bags, int64_t max_pairs);
+tt_status tt_index_graph_edges(const int64_t *indices, const int64_t *offsets, int64_t nnz, int64_t num_bags,
+                               const int32_t *rank, int64_t num_rows, int64_t hot_thresh, int32_t max_group,
+                               void *workspace, size_t workspace_bytes, int64_t max_pairs, int32_t *edge_u,
+                               int32_t *edge_v, int32_t *edge_w, int32_t *counts, void *stream);
+
+/*
  * Waits for `stream`, copies the plan's device-side counters to the host and
  * reports deferred errors.  counts_out (HOST, nullable) receives
  * {U_r, U_p, valid lookups, status bits}.  Returns TT_ERR_INDEX_RANGE if any

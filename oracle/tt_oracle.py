@@ -208,3 +208,30 @@ def forward_sample_reuse(shape, cores, indices, offsets):
             out[b] += np.einsum("jkc,cm->jkm", p12, s3).reshape(-1)    # [d1][d2][d3]
         groups += len(slice_sum)
     return out, groups
+
+
+def index_graph_edges(indices, offsets, rank, hot_thresh: int, max_group: int = 64, bag_cap: int = 256) -> dict:
+    """Weighted co-occurrence edges of one batch (Section III-G, index-graph generation): a dict
+    {(u, v): weight} with u < v, written as plain loops.
+
+    Every lookup becomes the node max(rank[row], hot_thresh) - hot_thresh (frequency rank shifted by
+    the hot threshold; node 0 = all hot rows, dropped).  A bag contributes every pair of its
+    distinct nodes once; bags with more than `max_group` distinct nodes keep the `max_group`
+    smallest, and only the first `bag_cap` lookups of a bag are looked at (both are limits of the
+    job, not of the paper, which pairs everything).  weight = number of bags holding both ends.
+    """
+    import itertools
+    idx, off = _i64(indices), _i64(offsets)
+    rank = np.asarray(rank)
+    edges = {}
+    for b in range(off.size - 1):
+        nodes = set()
+        for i in idx[off[b]:off[b + 1]][:bag_cap]:
+            if 0 <= i < rank.size:
+                node = max(int(rank[i]), hot_thresh) - hot_thresh
+                if node > 0:
+                    nodes.add(node)
+        kept = sorted(nodes)[:max_group]
+        for u, v in itertools.combinations(kept, 2):
+            edges[(u, v)] = edges.get((u, v), 0) + 1
+    return edges

@@ -14,7 +14,10 @@ Steps, in the paper's order:
      edge (weight = number of co-occurrences) between two rows looked up in the same group.  The
      paper pairs all rows of a mini-batch; `group="bag"` (default) pairs the rows of one bag, which
      is what carries signal for multi-hot features, and `group="batch"` follows the paper literally.
-     Groups larger than `max_group` are sub-sampled (seeded), the pair count is quadratic;
+     A group with more than `max_group` distinct nodes keeps its `max_group` smallest ones (the most
+     frequent rows), the pair count being quadratic.  With `device="cuda"` the edges of a batch are
+     generated on the GPU by the library's `tt_index_graph_edges` job (pair generation per bag, two
+     stable radix sorts, run heads) with the same rule, and merged across batches here;
   3. communities by greedy modularity maximisation (local moving of single nodes, the first phase
      of the Louvain method, in a seeded order until no move improves the modularity
      Q = sum_c [ e_cc / 2m - (k_c / 2m)^2 ]);
@@ -46,33 +49,52 @@ def frequency_order(batches, num_rows: int):
     return rank, counts
 
 
-def index_graph_edges(batches, rank, hot_thresh: int, group: str = "bag", max_group: int = 64, seed: int = 0):
-    """Weighted edge list (u, v, w), u < v, over frequency ranks shifted by the hot threshold (the
-    paper's clamp-and-subtract: every hot row collapses to node 0, which is dropped)."""
-    rng = np.random.default_rng(seed)
+def _merge_edges(us, vs, ws):
+    if not us:
+        return np.zeros(0, np.int64), np.zeros(0, np.int64), np.zeros(0, np.int64)
+    u, v, w = np.concatenate(us), np.concatenate(vs), np.concatenate(ws)
+    base = int(v.max()) + 1
+    uniq, inv = np.unique(u * base + v, return_inverse=True)
+    return uniq // base, uniq % base, np.bincount(inv, weights=w, minlength=uniq.size).astype(np.int64)
+
+
+def index_graph_edges(batches, rank, hot_thresh: int, group: str = "bag", max_group: int = 64, bag_cap: int = 256):
+    """Weighted edge list (u, v, w), u < v, sorted by (u, v), over frequency ranks shifted by the hot
+    threshold (the paper's clamp-and-subtract: every hot row collapses to node 0, which is dropped)."""
     us, vs = [], []
     for item in batches:
         if group == "bag":
             idx, off = item
-            groups = [np.asarray(idx[off[b]:off[b + 1]]) for b in range(len(off) - 1)]
+            groups = [np.asarray(idx[off[b]:off[b + 1]])[:bag_cap] for b in range(len(off) - 1)]
         else:
             groups = [np.asarray(item[0] if isinstance(item, tuple) else item)]
         for grp in groups:
+            grp = grp[(grp >= 0) & (grp < rank.size)]
             node = np.unique(np.maximum(rank[grp], hot_thresh) - hot_thresh)
-            node = node[node > 0]  # node 0 = the hot rows
-            if node.size > max_group:
-                node = np.sort(rng.choice(node, size=max_group, replace=False))
+            node = node[node > 0][:max_group]  # node 0 = the hot rows; the smallest max_group nodes are kept
             if node.size < 2:
                 continue
             a, b = np.triu_indices(node.size, k=1)
             us.append(node[a])
             vs.append(node[b])
-    if not us:
-        return np.zeros(0, np.int64), np.zeros(0, np.int64), np.zeros(0, np.int64)
-    u, v = np.concatenate(us), np.concatenate(vs)
-    key = u * (int(v.max()) + 1) + v
-    uniq, w = np.unique(key, return_counts=True)
-    return uniq // (int(v.max()) + 1), uniq % (int(v.max()) + 1), w.astype(np.int64)
+    return _merge_edges(us, vs, [np.ones(len(x), np.int64) for x in us])
+
+
+def index_graph_edges_gpu(batches, rank, hot_thresh: int, max_group: int = 64):
+    """The same edge list with the per-batch work done by the GPU job (bags as groups)."""
+    import torch
+
+    from . import binding
+    d_rank = torch.from_numpy(np.ascontiguousarray(rank, dtype=np.int32)).cuda()
+    us, vs, ws = [], [], []
+    for idx, off in batches:
+        d_idx = torch.from_numpy(np.ascontiguousarray(idx, dtype=np.int64)).cuda()
+        d_off = torch.from_numpy(np.ascontiguousarray(off, dtype=np.int64)).cuda()
+        u, v, w = binding.tt_index_graph_edges(d_idx, d_off, d_rank, hot_thresh, max_group)
+        us.append(u.cpu().numpy().astype(np.int64))
+        vs.append(v.cpu().numpy().astype(np.int64))
+        ws.append(w.cpu().numpy().astype(np.int64))
+    return _merge_edges(us, vs, ws)
 
 
 def greedy_modularity_communities(u, v, w, max_sweeps: int = 20, seed: int = 0):
@@ -118,13 +140,18 @@ def greedy_modularity_communities(u, v, w, max_sweeps: int = 20, seed: int = 0):
 
 
 def build_index_bijection(batches, num_rows: int, hot_ratio: float = 0.001, group: str = "bag",
-                          max_group: int = 64, seed: int = 0):
+                          max_group: int = 64, seed: int = 0, device: str = "cpu"):
     """remap[old row] = new row, an int64 permutation of range(num_rows), from sample `batches`
     (a list of (indices, offsets) pairs, CSR offsets of length bags + 1)."""
     flat = [np.asarray(b[0]) for b in batches]
     rank, counts = frequency_order(flat, num_rows)
     hot_thresh = int(num_rows * hot_ratio)
-    u, v, w = index_graph_edges(batches, rank, hot_thresh, group=group, max_group=max_group, seed=seed)
+    if device == "cuda":
+        if group != "bag":
+            raise ValueError("the GPU edge job pairs the rows of one bag")
+        u, v, w = index_graph_edges_gpu(batches, rank, hot_thresh, max_group=max_group)
+    else:
+        u, v, w = index_graph_edges(batches, rank, hot_thresh, group=group, max_group=max_group)
     comm = greedy_modularity_communities(u, v, w, seed=seed)
     by_rank = np.argsort(rank, kind="stable")  # row with rank r
     new_of_rank = np.full(num_rows, -1, dtype=np.int64)

@@ -25,7 +25,8 @@ TT_ERR_UNAVAILABLE = -6
 
 EXPORTS = ("tt_workspace_bytes", "tt_index_reorder", "tt_emb_bag_forward", "tt_emb_bag_backward",
            "tt_core_sgd_update", "tt_emb_bag_backward_sgd", "tt_emb_bag_forward_static", "tt_reuse_buffer_bytes", "tt_emb_bag_forward_sample",
-           "tt_bf16_cores_bytes", "tt_cores_to_bf16", "tt_emb_bag_forward_bf16", "tt_plan_status", "tt_strerror", "tt_prof_create", "tt_prof_destroy",
+           "tt_bf16_cores_bytes", "tt_cores_to_bf16", "tt_emb_bag_forward_bf16",
+           "tt_index_graph_workspace_bytes", "tt_index_graph_edges", "tt_plan_status", "tt_strerror", "tt_prof_create", "tt_prof_destroy",
            "tt_prof_collect", "tt_kernel_name", "tt_batch_desc_bytes", "tt_index_reorder_batched",
            "tt_emb_bag_forward_batched", "tt_emb_bag_backward_batched", "tt_core_sgd_update_batched")
 KERNELS = {"fwd_contract": 0, "bag_sum": 1, "grad_merge": 2, "bwd_contract": 3, "sort_scatter": 4, "sgd": 5,
@@ -104,6 +105,11 @@ def load_library():
         lib.tt_cores_to_bf16.argtypes = [vp, vp, ctypes.c_size_t, vp]
         lib.tt_emb_bag_forward_bf16.restype = ctypes.c_int
         lib.tt_emb_bag_forward_bf16.argtypes = [vp, vp, vp, vp, i64, i64, vp, vp]
+        lib.tt_index_graph_workspace_bytes.restype = ctypes.c_size_t
+        lib.tt_index_graph_workspace_bytes.argtypes = [i64, i64]
+        lib.tt_index_graph_edges.restype = ctypes.c_int
+        lib.tt_index_graph_edges.argtypes = [vp, vp, i64, i64, vp, i64, i64, ctypes.c_int32, vp, ctypes.c_size_t, i64,
+                                             vp, vp, vp, vp, vp]
         lib.tt_plan_status.restype = ctypes.c_int
         lib.tt_plan_status.argtypes = [vp, vp, vp]
         lib.tt_prof_create.restype = vp
@@ -299,6 +305,31 @@ def tt_emb_bag_forward_sample(table: Table, plan, offsets, reuse_buffer=None, ou
                                                   _ptr(reuse_buffer), reuse_buffer.numel(), _ptr(out), _stream(stream))
     _check(st, "tt_emb_bag_forward_sample")
     return out
+
+
+def tt_index_graph_edges(indices, offsets, rank, hot_thresh: int, max_group: int = 64, max_pairs: int = None,
+                         stream=None):
+    """Co-occurrence edges of one batch on the GPU: (u, v, w) int32 device tensors sorted by (u, v).
+    Synchronises to read the edge count.  `rank` is an int32 device tensor of frequency ranks."""
+    indices, offsets = _dev_i64(indices, "indices"), _dev_i64(offsets, "offsets")
+    if rank.dtype != torch.int32 or not rank.is_cuda or not rank.is_contiguous():
+        raise TypeError("rank must be a contiguous int32 device tensor")
+    nnz, nb = indices.numel(), offsets.numel() - 1
+    if max_pairs is None:  # every bag pairs at most min(length, max_group) nodes
+        lens = torch.clamp(offsets[1:] - offsets[:-1], max=max_group)
+        max_pairs = max(1, int((lens * (lens - 1) // 2).sum().item()))
+    lib = load_library()
+    ws = torch.empty(lib.tt_index_graph_workspace_bytes(nb, max_pairs), dtype=torch.uint8, device=indices.device)
+    eu, ev, ew = (torch.empty(max_pairs, dtype=torch.int32, device=indices.device) for _ in range(3))
+    counts = torch.zeros(4, dtype=torch.int32, device=indices.device)
+    st = lib.tt_index_graph_edges(_ptr(indices), _ptr(offsets), nnz, nb, _ptr(rank), rank.numel(), int(hot_thresh),
+                                  int(max_group), _ptr(ws), ws.numel(), max_pairs, _ptr(eu), _ptr(ev), _ptr(ew),
+                                  _ptr(counts), _stream(stream))
+    _check(st, "tt_index_graph_edges")
+    c = counts.cpu().tolist()  # synchronises
+    if c[2] != 0:
+        raise TTError(TT_ERR_WORKSPACE, "tt_index_graph_edges: more pairs than max_pairs")
+    return eu[:c[1]], ev[:c[1]], ew[:c[1]]
 
 
 def tt_bf16_cores_bytes(table: Table) -> int:

@@ -417,6 +417,26 @@ tt_status tt_emb_bag_forward_bf16(const tt_table *table, const void *bf16_cores,
   return ttk_bag_sum(b, (hipStream_t)stream);
 }
 
+size_t tt_index_graph_workspace_bytes(int64_t num_bags, int64_t max_pairs) {
+  if (num_bags < 0 || max_pairs < 1 || num_bags >= 2147483646LL || max_pairs >= 2147483647LL) return 0;
+  return (ttk_index_graph_workspace_bytes(num_bags, max_pairs) + 255) & ~(size_t)255;
+}
+
+tt_status tt_index_graph_edges(const int64_t *indices, const int64_t *offsets, int64_t nnz, int64_t num_bags,
+                               const int32_t *rank, int64_t num_rows, int64_t hot_thresh, int32_t max_group,
+                               void *workspace, size_t workspace_bytes, int64_t max_pairs, int32_t *edge_u,
+                               int32_t *edge_v, int32_t *edge_w, int32_t *counts, void *stream) {
+  if (!offsets || (nnz > 0 && !indices) || !rank || !workspace || !edge_u || !edge_v || !edge_w || !counts)
+    return TT_ERR_INVALID_ARG;
+  if (!batch_ok(nnz, num_bags) || num_rows < 1 || num_rows >= 2147483647LL || hot_thresh < 0) return TT_ERR_INVALID_ARG;
+  if (max_group < 2 || max_group > 64) return TT_ERR_INVALID_ARG;
+  const size_t need = tt_index_graph_workspace_bytes(num_bags, max_pairs);
+  if (need == 0) return TT_ERR_INVALID_ARG;
+  if (((uintptr_t)workspace & 255) != 0 || workspace_bytes < need) return TT_ERR_WORKSPACE;
+  return ttk_index_graph_edges(indices, offsets, nnz, num_bags, rank, num_rows, hot_thresh, max_group, workspace,
+                               max_pairs, edge_u, edge_v, edge_w, counts, (hipStream_t)stream);
+}
+
 tt_status tt_emb_bag_forward_static(const tt_table *table, const int64_t *indices, const int64_t *offsets,
                                     int64_t nnz, int64_t num_bags, float *out, void *stream) {
   if (!table || !offsets || (nnz > 0 && !indices) || (num_bags > 0 && !out)) return TT_ERR_INVALID_ARG;

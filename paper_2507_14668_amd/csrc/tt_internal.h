@@ -131,6 +131,18 @@ template <> struct TTArg<true> {
 // Launchers (host).  Each enqueues kernels on `s` for every table of the batch and returns the
 // launch status.  All tables of a batch share d[] and r[] (checked by the caller).
 tt_status ttk_reorder(const TTBatch &b, hipStream_t s);
+// The stable LSD radix sort of the plan on caller-chosen buffers: sorts the (key, payload) pairs of
+// sort slot 1 -- (plan.i3_of_sorted, plan.rows_by_i3) with partners (tmp.k3_alt, tmp.v3_alt), count in
+// plan.counts[0], capacity plan.max_rows, scratch tmp.hist / tmp.bin_total -- by keys of key_bits bits.
+// Input in the first pair for an even number of passes, in the partners for an odd one; result in the
+// first pair.
+int ttk_radix_passes(int key_bits);
+tt_status ttk_sort_slot1(const TTDev &d, int key_bits, hipStream_t s);
+size_t ttk_index_graph_workspace_bytes(long long num_bags, long long max_pairs);
+tt_status ttk_index_graph_edges(const int64_t *indices, const int64_t *offsets, long long nnz, long long num_bags,
+                                const int32_t *rank, long long num_rows, long long hot, int max_group,
+                                void *workspace, long long max_pairs, int32_t *eu, int32_t *ev, int32_t *ew,
+                                int32_t *counts_out, hipStream_t s);
 tt_status ttk_forward_plan(const TTBatch &b, hipStream_t s);
 bool ttk_forward_mfma_supported(const TTShape &sh);
 tt_status ttk_forward_mfma(const TTBatch &b, hipStream_t s);

@@ -768,6 +768,13 @@ tt_status radix_sort(const TTBatch &b, int which, int max_tiles, int key_bits, h
 
 }  // namespace
 
+int ttk_radix_passes(int key_bits) { return radix_plan(key_bits).passes; }
+
+tt_status ttk_sort_slot1(const TTDev &d, int key_bits, hipStream_t s) {
+  const TTBatch b = {1, &d, nullptr};
+  return radix_sort(b, 1, tt_ceil_div(d.plan.max_rows, TT_SORT_TILE), key_bits, s, 0);
+}
+
 size_t tt_sort_tmp_bytes(int64_t nnz, int64_t max_rows, int64_t max_prefixes) {
   const size_t ntiles = (size_t)tt_ceil_div(nnz, TT_SORT_TILE) + 1;
   const size_t utiles = (size_t)tt_ceil_div(nnz, TT_UNIQ_TILE) + 1;

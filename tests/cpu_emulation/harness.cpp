@@ -92,6 +92,24 @@ int main(int argc, char **argv) {
     for (int t = 0; t < 3; ++t)
       tabs.push_back(make_tab(ns[t], d, 5, 6, bags[t], 7, (int64_t)ns[t][0] * ns[t][1] * ns[t][2]));
   }
+  {  // index-graph edges of the first table's batch (sanitizer coverage; the result is compared with
+     // the oracle in the Python tests)
+    Tab &B = tabs[0];
+    std::vector<int32_t> rank((size_t)B.t.num_rows);
+    for (size_t i = 0; i < rank.size(); ++i) rank[i] = (int32_t)((i * 7919u) % rank.size());
+    int64_t cap = 1;
+    for (int b = 0; b < B.bags; ++b) { int64_t l = B.off[b + 1] - B.off[b]; if (l > 64) l = 64; cap += l * (l - 1) / 2; }
+    const size_t wb = tt_index_graph_workspace_bytes(B.bags, cap);
+    void *ws = amalloc(wb);
+    std::vector<int32_t> eu((size_t)cap), ev((size_t)cap), ew((size_t)cap), counts(4);
+    CK(tt_index_graph_edges(B.idx.data(), B.off.data(), B.nnz, B.bags, rank.data(), B.t.num_rows, 2, 64, ws, wb, cap,
+                            eu.data(), ev.data(), ew.data(), counts.data(), nullptr));
+    long long wsum = 0;
+    for (int e = 0; e < counts[1]; ++e) wsum += ew[e];
+    if (counts[2] != 0 || wsum != counts[0]) { fprintf(stderr, "FAIL index-graph edges: weights %lld pairs %d\n", wsum, counts[0]); return 6; }
+    fprintf(stderr, "index-graph edges: %d pairs -> %d edges\n", counts[0], counts[1]);
+    free(ws);
+  }
   const int T = (int)tabs.size();
   const float lr = 0.01f;
   for (int planned = 1; planned >= 0; --planned) {

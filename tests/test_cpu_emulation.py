@@ -141,6 +141,41 @@ def test_emulated_kernels_match_oracle(emu, ora, name, n, d, r, nb, ml):
         assert np.array_equal(res["fused"][k], res["updated"][k]), "fused update differs from backward + update"
 
 
+@pytest.mark.parametrize("nb,ml,rows,hot,max_group", [(300, 9, 400, 5, 64), (40, 300, 3000, 0, 16), (200, 5, 50, 45, 64)])
+def test_emulated_index_graph_edges_match_oracle(emu, ora, nb, ml, rows, hot, max_group):
+    """The edge-generation job (pairs per bag, two stable radix sorts, run heads) against the loop oracle:
+    short bags, bags longer than a wavefront round and than the per-bag cap, almost every row hot."""
+    lib, _ = emu
+    rng = np.random.default_rng(nb)
+    lens = rng.integers(0, ml + 1, nb)
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    idx = np.minimum((rows ** rng.random(int(off[-1]))).astype(np.int64), rows - 1)  # skewed
+    idx[::17] = -1
+    rank = rng.permutation(rows).astype(np.int32)
+    ref = ora.index_graph_edges(idx, off, rank, hot, max_group)
+    cap = max(1, int(sum(min(l, max_group) * (min(l, max_group) - 1) // 2 for l in lens)))
+    lib.tt_index_graph_workspace_bytes.restype = ctypes.c_size_t
+    lib.tt_index_graph_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int64]
+    ws = _aligned(lib.tt_index_graph_workspace_bytes(nb, cap))
+    eu, ev, ew = (np.full(cap, -1, np.int32) for _ in range(3))
+    counts = np.zeros(4, np.int32)
+    vp, i64 = ctypes.c_void_p, ctypes.c_int64
+    lib.tt_index_graph_edges.argtypes = [vp, vp, i64, i64, vp, i64, i64, ctypes.c_int32, vp, ctypes.c_size_t, i64,
+                                         vp, vp, vp, vp, vp]
+    assert lib.tt_index_graph_edges(_ptr(idx), _ptr(off), len(idx), nb, _ptr(rank), rows, hot, max_group, _ptr(ws),
+                                    ws.nbytes, cap, _ptr(eu), _ptr(ev), _ptr(ew), _ptr(counts), None) == 0
+    assert counts[2] == 0 and counts[0] == sum(ref.values()) and counts[1] == len(ref)
+    got = {(int(u), int(v)): int(w) for u, v, w in zip(eu[:counts[1]], ev[:counts[1]], ew[:counts[1]])}
+    assert got == ref
+    keys = list(zip(eu[:counts[1]].tolist(), ev[:counts[1]].tolist()))
+    assert keys == sorted(keys), "edges must come out sorted by (u, v)"
+    # a capacity that is too small is reported, and nothing is produced
+    if sum(ref.values()) > 1:
+        assert lib.tt_index_graph_edges(_ptr(idx), _ptr(off), len(idx), nb, _ptr(rank), rows, hot, max_group, _ptr(ws),
+                                        ws.nbytes, sum(ref.values()) - 1, _ptr(eu), _ptr(ev), _ptr(ew), _ptr(counts), None) == 0
+        assert counts[2] == 1 and counts[1] == 0
+
+
 @pytest.fixture(scope="module")
 def asan_harness():
     return emu_build.build_harness(BUILD_DIR, "address")

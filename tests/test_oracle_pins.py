@@ -328,3 +328,21 @@ def test_dedup_mode_matches_definition_mode_at_config_sizes(ora, cfg_id):
     l0 = float((a.astype(np.float64) * grad.reshape(a.shape)).sum())
     for k in range(3):
         assert abs(float(np.dot(ga[k].astype(np.float64), cores[k].astype(np.float64))) - l0) <= 1e-5 * abs(l0) + 1e-6
+
+
+# ----------------------------------------------------------------- index graph
+def test_index_graph_edges_on_a_hand_computed_batch(ora):
+    """Four bags over ranks written out by hand.  rank = identity, hot threshold 2 (rows 0..2 -> node 0).
+    bag 0 = rows {5, 3, 5, 9}  -> nodes {3, 1, 7}   pairs (1,3) (1,7) (3,7)
+    bag 1 = rows {3, 9, 1}     -> nodes {1, 7}      pair  (1,7)            (row 1 is hot)
+    bag 2 = rows {9}           -> no pair
+    bag 3 = rows {3, 5, 9, 4}  -> nodes {1, 3, 7, 2}, max_group 3 keeps {1, 2, 3}: (1,2) (1,3) (2,3)"""
+    idx = np.array([5, 3, 5, 9, 3, 9, 1, 9, 3, 5, 9, 4], np.int64)
+    off = np.array([0, 4, 7, 8, 12], np.int64)
+    got = ora.index_graph_edges(idx, off, np.arange(10), hot_thresh=2, max_group=3)
+    assert got == {(1, 3): 2, (1, 7): 2, (3, 7): 1, (1, 2): 1, (2, 3): 1}
+    # without the group limit bag 3 pairs all four of its nodes
+    got = ora.index_graph_edges(idx, off, np.arange(10), hot_thresh=2, max_group=64)
+    assert got == {(1, 3): 2, (1, 7): 3, (3, 7): 2, (1, 2): 1, (2, 3): 1, (2, 7): 1}
+    # total weight = sum over bags of C(distinct kept nodes, 2)
+    assert sum(got.values()) == 3 + 1 + 0 + 6
