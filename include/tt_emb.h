@@ -359,7 +359,7 @@ typedef enum {
   TT_KERNEL_FWD_CONTRACT = 0, /* prefix products + distinct rows (forward)                   */
   TT_KERNEL_BAG_SUM = 1,      /* per-bag sum of distinct rows                                */
   TT_KERNEL_GRAD_MERGE = 2,   /* stage 1 of merging grad_out per distinct row                */
-  TT_KERNEL_BWD_CONTRACT = 3, /* per-prefix backward contractions                            */
+  TT_KERNEL_BWD_CONTRACT = 3, /* backward contraction kernel (without the sum of split parts)  */
   TT_KERNEL_SORT_SCATTER = 4, /* one radix-sort scatter pass of the main lookup sort         */
   TT_KERNEL_SGD = 5,          /* core update                                                 */
   TT_KERNEL_P12_FILL = 6,     /* reuse buffer of the sample-level forward                    */

@@ -598,13 +598,15 @@ tt_status launch(const TTBatch &b, hipStream_t s) {
   if (!configured) return TT_ERR_HIP;
   const long long blocks = tt_batch_max(b, [](const TTDev &d) {
     return (long long)((d.sh.n2 + 7) & ~7) * G::NSB * d.bwd_split; });
-  TTProfScope prof(&b.host[0].plan, TT_KERNEL_BWD_CONTRACT, s);
-  if (b.dev)
-    hipLaunchKernelGGL((k_bwd_mfma<true, R1, R2>), dim3((unsigned)blocks, (unsigned)b.T),
-                       dim3(NTHR), lds, s, TTArg<true>{b.dev});
-  else
-    hipLaunchKernelGGL((k_bwd_mfma<false, R1, R2>), dim3((unsigned)blocks), dim3(NTHR), lds, s,
-                       TTArg<false>{b.host[0]});
+  {
+    TTProfScope prof(&b.host[0].plan, TT_KERNEL_BWD_CONTRACT, s);  // the contraction kernel alone
+    if (b.dev)
+      hipLaunchKernelGGL((k_bwd_mfma<true, R1, R2>), dim3((unsigned)blocks, (unsigned)b.T),
+                         dim3(NTHR), lds, s, TTArg<true>{b.dev});
+    else
+      hipLaunchKernelGGL((k_bwd_mfma<false, R1, R2>), dim3((unsigned)blocks), dim3(NTHR), lds, s,
+                         TTArg<false>{b.host[0]});
+  }
   if (tt_batch_max(b, [](const TTDev &d) { return (long long)d.bwd_split; }) > 1) {
     const int tiles = tt_ceil_div((long long)R1 * G::S2, TT_BLOCK * 4);
     const long long n2max = tt_batch_max(b, [](const TTDev &d) { return (long long)d.sh.n2; });
