@@ -373,10 +373,127 @@ tt_status seg_sum(const TTBatch &b, int kind, int chunk, int prof_kernel, hipStr
   return seg_launch(b, p, kind, nullptr, -1, prof_kernel, s);
 }
 
-// The core-2 and core-0 reductions are independent; when their vectors have the same width they
-// share their launches (the smaller one would otherwise pay two launches for a few workgroups).
+// Whole segments: ONE launch for the core-2 and the core-0 reduction.  The first nseg_a * parts_a
+// workgroups serve core 2 (rows that share i3: the index split spreads them evenly), the rest core 0,
+// `parts` workgroups per segment, each summing its own range of the vector's columns.  Cutting by
+// columns gives a long segment more lane groups -- more gathers in flight -- without a second stage:
+// a table with few i3 values has few, long core-2 segments, and under a skewed access distribution the
+// distinct prefixes pile up under the first few i1 (up to n2 prefixes times the strips each).
+// The lane groups of a workgroup take the segment's positions round-robin, TT_SEG_UNROLL gathers in
+// flight each, and their sums are added in group order through LDS, so the result does not depend on
+// timing.  (The lookups of one hot row can be a fifth of a batch, which is why the gradient merge
+// keeps the two-stage sum.)  A long segment is summed by its workgroups alone: correct, only slow.
+template <bool BATCHED, int VEC>
+__global__ void __launch_bounds__(TT_BLOCK)
+k_seg_whole(TTArg<BATCHED> arg, int nseg_a, int lanes_a, int parts_a, int lanes_b, int parts_b) {
+  const TTDev &d = arg.get();
+  const bool second = (int)blockIdx.x >= nseg_a * parts_a;
+  const SegView sv = seg_view(d, second ? SEG_DG1 : SEG_DG3);
+  const int parts = second ? parts_b : parts_a;
+  const int wg = second ? (int)blockIdx.x - nseg_a * parts_a : (int)blockIdx.x;
+  const int s = wg / parts, part = wg - s * parts;
+  if (s >= sv.nseg) return;  // uniform: a table of the batch with fewer segments
+  const int lanes = second ? lanes_b : lanes_a;
+  const int W = sv.W, nsub = sv.nsub, out_inner = sv.out_inner, nseg = sv.nseg;
+  const int Wp = W / parts, e0 = part * Wp;  // this workgroup's columns
+  const int32_t *__restrict__ gidx = sv.gidx, *__restrict__ seg_off = sv.seg_off;
+  const float *__restrict__ src = sv.src;
+  float *__restrict__ out = sv.out;
+  const int groups = blockDim.x / lanes, g = threadIdx.x / lanes, lane = threadIdx.x - g * lanes;
+  extern __shared__ float red[];  // [groups][Wp]
+  const int a = seg_off[s], b = seg_off[s + 1];
+  if (a == b) {  // uniform: an empty segment (a slice no lookup touched)
+    if (sv.dense && g == 0) {
+      Vec<VEC> z;
+      z.zero();
+      for (int e = lane * VEC; e < Wp; e += lanes * VEC) z.store(out + seg_out_index(s, e0 + e, out_inner, nseg));
+    }
+    return;
+  }
+  auto load_pos = [&](int pos, int e, Vec<VEC> &x) {
+    const int row = gidx ? gidx[pos] : pos;
+    x.load(src + (size_t)row * nsub * W + e0 + e);
+    for (int t = 1; t < nsub; ++t) {
+      Vec<VEC> y;
+      y.load(src + ((size_t)row * nsub + t) * W + e0 + e);
+      x.add(y);
+    }
+  };
+  for (int e = lane * VEC; e < Wp; e += lanes * VEC) {
+    Vec<VEC> acc;
+    acc.zero();
+    int pos = a + g;
+    for (; pos + (TT_SEG_UNROLL - 1) * groups < b; pos += TT_SEG_UNROLL * groups) {
+      Vec<VEC> x[TT_SEG_UNROLL];
+#pragma unroll
+      for (int k = 0; k < TT_SEG_UNROLL; ++k) load_pos(pos + k * groups, e, x[k]);
+#pragma unroll
+      for (int k = 0; k < TT_SEG_UNROLL; ++k) acc.add(x[k]);
+    }
+    for (; pos < b; pos += groups) {
+      Vec<VEC> x;
+      load_pos(pos, e, x);
+      acc.add(x);
+    }
+    acc.store(red + (size_t)g * Wp + e);
+  }
+  __syncthreads();
+  if (g == 0)
+    for (int e = lane * VEC; e < Wp; e += lanes * VEC) {
+      Vec<VEC> acc, x;
+      acc.load(red + e);
+      for (int k = 1; k < groups; ++k) {
+        x.load(red + (size_t)k * Wp + e);
+        acc.add(x);
+      }
+      float *dst = out + seg_out_index(s, e0 + e, out_inner, nseg);
+      if (sv.fused) acc.store_sgd(dst, sv.lr); else acc.store(dst);
+    }
+}
+
+#ifndef TT_SEG_WHOLE_PARTS
+#define TT_SEG_WHOLE_PARTS 8  // column parts of a core-0 segment
+#endif
+#ifndef TT_SEG_WHOLE_MAX_AVG
+#define TT_SEG_WHOLE_MAX_AVG 2048  // positions per segment (capacity / segments) up to which whole segments are used
+#endif
+
+// The core-2 and core-0 reductions are independent.  With segments of moderate length they take one
+// launch of whole-segment workgroups; otherwise the two-stage sum, sharing its launches when their
+// vectors have the same width (the smaller one would otherwise pay two launches for a few workgroups).
 tt_status seg_sum_dg3_dg1(const TTBatch &b, hipStream_t s) {
   const SegParams p3 = seg_params(b, SEG_DG3, 0), p1 = seg_params(b, SEG_DG1, 0);
+  bool whole = p3.vec == p1.vec;
+  for (int t = 0; t < b.T && whole; ++t) {
+    const TTDev &d = b.host[t];
+    whole = d.plan.max_rows / d.sh.n3 <= TT_SEG_WHOLE_MAX_AVG &&
+            d.plan.max_prefixes * d.strips / d.sh.n1 <= TT_SEG_WHOLE_MAX_AVG;
+  }
+  if (whole) {
+    const long long n3max = tt_batch_max(b, [](const TTDev &d) { return (long long)d.sh.n3; });
+    const long long n1max = tt_batch_max(b, [](const TTDev &d) { return (long long)d.sh.n1; });
+    // column parts per segment: core 0 as many (at most TT_SEG_WHOLE_PARTS) as leave a part 8 lanes wide;
+    // core 2 only as many as bring its workgroups to about two per compute unit
+    auto parts_for = [](const SegParams &p, int want) {
+      int parts = 1;
+      while (parts * 2 <= want && p.W % (parts * 2 * p.vec) == 0 && p.W / (parts * 2 * p.vec) >= 8) parts *= 2;
+      return parts;
+    };
+    auto lanes_for = [](const SegParams &p, int parts) {
+      int lanes = 1;
+      while (lanes < TT_WAVE && lanes * p.vec < p.W / parts) lanes <<= 1;
+      return lanes;
+    };
+    const int parts3 = parts_for(p3, tt_ceil_div(512, n3max) < TT_SEG_WHOLE_PARTS ? tt_ceil_div(512, n3max) : TT_SEG_WHOLE_PARTS);
+    const int parts1 = parts_for(p1, TT_SEG_WHOLE_PARTS);
+    const int lanes3 = lanes_for(p3, parts3), lanes1 = lanes_for(p1, parts1);
+    const size_t g3 = (size_t)(TT_BLOCK / lanes3) * (p3.W / parts3), g1 = (size_t)(TT_BLOCK / lanes1) * (p1.W / parts1);
+    const size_t lds = sizeof(float) * (g3 > g1 ? g3 : g1);
+    const long long grid = n3max * parts3 + n1max * parts1;
+    if (p3.vec == 4) TT_LAUNCH_T(k_seg_whole, 4, grid, TT_BLOCK, lds, s, b, (int)n3max, lanes3, parts3, lanes1, parts1);
+    else TT_LAUNCH_T(k_seg_whole, 1, grid, TT_BLOCK, lds, s, b, (int)n3max, lanes3, parts3, lanes1, parts1);
+    return tt_launch_status();
+  }
   if (p3.W == p1.W && p3.vec == p1.vec && p3.lanes == p1.lanes && p3.blocks1 > 0 && p1.blocks1 > 0)
     return seg_launch(b, p3, SEG_DG3, &p1, SEG_DG1, -1, s);
   tt_status st = seg_launch(b, p3, SEG_DG3, nullptr, -1, -1, s);
