@@ -362,7 +362,7 @@ k_radix_scatter(TTArg<BATCHED> a, int which, int in_a, int shift, int bits, int 
 #define TT_UNIQ_ITEMS 4
 #define TT_UNIQ_TILE (TT_BLOCK * TT_UNIQ_ITEMS)
 #define TT_UNIQ_SELF_SCAN_TILES 1024  // up to this many tiles k_uniq_emit does without k_uniq_scan
-#define TT_GROUP_MAX_TILES 64         // up to this many tiles of distinct rows the groupings take one launch
+#define TT_GROUP_MAX_TILES 512        // up to this many tiles of (capacity for) distinct rows the groupings take one launch
 
 __device__ __forceinline__ void head_flags(const int32_t *__restrict__ keys, int s, int nnz,
                                            int sentinel, int n3, int &hr, int &hp) {
@@ -577,6 +577,9 @@ __device__ __forceinline__ void counting_sort_tile(CountingSortLds &L, const int
   int (*wave_cnt)[MAXB] = L.wave_cnt;
   const int nbins = 1 << bits, base = tile * TT_SORT_TILE;
   const int lane = threadIdx.x & (TT_WAVE - 1), wave = threadIdx.x / TT_WAVE;
+  // uniform: the launch is sized by the capacity; a tile past the actual count has nothing to place
+  // (tile 0 still writes the segment starts)
+  if (base >= count && tile != 0) return;
   for (int b = threadIdx.x; b < nbins; b += TT_BLOCK) { gofs[b] = 0; pre[b] = 0; }
   __syncthreads();
   {  // four sources in flight per thread (src is 16-byte aligned: four items per load)
