@@ -131,8 +131,7 @@ k_seg_stage1(TTArg<BATCHED> arg, SegLaunch L, int lanes) {
   const int chunk = pk.chunk;
   const SegView sv = seg_view(arg.get(), pk.kind);
   const int W = sv.W, seg_div = sv.seg_div, nsub = sv.nsub, out_inner = sv.out_inner, nseg = sv.nseg;
-  const int32_t *__restrict__ seg_src = sv.seg_src, *__restrict__ gidx = sv.gidx,
-                *__restrict__ seg_off = sv.seg_off;
+  const int32_t *__restrict__ seg_src = sv.seg_src, *__restrict__ gidx = sv.gidx;
   const float *__restrict__ src = sv.src;
   float *__restrict__ out = sv.out, *__restrict__ partial = sv.partial + pk.poff;
   const int M = *sv.count_ptr;
@@ -147,19 +146,28 @@ k_seg_stage1(TTArg<BATCHED> arg, SegLaunch L, int lanes) {
     // every lane group see the same thing, so `merged` is uniform over the workgroup
     const int block_lo = (c - g) * chunk, block_hi = block_lo + groups * chunk;
     bool merged = false;
+    // segment ids just outside the chunk and just outside the workgroup's range (-1 / -2: nothing there)
+    const int s_before = lo > 0 ? seg_src[lo - 1] / seg_div : -1;
+    const int s_after = hi < M ? seg_src[hi] / seg_div : -2;
+    const int s_blk_before = block_lo > 0 ? seg_src[block_lo - 1] / seg_div : -1;
+    const int s_blk_after = block_hi < M ? seg_src[block_hi] / seg_div : -2;
     for (int e = lane * VEC; e < W; e += lanes * VEC) {
       Vec<VEC> acc;
       acc.zero();
       int cur = -1;
-      auto flush = [&]() {
-        const int a = seg_off[cur], b = seg_off[cur + 1];
-        if (a >= lo && b <= hi) {
+      // Where a finished run goes is decided from the segment ids next to the chunk and next to the
+      // workgroup's range (ids are non-decreasing), not from the segment's offsets: those would be two
+      // dependent loads at every segment change.  `at_end`: the run reaches the chunk's last position.
+      auto flush = [&](bool at_end) {
+        const bool starts_in = cur != s_before;          // the segment begins inside the chunk
+        const bool ends_in = !at_end || cur != s_after;  // ... and ends inside it
+        if (starts_in && ends_in) {
           float *dst = out + seg_out_index(cur, e, out_inner, nseg);
           if (fused) acc.store_sgd(dst, lr); else acc.store(dst);
-        } else if (a < block_lo && b > block_hi) {  // one partial for the whole workgroup, summed below
-          acc.store(red + (size_t)g * W + e);
+        } else if (cur == s_blk_before && cur == s_blk_after) {  // it covers the workgroup's whole range:
+          acc.store(red + (size_t)g * W + e);                      // one partial for the workgroup, summed below
           merged = true;
-        } else acc.store(partial + ((size_t)c * 2 + (a < lo ? 0 : 1)) * W + e);
+        } else acc.store(partial + ((size_t)c * 2 + (starts_in ? 1 : 0)) * W + e);
       };
       int pos = lo;
       for (; pos + TT_SEG_UNROLL <= end; pos += TT_SEG_UNROLL) {  // independent gathers in flight,
@@ -179,7 +187,7 @@ k_seg_stage1(TTArg<BATCHED> arg, SegLaunch L, int lanes) {
 #pragma unroll
         for (int k = 0; k < TT_SEG_UNROLL; ++k) {
           if (sg[k] != cur) {
-            if (cur >= 0) flush();
+            if (cur >= 0) flush(false);
             cur = sg[k];
             acc.zero();
           }
@@ -197,13 +205,13 @@ k_seg_stage1(TTArg<BATCHED> arg, SegLaunch L, int lanes) {
           x.add(y);
         }
         if (sgk != cur) {
-          if (cur >= 0) flush();
+          if (cur >= 0) flush(false);
           cur = sgk;
           acc.zero();
         }
         acc.add(x);
       }
-      if (cur >= 0) flush();
+      if (cur >= 0) flush(true);
     }
     if (merged) {  // uniform: the chunks' sums in chunk order -> slot 0 of the workgroup's first chunk
       __syncthreads();
@@ -373,6 +381,9 @@ tt_status seg_sum(const TTBatch &b, int kind, int chunk, int prof_kernel, hipStr
   return seg_launch(b, p, kind, nullptr, -1, prof_kernel, s);
 }
 
+#ifndef TT_SEG_WHOLE_UNROLL
+#define TT_SEG_WHOLE_UNROLL TT_SEG_UNROLL  // gathers a lane group of the whole-segment kernel keeps in flight
+#endif
 // Whole segments: ONE launch for the core-2 and the core-0 reduction.  The first nseg_a * parts_a
 // workgroups serve core 2 (rows that share i3: the index split spreads them evenly), the rest core 0,
 // `parts` workgroups per segment, each summing its own range of the vector's columns.  Cutting by
@@ -423,12 +434,12 @@ k_seg_whole(TTArg<BATCHED> arg, int nseg_a, int lanes_a, int parts_a, int lanes_
     Vec<VEC> acc;
     acc.zero();
     int pos = a + g;
-    for (; pos + (TT_SEG_UNROLL - 1) * groups < b; pos += TT_SEG_UNROLL * groups) {
-      Vec<VEC> x[TT_SEG_UNROLL];
+    for (; pos + (TT_SEG_WHOLE_UNROLL - 1) * groups < b; pos += TT_SEG_WHOLE_UNROLL * groups) {
+      Vec<VEC> x[TT_SEG_WHOLE_UNROLL];
 #pragma unroll
-      for (int k = 0; k < TT_SEG_UNROLL; ++k) load_pos(pos + k * groups, e, x[k]);
+      for (int k = 0; k < TT_SEG_WHOLE_UNROLL; ++k) load_pos(pos + k * groups, e, x[k]);
 #pragma unroll
-      for (int k = 0; k < TT_SEG_UNROLL; ++k) acc.add(x[k]);
+      for (int k = 0; k < TT_SEG_WHOLE_UNROLL; ++k) acc.add(x[k]);
     }
     for (; pos < b; pos += groups) {
       Vec<VEC> x;

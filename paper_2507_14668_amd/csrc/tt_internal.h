@@ -41,7 +41,9 @@ struct TTShape {
 // ---- segmented-reduction geometry -----------------------------------------------------------
 #define TT_SEG_MIN_CHUNK 8   // smallest stage-1 chunk of the two-stage segmented sum (sizes the partials)
 #define TT_SEG_MAX_CHUNK 64
-#define TT_SEG_UNROLL 8      // gathers a lane group keeps in flight
+#ifndef TT_SEG_UNROLL
+#define TT_SEG_UNROLL 4      // gathers a lane group keeps in flight (8 and 16 measured slower: fewer resident lane groups)
+#endif
 
 static inline int tt_ceil_div(long long a, long long b) { return (int)((a + b - 1) / b); }
 
