@@ -599,13 +599,14 @@ tt_status launch(const TTBatch &b, hipStream_t s) {
   const long long blocks = tt_batch_max(b, [](const TTDev &d) {
     return (long long)((d.sh.n2 + 7) & ~7) * G::NSB * d.bwd_split; });
   {
-    TTProfScope prof(&b.host[0].plan, TT_KERNEL_BWD_CONTRACT, s);  // the contraction kernel alone
+    // the contraction kernel alone, timed by its own begin and end stamps when a profile object asks
+    TTProfScope prof(&b.host[0].plan, TT_KERNEL_BWD_CONTRACT, s, false);
     if (b.dev)
-      hipLaunchKernelGGL((k_bwd_mfma<true, R1, R2>), dim3((unsigned)blocks, (unsigned)b.T),
-                         dim3(NTHR), lds, s, TTArg<true>{b.dev});
+      hipExtLaunchKernelGGL((k_bwd_mfma<true, R1, R2>), dim3((unsigned)blocks, (unsigned)b.T),
+                            dim3(NTHR), lds, s, prof.start(), prof.stop(), 0, TTArg<true>{b.dev});
     else
-      hipLaunchKernelGGL((k_bwd_mfma<false, R1, R2>), dim3((unsigned)blocks), dim3(NTHR), lds, s,
-                         TTArg<false>{b.host[0]});
+      hipExtLaunchKernelGGL((k_bwd_mfma<false, R1, R2>), dim3((unsigned)blocks), dim3(NTHR), lds, s,
+                            prof.start(), prof.stop(), 0, TTArg<false>{b.host[0]});
   }
   if (tt_batch_max(b, [](const TTDev &d) { return (long long)d.bwd_split; }) > 1) {
     const int tiles = tt_ceil_div((long long)R1 * G::S2, TT_BLOCK * 4);

@@ -334,13 +334,14 @@ tt_status launch(const TTBatch &b, hipStream_t s) {
   int split = (int)(TT_FWD_WG_TARGET / (n2p8 * G::NSTRIP));
   split = split < 1 ? 1 : (split > TT_FWD_MAX_SPLIT ? TT_FWD_MAX_SPLIT : split);
   const long long blocks = n2p8 * G::NSTRIP * split;
-  TTProfScope prof(&b.host[0].plan, P12OUT ? TT_KERNEL_P12_FILL : TT_KERNEL_FWD_CONTRACT, s);
+  // timed by the kernel's own begin and end stamps when a profile object asks
+  TTProfScope prof(&b.host[0].plan, P12OUT ? TT_KERNEL_P12_FILL : TT_KERNEL_FWD_CONTRACT, s, false);
   if (b.dev)
-    hipLaunchKernelGGL((k_fwd_mfma<true, R1, R2, D2, P12OUT, BF16>), dim3((unsigned)blocks, (unsigned)b.T),
-                       dim3(FTHR), lds, s, TTArg<true>{b.dev}, split);
+    hipExtLaunchKernelGGL((k_fwd_mfma<true, R1, R2, D2, P12OUT, BF16>), dim3((unsigned)blocks, (unsigned)b.T),
+                          dim3(FTHR), lds, s, prof.start(), prof.stop(), 0, TTArg<true>{b.dev}, split);
   else
-    hipLaunchKernelGGL((k_fwd_mfma<false, R1, R2, D2, P12OUT, BF16>), dim3((unsigned)blocks), dim3(FTHR), lds, s,
-                       TTArg<false>{b.host[0]}, split);
+    hipExtLaunchKernelGGL((k_fwd_mfma<false, R1, R2, D2, P12OUT, BF16>), dim3((unsigned)blocks), dim3(FTHR), lds, s,
+                          prof.start(), prof.stop(), 0, TTArg<false>{b.host[0]}, split);
   return tt_launch_status();
 }
 

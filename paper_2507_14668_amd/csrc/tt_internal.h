@@ -3,6 +3,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "tt_emb.h"
@@ -203,16 +204,23 @@ struct tt_prof {
 struct TTProfScope {
   tt_prof *p;
   hipStream_t s;
-  TTProfScope(const tt_plan *plan, int kernel, hipStream_t stream) : p(nullptr), s(stream) {
+  bool record;
+  // record = false: the scope only hands out the event pair (start(), stop()) for ONE launch made with
+  // hipExtLaunchKernelGGL, which stamps them with that kernel's own begin and end -- the duration a
+  // kernel trace reports, without the dispatch gap an event recorded in front of the launch includes.
+  TTProfScope(const tt_plan *plan, int kernel, hipStream_t stream, bool record_events = true)
+      : p(nullptr), s(stream), record(record_events) {
     tt_prof *q = plan ? (tt_prof *)plan->prof : nullptr;
     if (q && q->kernel == kernel && q->used < q->capacity) {
       p = q;
-      (void)hipEventRecord(p->ev[2 * p->used], s);
+      if (record) (void)hipEventRecord(p->ev[2 * p->used], s);
     }
   }
+  hipEvent_t start() const { return p ? p->ev[2 * p->used] : nullptr; }
+  hipEvent_t stop() const { return p ? p->ev[2 * p->used + 1] : nullptr; }
   ~TTProfScope() {
     if (p) {
-      (void)hipEventRecord(p->ev[2 * p->used + 1], s);
+      if (record) (void)hipEventRecord(p->ev[2 * p->used + 1], s);
       ++p->used;
     }
   }

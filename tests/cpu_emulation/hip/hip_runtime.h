@@ -58,6 +58,9 @@ void wave_mfma_16x16x4(float a, float b, float *c4);
 #define hipLaunchKernelGGL(kernel, grid, block, lds, stream, ...) \
   emu::launch(grid, block, lds, #kernel, [=]() { kernel(__VA_ARGS__); })
 
+#define hipExtLaunchKernelGGL(kernel, grid, block, lds, stream, start_event, stop_event, flags, ...) \
+  emu::launch(grid, block, lds, #kernel, [=]() { kernel(__VA_ARGS__); })
+
 static inline hipError_t hipGetLastError() { return hipSuccess; }
 static inline hipError_t hipGetDevice(int *dev) { *dev = 0; return hipSuccess; }
 enum { hipDeviceAttributeMultiprocessorCount = 1 };
