@@ -748,15 +748,19 @@ tt_status radix_sort(const TTBatch &b, int which, int max_tiles, int key_bits, h
     const int self_scan = max_tiles <= TT_SELF_SCAN_TILES ? 1 : 0;
     const bool main_sort = status_tiles > 0;
     const int status = (main_sort && p == 0) ? 1 : 0;
-    // the main sort never launches a histogram kernel: pass 0 was counted while the keys were
-    // extracted, pass p + 1 is counted by the scatter of pass p
+    // The main sort finds the histogram of pass 0 already there (counted while the keys were extracted).
+    // Short main sorts, whose cost is launches, also let the scatter of pass p count pass p + 1 (atomic
+    // additions per destination tile); long ones keep the histogram launch, which is cheaper than the
+    // atomics from a few hundred tiles on (335 k keys: 4.4 us against 13 us more per scatter).
+    const bool count_next = main_sort && max_tiles <= TT_SELF_SCAN_TILES;
     const int pass = main_sort ? p : 0;
     int next_bits = 0;
-    if (main_sort && p + 1 < rp.passes) {
+    if (count_next && p + 1 < rp.passes) {
       const int left = key_bits - shift - bits;
       next_bits = left < rp.bits_per_pass ? left : rp.bits_per_pass;
     }
-    if (!main_sort) TT_LAUNCH(k_radix_hist, max_tiles, TT_BLOCK, 0, s, b, which, in_a, shift, bits, 0);
+    if (!main_sort || (p > 0 && !count_next))
+      TT_LAUNCH(k_radix_hist, max_tiles, TT_BLOCK, 0, s, b, which, in_a, shift, bits, pass);
     if (!self_scan) TT_LAUNCH(k_radix_binscan, 1 << bits, TT_BLOCK, 0, s, b, which, 1 << bits, pass);
     {
       TTProfScope prof(which == 0 ? &b.host[0].plan : nullptr, TT_KERNEL_SORT_SCATTER, s);
