@@ -60,7 +60,8 @@ tt_status ttk_cores_to_bf16(const TTShape &sh, const float *const core[3], void 
   const long long elems = (long long)sh.n1 * sh.S1 + (long long)sh.R1 * sh.n2 * sh.S2 + (long long)sh.R2 * sh.n3 * sh.d3;
   long long blocks = (elems + TT_BLOCK - 1) / TT_BLOCK;
   if (blocks > 8192) blocks = 8192;
-  hipLaunchKernelGGL(k_cores_to_bf16, dim3((unsigned)blocks), dim3(TT_BLOCK), 0, s, sh, core[0], core[1], core[2],
+  const float *c0 = core[0], *c1 = core[1], *c2 = core[2];  // read the host array here, not in the launch expression
+  hipLaunchKernelGGL(k_cores_to_bf16, dim3((unsigned)blocks), dim3(TT_BLOCK), 0, s, sh, c0, c1, c2,
                      (unsigned short *)(base + off[0]), (unsigned short *)(base + off[1]),
                      (unsigned short *)(base + off[2]));
   return tt_launch_status();

@@ -39,6 +39,10 @@ def _generate(gen: str) -> list:
         text = open(os.path.join(CSRC, u + ".hip")).read()
         text = re.sub(r"extern __shared__ float (\w+)\[\];", r"float *\1 = (float *)emu::dyn_lds();", text)
         text = text.replace("kBatchedCallsEnabled = false", "kBatchedCallsEnabled = true")
+        # the host copies of the table descriptors are for the host only: kernels get the uploaded array
+        text = text.replace("  if (!host) return TT_ERR_INVALID_ARG;\n",
+                            "  if (!host) return TT_ERR_INVALID_ARG;\n  emu::host_only(host, (size_t)T * sizeof(TTDev));\n")
+        text = text.replace("  free(host);\n  return st;", "  emu::host_only_release(host);\n  free(host);\n  return st;")
         path = os.path.join(gen, u + ".cpp")
         open(path, "w").write(text)
         out.append(path)

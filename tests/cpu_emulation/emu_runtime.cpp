@@ -243,6 +243,35 @@ void ensure_pool() {
 }
 }  // namespace
 
+// Host-only regions: memory a kernel must never touch (host structs of the C ABI, the host copies of
+// the table descriptors).  With AddressSanitizer they are poisoned for the duration of every launch, so
+// a kernel that dereferences a host pointer -- which works on the CPU and faults on a GPU -- is reported.
+#if defined(__has_feature)
+#if __has_feature(address_sanitizer)
+#define EMU_ASAN 1
+extern "C" void __asan_poison_memory_region(void const volatile *addr, size_t size);
+extern "C" void __asan_unpoison_memory_region(void const volatile *addr, size_t size);
+#endif
+#endif
+namespace {
+struct HostOnly { const void *p; size_t n; };
+std::vector<HostOnly> host_only_regions;
+void poison_host_only(bool on) {
+#ifdef EMU_ASAN
+  for (const HostOnly &r : host_only_regions) {
+    if (on) __asan_poison_memory_region(r.p, r.n); else __asan_unpoison_memory_region(r.p, r.n);
+  }
+#else
+  (void)on;
+#endif
+}
+}  // namespace
+void host_only(const void *p, size_t n) { host_only_regions.push_back({p, n}); }
+void host_only_release(const void *p) {
+  for (size_t i = 0; i < host_only_regions.size(); ++i)
+    if (host_only_regions[i].p == p) { host_only_regions.erase(host_only_regions.begin() + i); return; }
+}
+
 void launch(dim3 grid, dim3 block, size_t lds, const char *name, const std::function<void()> &body) {
   ensure_pool();
   if (block.x > NW * WL || block.y != 1 || block.z != 1 || grid.x == 0 || grid.y == 0) {
@@ -255,8 +284,22 @@ void launch(dim3 grid, dim3 block, size_t lds, const char *name, const std::func
   if (g_lds) memset(g_lds, 0x7F, lds);   // defined garbage (NaN pattern): uninitialised-read hunts target global memory
   // EMU_REVERSE runs the workgroups of a launch last to first: results must not depend on the order
   static const bool reverse = getenv("EMU_REVERSE") != nullptr;
-  for (unsigned by = 0; by < grid.y; ++by)
-    for (unsigned bi = 0; bi < grid.x; ++bi) {
+  // EMU_SHUFFLE=<seed> runs them in a seeded random order over BOTH grid dimensions, so that the
+  // workgroups of different tables of a batched launch are interleaved
+  static const char *shuffle = getenv("EMU_SHUFFLE");
+  std::vector<unsigned> order((size_t)grid.x * grid.y);
+  for (size_t i = 0; i < order.size(); ++i) order[i] = (unsigned)i;
+  if (shuffle) {
+    static uint64_t rs = 0x9E3779B97F4A7C15ull ^ strtoull(shuffle, nullptr, 0);
+    for (size_t i = order.size(); i > 1; --i) {
+      rs ^= rs << 13; rs ^= rs >> 7; rs ^= rs << 17;
+      std::swap(order[i - 1], order[(size_t)(rs % i)]);
+    }
+  }
+  poison_host_only(true);
+  for (size_t oi = 0; oi < order.size(); ++oi) {
+    {
+      const unsigned by = order[oi] / grid.x, bi = order[oi] % grid.x;
       const unsigned bx = reverse ? grid.x - 1 - bi : bi;
       g_blockIdx = dim3(bx, by, 0);
       int nwaves = 0;
@@ -270,6 +313,8 @@ void launch(dim3 grid, dim3 block, size_t lds, const char *name, const std::func
       start_gen.fetch_add(1, std::memory_order_release);
       { int n = 0; while (done_count.load(std::memory_order_acquire) != NW) spin_pause(n); }
     }
+  }
+  poison_host_only(false);
   free(g_lds);
   g_lds = nullptr;
 }

@@ -11,6 +11,9 @@
 #include <vector>
 #include "tt_emb.h"
 
+// regions the kernels must never touch (host structs of the C ABI): poisoned while a launch runs
+namespace emu { void host_only(const void *p, size_t n); void host_only_release(const void *p); }
+
 static int g_off = 0;  // floats by which core and gradient pointers are shifted off their alignment
 static uint64_t rs = 88172645463325252ull;
 static uint32_t rnd() { rs ^= rs << 13; rs ^= rs >> 7; rs ^= rs << 17; return (uint32_t)(rs >> 11); }
@@ -110,6 +113,7 @@ int main(int argc, char **argv) {
     fprintf(stderr, "index-graph edges: %d pairs -> %d edges\n", counts[0], counts[1]);
     free(ws);
   }
+  for (auto &B : tabs) emu::host_only(&B.t, sizeof(B.t));
   const int T = (int)tabs.size();
   const float lr = 0.01f;
   for (int planned = 1; planned >= 0; --planned) {
@@ -121,6 +125,7 @@ int main(int argc, char **argv) {
       Tab &B = tabs[t];
       for (int k = 0; k < 3; ++k) { B.core[k] = B.core0[k]; B.t.core[k] = B.core[k].data() + g_off; }
       tt_plan plan; memset(&plan, 0, sizeof(plan));
+      emu::host_only(&plan, sizeof(plan));
       void *ws = nullptr;
       if (planned) {
         size_t wb = tt_workspace_bytes(&B.t, B.nnz, B.bags);
@@ -181,6 +186,7 @@ int main(int argc, char **argv) {
             return 3;
           }
       }
+      emu::host_only_release(&plan);
       free(ws);
       fprintf(stderr, "single table %d done\n", t);
     }
@@ -190,6 +196,8 @@ int main(int argc, char **argv) {
     std::vector<void *> wss(T, nullptr);
     size_t db = tt_batch_desc_bytes(T);
     void *desc = amalloc(db);
+    emu::host_only(items.data(), items.size() * sizeof(tt_batch_item));
+    emu::host_only(plans.data(), plans.size() * sizeof(tt_plan));
     for (int t = 0; t < T; ++t) {
       Tab &B = tabs[t];
       for (int k = 0; k < 3; ++k) { B.core[k] = B.core0[k]; B.t.core[k] = B.core[k].data() + g_off; }
@@ -241,6 +249,8 @@ int main(int argc, char **argv) {
       for (int t = 0; t < T; ++t) { mix(single[t].out); for (int k = 0; k < 3; ++k) { mix(single[t].dg[k]); mix(single[t].core[k]); } }
       fprintf(stderr, "checksum of single-table results: %016llx\n", (unsigned long long)h);
     }
+    emu::host_only_release(items.data());
+    emu::host_only_release(plans.data());
     for (void *w : wss) free(w);
     free(desc);
     fprintf(stderr, "== kind %s planned %d: %s\n", kind, planned, bad ? "MISMATCH" : "identical");

@@ -35,6 +35,8 @@ namespace emu {
 extern thread_local dim3 t_threadIdx;
 extern dim3 g_blockIdx, g_blockDim, g_gridDim;
 void launch(dim3 grid, dim3 block, size_t lds, const char *name, const std::function<void()> &body);
+void host_only(const void *p, size_t n);   // a region kernels must not touch: poisoned (ASan) while a launch runs
+void host_only_release(const void *p);
 void syncthreads();
 void *dyn_lds();
 uint64_t wave_exchange(uint64_t v, int src_lane);          // value of lane src_lane (own lane if out of range)

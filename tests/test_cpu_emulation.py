@@ -181,9 +181,16 @@ def asan_harness():
     return emu_build.build_harness(BUILD_DIR, "address")
 
 
-@pytest.mark.parametrize("kind", ["mfma", "plain", "unaligned"])
-def test_sanitized_single_and_batched_calls(asan_harness, kind):
+@pytest.mark.parametrize("kind,shuffle", [("mfma", None), ("plain", None), ("unaligned", None), ("mfma", "11"), ("plain", "12")])
+def test_sanitized_single_and_batched_calls(asan_harness, kind, shuffle):
+    """Every entry point under AddressSanitizer + UBSan.  While a launch runs, the host structs of the
+    C ABI (tables, plans, batch items) and the library's host copies of the table descriptors are
+    poisoned: a kernel that followed a host pointer -- harmless on the CPU, a fault on a GPU -- is
+    reported.  With `shuffle` the workgroups of every launch run in a seeded random order over both grid
+    dimensions, so that the tables of a batched launch are interleaved."""
     env = dict(os.environ, ASAN_OPTIONS="detect_stack_use_after_return=0:detect_leaks=0", UBSAN_OPTIONS="halt_on_error=1")
+    if shuffle:
+        env["EMU_SHUFFLE"] = shuffle
     res = subprocess.run([asan_harness, kind], capture_output=True, text=True, env=env, timeout=600)
     text = res.stdout + res.stderr
     assert res.returncode == 0, text[-4000:]
