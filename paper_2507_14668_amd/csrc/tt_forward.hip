@@ -111,7 +111,38 @@ k_bag_sum(TTArg<BATCHED> a, int lanes) {
   float *__restrict__ out = d.out;
   const int groups_per_block = blockDim.x / lanes;
   const int g = threadIdx.x / lanes, lane = threadIdx.x - g * lanes;
-  for (int b = blockIdx.x * groups_per_block + g; b < num_bags; b += gridDim.x * groups_per_block) {
+  const int stride = gridDim.x * groups_per_block;
+  int b = blockIdx.x * groups_per_block + g;
+  // One-lookup bags (one-hot features), four bags of a lane group at a time: the four chains
+  // offsets -> row slot -> row -> store are independent and overlap.  Same arithmetic as the general
+  // path below (0 + row), so the result does not depend on which path served a bag.
+  for (; b + 3 * stride < num_bags; b += 4 * stride) {
+    long long o[4][2];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) { o[k][0] = offsets[b + k * stride]; o[k][1] = offsets[b + k * stride + 1]; }
+    bool single = true;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) single = single && o[k][0] >= 0 && o[k][0] < nnz && o[k][1] == o[k][0] + 1;
+    if (!single) break;  // the general path takes over from bag b (the same for every lane of the group)
+    int u[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) u[k] = lookup2row[o[k][0]];
+    for (int c = lane * VEC; c < D; c += lanes * VEC) {
+      float x[4][VEC];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) load_row_vec<VEC>(rowbuf, u[k], D, c, x[k]);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        float t[VEC];
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) t[v] = 0.f + (0.f + x[k][v]);
+        float *dst = out + (size_t)(b + k * stride) * D + c;
+        if (VEC == 4) *reinterpret_cast<float4 *>(dst) = make_float4(t[0], t[1 % VEC], t[2 % VEC], t[3 % VEC]);
+        else dst[0] = t[0];
+      }
+    }
+  }
+  for (; b < num_bags; b += stride) {
     // offsets are clamped to [0, nnz] so that a malformed CSR array cannot index out of bounds
     const long long o0 = offsets[b], o1 = offsets[b + 1];
     const int l0 = o0 < 0 ? 0 : (o0 > nnz ? nnz : (int)o0), l1 = o1 < l0 ? l0 : (o1 > nnz ? nnz : (int)o1);
@@ -240,6 +271,10 @@ tt_status ttk_bag_sum(const TTBatch &b, hipStream_t s) {
     while (lanes < TT_WAVE && lanes * (vec4 ? 4 : 1) < sh.D) lanes <<= 1;
     const int groups = TT_BLOCK / lanes;
     long long blocks = (max_bags + groups - 1) / groups;
+    // a batch of one-lookup bags (as many lookups as bags) lets every lane group take four bags at a time
+    bool one_hot = true;
+    for (int t = 0; t < b.T; ++t) one_hot = one_hot && b.host[t].nnz == b.host[t].num_bags;
+    if (one_hot) blocks = (blocks + 3) / 4;
     if (blocks > 16384) blocks = 16384;
     TTProfScope prof(&b.host[0].plan, TT_KERNEL_BAG_SUM, s);
     if (vec4) TT_LAUNCH_T(k_bag_sum, 4, blocks, TT_BLOCK, 0, s, b, lanes);

@@ -141,6 +141,24 @@ def test_emulated_kernels_match_oracle(emu, ora, name, n, d, r, nb, ml):
         assert np.array_equal(res["fused"][k], res["updated"][k]), "fused update differs from backward + update"
 
 
+def test_emulated_one_hot_batch_and_mixed_bag_lengths(emu, ora):
+    """One lookup per bag (the bag sum takes four bags of a lane group at a time) and a batch whose bags
+    hold zero or one lookup (the fast path gives way to the general one wherever a bag is not single)."""
+    import gpu_util as g
+    shape, cores, _, _, _ = wl.small_random_problem(41, n=(5, 4, 6), d=(2, 3, 2), r=(1, 3, 5, 1))
+    rng = np.random.default_rng(5)
+    for nb, lens in ((1500, None), (1100, rng.integers(0, 2, 1100))):
+        lens = np.ones(nb, np.int64) if lens is None else lens
+        off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+        idx = rng.integers(0, shape.num_rows, int(off[-1])).astype(np.int64)
+        grad = rng.standard_normal(nb * shape.dim).astype(np.float32)
+        res = _run(emu, shape, cores, idx, off, grad, 0.05)
+        ref_out = ora.forward(shape, cores, idx, off)
+        for arm in ("plan", "naive"):
+            g.assert_close_rows(res[arm][0], ref_out, g.FWD_RTOL, shape.dim, "one-hot forward (%s)" % arm)
+        g.assert_grads_close(shape, res["plan"][1], ora.backward(shape, cores, idx, off, grad), what="one-hot dG")
+
+
 @pytest.mark.parametrize("nb,ml,rows,hot,max_group", [(300, 9, 400, 5, 64), (40, 300, 3000, 0, 16), (200, 5, 50, 45, 64)])
 def test_emulated_index_graph_edges_match_oracle(emu, ora, nb, ml, rows, hot, max_group):
     """The edge-generation job (pairs per bag, two stable radix sorts, run heads) against the loop oracle:
