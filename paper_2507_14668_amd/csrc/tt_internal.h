@@ -40,7 +40,9 @@ struct TTShape {
 #define TT_MP 8  // distinct prefixes per chunk: two 16-row MFMA tiles of (prefix, j1) rows
 
 // ---- segmented-reduction geometry -----------------------------------------------------------
+#ifndef TT_SEG_MIN_CHUNK
 #define TT_SEG_MIN_CHUNK 8   // smallest stage-1 chunk of the two-stage segmented sum (sizes the partials)
+#endif
 #define TT_SEG_MAX_CHUNK 64
 #ifndef TT_SEG_UNROLL
 #define TT_SEG_UNROLL 4      // gathers a lane group keeps in flight (8 and 16 measured slower: fewer resident lane groups)

@@ -582,8 +582,8 @@ __device__ __forceinline__ void counting_sort_tile(CountingSortLds &L, const int
   if (base >= count && tile != 0) return;
   for (int b = threadIdx.x; b < nbins; b += TT_BLOCK) { gofs[b] = 0; pre[b] = 0; }
   __syncthreads();
-  {  // four sources in flight per thread (src is 16-byte aligned: four items per load)
-    constexpr int INFLIGHT = 4;
+  {  // eight loads in flight per thread (src is 16-byte aligned: four items per load)
+    constexpr int INFLIGHT = 8;
     for (int p4 = threadIdx.x * 4; p4 < count; p4 += TT_BLOCK * 4 * INFLIGHT) {
       int4 v[INFLIGHT];
 #pragma unroll
