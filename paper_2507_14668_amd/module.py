@@ -11,6 +11,13 @@ Two ways to train:
     torch.optim optimizer can be used;
   * `fused_sgd_lr=lr`: backward applies `G <- G - lr * dG` inside the backward kernels
     (Section III-F, fused TT-core update) and reports no gradient for the cores.
+
+Two more forward routes of the library are selectable:
+  * `forward_route="sample"`: sample-level reuse (Section III-B reuse equation) on top of the reuse
+    buffer of prefix products -- same bag sums, one chain per (bag, prefix) group; backward is
+    unchanged (it only needs the plan);
+  * `bf16_inference()` / `forward_bf16(...)`: forward on bf16 copies of the cores with fp32
+    accumulation, for inference (no gradient); the copies are refreshed on request.
 """
 from __future__ import annotations
 
@@ -24,7 +31,10 @@ class _TTBagFunction(torch.autograd.Function):
     def forward(ctx, core0, core1, core2, indices, offsets, module):
         table = module._table((core0, core1, core2))
         plan = binding.tt_index_reorder(table, indices, offsets)
-        out = binding.tt_emb_bag_forward(table, plan, indices, offsets)
+        if module.forward_route == "sample":
+            out = binding.tt_emb_bag_forward_sample(table, plan, offsets)
+        else:
+            out = binding.tt_emb_bag_forward(table, plan, indices, offsets)
         ctx.module, ctx.table, ctx.plan = module, table, plan
         ctx.save_for_backward(indices, offsets)
         return out
@@ -57,7 +67,7 @@ class TTEmbeddingBag(torch.nn.Module):
 
     def __init__(self, num_embeddings: int, embedding_dim: int, n, d, ranks, mode: str = "sum",
                  include_last_offset: bool = False, init_row_std: float = 0.1, fused_sgd_lr=None,
-                 device="cuda", generator=None):
+                 forward_route: str = "batch", device="cuda", generator=None):
         super().__init__()
         if mode != "sum":
             raise NotImplementedError("only sum pooling is defined for the TT embedding bag")
@@ -72,6 +82,10 @@ class TTEmbeddingBag(torch.nn.Module):
         self.n, self.d, self.r = n, d, (1, ranks[0], ranks[1], 1)
         self.include_last_offset = bool(include_last_offset)
         self.fused_sgd_lr = None if fused_sgd_lr is None else float(fused_sgd_lr)
+        if forward_route not in ("batch", "sample"):
+            raise ValueError("forward_route is 'batch' (each distinct row once, then a bag sum) or 'sample'")
+        self.forward_route = forward_route
+        self._bf16_cores = None
         # a row entry is a sum of R1*R2 products of three core entries: choose the core scale so that
         # the rows start with standard deviation `init_row_std`
         s = (init_row_std ** 2 / (ranks[0] * ranks[1])) ** (1.0 / 6.0)
@@ -110,6 +124,24 @@ class TTEmbeddingBag(torch.nn.Module):
             input = input.to(torch.int64)
         indices, offsets = self._bag_offsets(input, offsets)
         return _TTBagFunction.apply(self.core0, self.core1, self.core2, indices, offsets, self)
+
+    def bf16_inference(self):
+        """(Re)build the bf16 copies of the cores that `forward_bf16` reads; call again after the cores
+        have changed.  Only for shapes the matrix-core kernels serve (the library refuses others)."""
+        self._bf16_cores = binding.tt_cores_to_bf16(self._table(self.cores()))
+        return self
+
+    @torch.no_grad()
+    def forward_bf16(self, input, offsets=None):
+        """Inference forward on the bf16 copies of the cores (fp32 accumulation); no autograd graph."""
+        if self._bf16_cores is None:
+            self.bf16_inference()
+        if input.dtype != torch.int64:
+            input = input.to(torch.int64)
+        indices, offsets = self._bag_offsets(input, offsets)
+        table = self._table(self.cores())
+        plan = binding.tt_index_reorder(table, indices, offsets)
+        return binding.tt_emb_bag_forward_bf16(table, self._bf16_cores, plan, offsets)
 
     def extra_repr(self) -> str:
         return "%d x %d, n=%s, d=%s, ranks=%s, %.1fx smaller than dense%s" % (

@@ -136,3 +136,35 @@ def test_collection_on_side_streams_equals_single_modules(g):
         results.append(([o.detach().clone() for o in outs], [p.grad.clone() for p in coll.parameters()]))
     for a, b in zip(results[0][0] + results[0][1], results[1][0] + results[1][1]):
         assert torch.equal(a, b)
+
+
+@pytest.mark.gpu
+def test_module_sample_route_and_bf16_inference(g, ora):
+    """The module's other forward routes: sample-level reuse (same sums, gradients unchanged) and the
+    bf16-core inference forward (against the oracle on cores rounded to bf16, fp32 tolerance)."""
+    import paper_2507_14668_amd as tt
+    from test_gpu_parity_small import round_to_bf16
+    shape, cores, idx, off, grad = wl.small_random_problem(93, n=(6, 5, 7), d=(4, 8, 4), r=(1, 32, 32, 1), num_bags=500,
+                                                          max_len=9, sigma=0.2)
+    d_idx, d_off, d_g = g.to_dev(idx, torch.int64), g.to_dev(off, torch.int64), g.to_dev(grad, torch.float32)
+    ref_out = ora.forward(shape, cores, idx, off)
+    ref_dg = ora.backward(shape, cores, idx, off, grad)
+    m = _module_like(tt, shape, cores, include_last_offset=True, forward_route="sample")
+    out = m(d_idx, d_off)
+    g.assert_close_rows(out.detach().cpu().numpy(), ref_out, g.FWD_RTOL, shape.dim, "module forward (sample route)")
+    out.backward(d_g.view_as(out))
+    g.assert_grads_close(shape, [p.grad for p in m.cores()], ref_dg, what="module dG (sample route)")
+    # bf16 inference: no graph, copies rebuilt on request
+    out_b = m.forward_bf16(d_idx, d_off)
+    assert not out_b.requires_grad
+    rounded = [round_to_bf16(c) for c in cores]
+    g.assert_close_rows(out_b.cpu().numpy(), ora.forward(shape, rounded, idx, off), g.FWD_RTOL, shape.dim,
+                        "module forward_bf16")
+    with torch.no_grad():
+        m.core2.mul_(2.0)
+    m.bf16_inference()
+    doubled = [rounded[0], rounded[1], round_to_bf16(2.0 * np.asarray(cores[2], np.float32))]
+    g.assert_close_rows(m.forward_bf16(d_idx, d_off).cpu().numpy(), ora.forward(shape, doubled, idx, off), g.FWD_RTOL,
+                        shape.dim, "module forward_bf16 after refresh")
+    with pytest.raises(ValueError):
+        _module_like(tt, shape, cores, forward_route="nope")
