@@ -75,7 +75,64 @@ k_extract_keys(TTArg<BATCHED> a, int in_a, int bits, int passes) {
     if (l < nnz && l < num_bags && offsets[l] == (long long)l && offsets[l + 1] > (long long)l) {
       lo[i] = l; hi[i] = l + 1;  // bag b starts at lookup b (every earlier bag holds one lookup): no search
     }
+    if (l >= nnz) hi[i] = lo[i] + 1;  // no lookup: nothing to find
     searching |= hi[i] - lo[i] > 1;
+  }
+  // Multi-lookup bags.  The tile's lookups are consecutive, so their bags start at the bag of the
+  // tile's first lookup: the workgroup finds that bag with a 256-ary search (two rounds of one probe
+  // per thread for 65 536 bags, instead of sixteen dependent halving steps per thread), stages the
+  // next TT_SORT_TILE + 1 offsets in LDS and every thread bisects there.  Only a thread whose bag lies
+  // beyond the staged window (more than a tile's worth of bags, i.e. runs of empty bags) goes on
+  // halving in memory.  With offsets that are not monotone the searches still stay inside
+  // [0, num_bags]; the offsets check reports them.
+  __shared__ long long s_off[TT_SORT_TILE + 1];
+  __shared__ int s_cnt[TT_BLOCK / TT_WAVE], s_any;
+  if (threadIdx.x == 0) s_any = 0;
+  __syncthreads();
+  if (searching) s_any = 1;
+  __syncthreads();
+  if (s_any) {  // uniform
+    const long long first = (long long)blockIdx.x * TT_SORT_TILE;
+    int wlo = 0, whi = num_bags;  // the bag of lookup `first` is in [wlo, whi)
+    while (whi - wlo > 1) {       // uniform
+      const int step = (whi - wlo + TT_BLOCK) / (TT_BLOCK + 1);  // probes wlo + (t+1)*step, t = thread
+      const long long q = (long long)wlo + (long long)(threadIdx.x + 1) * step;
+      const bool le = q < whi && offsets[q] <= first;
+      const unsigned long long m = __ballot(le);
+      if ((threadIdx.x & (TT_WAVE - 1)) == 0) s_cnt[threadIdx.x / TT_WAVE] = __popcll(m);
+      __syncthreads();
+      int cnt = 0;
+#pragma unroll
+      for (int w = 0; w < TT_BLOCK / TT_WAVE; ++w) cnt += s_cnt[w];
+      __syncthreads();
+      // monotone offsets: the probes that are <= first are the first `cnt` ones
+      const long long nlo = (long long)wlo + (long long)cnt * step, nhi = nlo + step;
+      wlo = (int)nlo;
+      whi = nhi < whi ? (int)nhi : whi;
+    }
+    const int wcount = (num_bags + 1 - wlo) < (TT_SORT_TILE + 1) ? (num_bags + 1 - wlo) : (TT_SORT_TILE + 1);
+    for (int e = threadIdx.x; e < wcount; e += TT_BLOCK) s_off[e] = offsets[wlo + e];
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < TT_SORT_ITEMS; ++i) {
+      const int l = blockIdx.x * TT_SORT_TILE + i * TT_BLOCK + threadIdx.x;
+      if (hi[i] - lo[i] <= 1) continue;
+      if (s_off[wcount - 1] <= (long long)l && wlo + wcount - 1 < num_bags) {
+        lo[i] = wlo + wcount - 1;  // beyond the window: go on in memory
+        continue;
+      }
+      int a = 0, b = wcount - 1;  // s_off[a] <= l is assumed, the answer is in [a, b)
+      if (s_off[b] <= (long long)l) b = wcount;  // the last bag of the table
+      while (b - a > 1) {
+        const int mid = (a + b) >> 1;
+        if (s_off[mid] <= (long long)l) a = mid; else b = mid;
+      }
+      lo[i] = wlo + a < num_bags ? wlo + a : num_bags - 1;
+      hi[i] = lo[i] + 1;
+    }
+    searching = false;
+#pragma unroll
+    for (int i = 0; i < TT_SORT_ITEMS; ++i) searching |= hi[i] - lo[i] > 1;
   }
   while (searching) {  // one halving step for all four per round
     searching = false;

@@ -147,13 +147,16 @@ def test_emulated_one_hot_batch_and_mixed_bag_lengths(emu, ora):
     import gpu_util as g
     shape, cores, _, _, _ = wl.small_random_problem(41, n=(5, 4, 6), d=(2, 3, 2), r=(1, 3, 5, 1))
     rng = np.random.default_rng(5)
-    for nb, lens in ((1500, None), (1100, rng.integers(0, 2, 1100))):
+    sparse = np.zeros(4000, np.int64)  # runs of more than a tile's worth of empty bags between the lookups
+    sparse[[0, 1500, 1501, 3999]] = (3, 2, 1200, 4)
+    for nb, lens in ((1500, None), (1100, rng.integers(0, 2, 1100)), (4000, sparse)):
         lens = np.ones(nb, np.int64) if lens is None else lens
         off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
         idx = rng.integers(0, shape.num_rows, int(off[-1])).astype(np.int64)
         grad = rng.standard_normal(nb * shape.dim).astype(np.float32)
         res = _run(emu, shape, cores, idx, off, grad, 0.05)
         ref_out = ora.forward(shape, cores, idx, off)
+        assert np.array_equal(res["plan_arrays"]["lookup2row"], ora.reorder_plan(shape, idx, off)["lookup2row"])
         for arm in ("plan", "naive"):
             g.assert_close_rows(res[arm][0], ref_out, g.FWD_RTOL, shape.dim, "one-hot forward (%s)" % arm)
         g.assert_grads_close(shape, res["plan"][1], ora.backward(shape, cores, idx, off, grad), what="one-hot dG")
