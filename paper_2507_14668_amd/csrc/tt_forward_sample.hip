@@ -70,7 +70,9 @@ k_bag_chains(TTArg<BATCHED> a, int lds_per_wave) {
     scol[k] = o < sh.D ? o - jj * sh.d3 : 0;
     acc[k] = 0.f;
   }
-  const long long lo = offsets[b], hi = offsets[b + 1];
+  // offsets are clamped to [0, nnz] so that a malformed CSR array cannot index out of bounds
+  const long long o0 = offsets[b], o1 = offsets[b + 1], nnz = d.nnz;
+  const long long lo = o0 < 0 ? 0 : (o0 > nnz ? nnz : o0), hi = o1 < lo ? lo : (o1 > nnz ? nnz : o1);
   const bool vec4 = (sh.R2 & 3) == 0;  // the buffer is 256-byte aligned and P a multiple of 4 then
   for (long long base = lo; base < hi; base += TT_WAVE) {
     // this lane's lookup: prefix slot and i3 (an invalid lookup has no row slot and takes no part)

@@ -20,7 +20,7 @@ namespace {
 struct EdgeArgs {
   const int64_t *indices, *offsets;
   const int32_t *rank;
-  long long num_rows, hot;
+  long long num_rows, hot, nnz;
   int num_bags, max_group;
   long long cap;          // pair capacity
   int32_t *bag_off;       // [num_bags + 1] pair offset of each bag
@@ -33,7 +33,9 @@ struct EdgeArgs {
 // wavefront's LDS scratch of TT_EDGE_BAG_CAP ints each.  Executed by all lanes of the wavefront.
 __device__ int bag_nodes(const EdgeArgs &a, int bag, int *nodes, int *uniq, int *sorted) {
   const int lane = threadIdx.x & (TT_WAVE - 1);
-  const long long lo = a.offsets[bag], hi = a.offsets[bag + 1];
+  // offsets are clamped to [0, nnz] so that a malformed CSR array cannot index out of bounds
+  const long long o0 = a.offsets[bag], o1 = a.offsets[bag + 1];
+  const long long lo = o0 < 0 ? 0 : (o0 > a.nnz ? a.nnz : o0), hi = o1 < lo ? lo : (o1 > a.nnz ? a.nnz : o1);
   const int len = (int)((hi - lo) < TT_EDGE_BAG_CAP ? (hi - lo) : TT_EDGE_BAG_CAP);
   for (int p = lane; p < len; p += TT_WAVE) {
     const long long row = a.indices[lo + p];
@@ -230,7 +232,6 @@ tt_status ttk_index_graph_edges(const int64_t *indices, const int64_t *offsets, 
                                 const int32_t *rank, long long num_rows, long long hot, int max_group,
                                 void *workspace, long long max_pairs, int32_t *eu, int32_t *ev, int32_t *ew,
                                 int32_t *counts_out, hipStream_t s) {
-  (void)nnz;
   const EdgeLayout L = edge_layout(num_bags, max_pairs);
   int32_t *w = (int32_t *)workspace;
   int key_bits = 1;
@@ -243,7 +244,7 @@ tt_status ttk_index_graph_edges(const int64_t *indices, const int64_t *offsets, 
   const bool in_a = (passes % 2) == 0;
   EdgeArgs ea;
   ea.indices = indices; ea.offsets = offsets; ea.rank = rank;
-  ea.num_rows = num_rows; ea.hot = hot;
+  ea.num_rows = num_rows; ea.hot = hot; ea.nnz = nnz;
   ea.num_bags = (int)num_bags; ea.max_group = max_group;
   ea.cap = max_pairs;
   ea.bag_off = w + L.bag_off;

@@ -113,6 +113,32 @@ int main(int argc, char **argv) {
     fprintf(stderr, "index-graph edges: %d pairs -> %d edges\n", counts[0], counts[1]);
     free(ws);
   }
+  {  // malformed CSR offsets (negative, beyond nnz, decreasing): every kernel has to stay in bounds; the
+     // results are unspecified, the plan reports the error
+    Tab &B = tabs[0];
+    for (int k = 0; k < 3; ++k) B.t.core[k] = B.core[k].data() + g_off;
+    std::vector<int64_t> bad = B.off;
+    for (size_t i = 1; i + 1 < bad.size(); i += 7) bad[i] = (i % 3 == 0) ? -5 : ((i % 3 == 1) ? B.nnz + 9 : bad[i - 1] - 2);
+    tt_plan plan; memset(&plan, 0, sizeof(plan));
+    const size_t wb = tt_workspace_bytes(&B.t, B.nnz, B.bags);
+    void *ws = amalloc(wb);
+    CK(tt_index_reorder(&B.t, B.idx.data(), bad.data(), B.nnz, B.bags, nullptr, ws, wb, &plan, nullptr));
+    int64_t counts[4];
+    if (tt_plan_status(&plan, nullptr, counts) != TT_ERR_INDEX_RANGE) { fprintf(stderr, "FAIL malformed offsets not reported\n"); return 7; }
+    std::vector<float> out((size_t)B.bags * B.D);
+    CK(tt_emb_bag_forward(&B.t, &plan, B.idx.data(), bad.data(), B.nnz, B.bags, out.data(), nullptr));
+    const size_t rb = tt_reuse_buffer_bytes(&B.t, B.nnz);
+    void *reuse = amalloc(rb);
+    CK(tt_emb_bag_forward_sample(&B.t, &plan, bad.data(), B.nnz, B.bags, reuse, rb, out.data(), nullptr));
+    CK(tt_emb_bag_backward_sgd(&B.t, &plan, B.idx.data(), bad.data(), B.nnz, B.bags, B.grad.data(), 0.f, nullptr));
+    std::vector<int32_t> rank((size_t)B.t.num_rows, 3), eu(4096), ev(4096), ew(4096), ec(4);
+    const size_t gb = tt_index_graph_workspace_bytes(B.bags, 4096);
+    void *gws = amalloc(gb);
+    CK(tt_index_graph_edges(B.idx.data(), bad.data(), B.nnz, B.bags, rank.data(), B.t.num_rows, 0, 64, gws, gb, 4096,
+                            eu.data(), ev.data(), ew.data(), ec.data(), nullptr));
+    free(gws); free(reuse); free(ws);
+    fprintf(stderr, "malformed offsets: reported, no access out of bounds\n");
+  }
   for (auto &B : tabs) emu::host_only(&B.t, sizeof(B.t));
   const int T = (int)tabs.size();
   const float lr = 0.01f;

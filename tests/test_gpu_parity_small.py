@@ -218,6 +218,8 @@ def test_invalid_indices_are_reported_and_skipped(g, ora):
     assert st == binding.TT_ERR_INDEX_RANGE and counts[3] & 2
     out = tt.tt_emb_bag_forward(table, bad, g.to_dev(good, torch.int64), g.to_dev(bad_off, torch.int64))
     assert torch.isfinite(out).all()
+    out = tt.tt_emb_bag_forward_sample(table, bad, g.to_dev(bad_off, torch.int64))
+    assert torch.isfinite(out).all()
 
 
 def test_host_side_argument_errors(g):
