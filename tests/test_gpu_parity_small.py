@@ -348,3 +348,37 @@ def test_bf16_cores_refused_for_other_shapes(g):
     assert tt.tt_bf16_cores_bytes(table) == 0
     with pytest.raises(tt.TTError):
         tt.tt_cores_to_bf16(table)
+
+
+def test_seeded_random_shapes(g, ora):
+    """Sixty seeded random shapes and batches within the library's limits (ranks and factors that are not
+    powers of two, single-slice cores, padded row counts, the matrix-core shapes, bags of up to 70
+    lookups, batches of up to 3000 bags): every entry point of the planned and naive arms against the
+    oracle, the plan bit for bit, the fused update bit for bit against backward + update."""
+    rng = np.random.default_rng(20250715)
+    for case in range(60):
+        while True:
+            n = tuple(int(x) for x in rng.integers(1, 40, size=3))
+            d = tuple(int(x) for x in rng.choice([1, 2, 3, 4, 5, 8], size=3))
+            r1, r2 = int(rng.choice([1, 2, 3, 7, 16, 33, 64])), int(rng.choice([1, 2, 5, 8, 17, 32, 64]))
+            if rng.random() < 0.3:
+                d, r1 = (4, 8, 4), int(rng.choice([32, 64]))
+                r2 = r1
+            dim, p12, s2 = d[0] * d[1] * d[2], d[0] * d[1] * r2, d[1] * r2
+            lds = d[0] * r1 + d[0] * d[1] * (r2 | 1) + p12 + dim + 8 * r2 * d[2]
+            if dim <= 1024 and p12 <= 4096 and s2 <= 4096 and lds * 4 <= 65536:
+                break
+        cap = n[0] * n[1] * n[2]
+        num_rows = int(rng.integers(max(1, cap - n[2] + 1), cap + 1))
+        nb = int(rng.choice([1, 7, 100, 700, 3000]))
+        ml = int(rng.choice([1, 3, 9, 70]))
+        if nb * ml > 40000:
+            nb = 40000 // ml
+        print("case random %d n=%s d=%s r=(%d,%d) rows=%d bags=%d max_len=%d" % (case, n, d, r1, r2, num_rows, nb, ml), flush=True)
+        shape, cores, idx, off, grad = wl.small_random_problem(8000 + case, n=n, d=d, r=(1, r1, r2, 1), num_rows=num_rows,
+                                                              num_bags=nb, max_len=ml, sigma=0.3)
+        if case % 3 == 0 and len(idx):  # skew: a third of the cases look mostly at a few rows
+            hot = rng.integers(0, num_rows, size=3)
+            mask = rng.random(len(idx)) < 0.7
+            idx = np.where(mask, hot[rng.integers(0, 3, len(idx))], idx).astype(np.int64)
+        run_all(g, ora, shape, cores, idx, off, grad)
