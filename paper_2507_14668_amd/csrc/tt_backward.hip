@@ -151,67 +151,92 @@ k_seg_stage1(TTArg<BATCHED> arg, SegLaunch L, int lanes) {
     const int s_after = hi < M ? seg_src[hi] / seg_div : -2;
     const int s_blk_before = block_lo > 0 ? seg_src[block_lo - 1] / seg_div : -1;
     const int s_blk_after = block_hi < M ? seg_src[block_hi] / seg_div : -2;
-    for (int e = lane * VEC; e < W; e += lanes * VEC) {
-      Vec<VEC> acc;
-      acc.zero();
-      int cur = -1;
-      // Where a finished run goes is decided from the segment ids next to the chunk and next to the
-      // workgroup's range (ids are non-decreasing), not from the segment's offsets: those would be two
-      // dependent loads at every segment change.  `at_end`: the run reaches the chunk's last position.
-      auto flush = [&](bool at_end) {
-        const bool starts_in = cur != s_before;          // the segment begins inside the chunk
-        const bool ends_in = !at_end || cur != s_after;  // ... and ends inside it
-        if (starts_in && ends_in) {
+    // Where a finished run goes is decided from the segment ids next to the chunk and next to the
+    // workgroup's range (ids are non-decreasing), not from the segment's offsets: those would be two
+    // dependent loads at every segment change.  `at_end`: the run reaches the chunk's last position.
+    // `active`: this lane holds columns of the vector (the flag `merged` is set by idle lanes too: it
+    // decides a workgroup barrier).
+    auto flush = [&](const Vec<VEC> &acc, int cur, int e, bool active, bool at_end) {
+      const bool starts_in = cur != s_before;          // the segment begins inside the chunk
+      const bool ends_in = !at_end || cur != s_after;  // ... and ends inside it
+      if (starts_in && ends_in) {
+        if (active) {
           float *dst = out + seg_out_index(cur, e, out_inner, nseg);
           if (fused) acc.store_sgd(dst, lr); else acc.store(dst);
-        } else if (cur == s_blk_before && cur == s_blk_after) {  // it covers the workgroup's whole range:
-          acc.store(red + (size_t)g * W + e);                      // one partial for the workgroup, summed below
-          merged = true;
-        } else acc.store(partial + ((size_t)c * 2 + (starts_in ? 1 : 0)) * W + e);
-      };
-      int pos = lo;
-      for (; pos + TT_SEG_UNROLL <= end; pos += TT_SEG_UNROLL) {  // independent gathers in flight,
-        int sg[TT_SEG_UNROLL];                                    // added in position order
-        Vec<VEC> x[TT_SEG_UNROLL];
+        }
+      } else if (cur == s_blk_before && cur == s_blk_after) {  // it covers the workgroup's whole range:
+        if (active) acc.store(red + (size_t)g * W + e);       // one partial for the workgroup, summed below
+        merged = true;
+      } else if (active) acc.store(partial + ((size_t)c * 2 + (starts_in ? 1 : 0)) * W + e);
+    };
+    auto load_row = [&](int row, int e, Vec<VEC> &x) {
+      x.load(src + (size_t)row * nsub * W + e);
+      for (int t = 1; t < nsub; ++t) {
+        Vec<VEC> y;
+        y.load(src + ((size_t)row * nsub + t) * W + e);
+        x.add(y);
+      }
+    };
+    if (lanes >= TT_SEG_UNROLL) {
+      // The lanes of the group fetch the segment ids and gather indices of `lanes` positions at once,
+      // one position per lane, and hand them round with lane shuffles: one round trip for the indices
+      // of a whole block of positions instead of one in front of every group of gathers.  (Every lane
+      // runs every shuffle; positions past the chunk's end carry the id -3 and are skipped.)
+      for (int e0 = 0; e0 < W; e0 += lanes * VEC) {
+        const int e = e0 + lane * VEC;
+        const bool active = e < W;
+        Vec<VEC> acc;
+        acc.zero();
+        int cur = -1;
+        for (int sub = lo; sub < hi; sub += lanes) {
+          const int mine = sub + lane;
+          int my_sg = -3, my_row = 0;
+          if (mine < end) {
+            my_sg = seg_src[mine] / seg_div;
+            my_row = gidx ? gidx[mine] : mine;
+          }
+          const int cnt = (hi - sub) < lanes ? (hi - sub) : lanes;  // a multiple of TT_SEG_UNROLL
+          for (int k = 0; k < cnt; k += TT_SEG_UNROLL) {
+            int sg[TT_SEG_UNROLL];
+            Vec<VEC> x[TT_SEG_UNROLL];
 #pragma unroll
-        for (int k = 0; k < TT_SEG_UNROLL; ++k) {
-          sg[k] = seg_src[pos + k] / seg_div;
-          const int row = gidx ? gidx[pos + k] : pos + k;
-          x[k].load(src + (size_t)row * nsub * W + e);
-          for (int t = 1; t < nsub; ++t) {
-            Vec<VEC> y;
-            y.load(src + ((size_t)row * nsub + t) * W + e);
-            x[k].add(y);
+            for (int u = 0; u < TT_SEG_UNROLL; ++u) {
+              sg[u] = __shfl(my_sg, k + u, lanes);
+              const int row = __shfl(my_row, k + u, lanes);
+              if (sg[u] != -3 && active) load_row(row, e, x[u]); else x[u].zero();
+            }
+#pragma unroll
+            for (int u = 0; u < TT_SEG_UNROLL; ++u) {
+              if (sg[u] == -3) continue;
+              if (sg[u] != cur) {
+                if (cur >= 0) flush(acc, cur, e, active, false);
+                cur = sg[u];
+                acc.zero();
+              }
+              acc.add(x[u]);
+            }
           }
         }
-#pragma unroll
-        for (int k = 0; k < TT_SEG_UNROLL; ++k) {
-          if (sg[k] != cur) {
-            if (cur >= 0) flush(false);
-            cur = sg[k];
+        if (cur >= 0) flush(acc, cur, e, active, true);
+      }
+    } else {
+      for (int e = lane * VEC; e < W; e += lanes * VEC) {
+        Vec<VEC> acc;
+        acc.zero();
+        int cur = -1;
+        for (int pos = lo; pos < end; ++pos) {
+          const int sgk = seg_src[pos] / seg_div;
+          Vec<VEC> x;
+          load_row(gidx ? gidx[pos] : pos, e, x);
+          if (sgk != cur) {
+            if (cur >= 0) flush(acc, cur, e, true, false);
+            cur = sgk;
             acc.zero();
           }
-          acc.add(x[k]);
+          acc.add(x);
         }
+        if (cur >= 0) flush(acc, cur, e, true, true);
       }
-      for (; pos < end; ++pos) {
-        const int sgk = seg_src[pos] / seg_div;
-        const int row = gidx ? gidx[pos] : pos;
-        Vec<VEC> x;
-        x.load(src + (size_t)row * nsub * W + e);
-        for (int t = 1; t < nsub; ++t) {
-          Vec<VEC> y;
-          y.load(src + ((size_t)row * nsub + t) * W + e);
-          x.add(y);
-        }
-        if (sgk != cur) {
-          if (cur >= 0) flush(false);
-          cur = sgk;
-          acc.zero();
-        }
-        acc.add(x);
-      }
-      if (cur >= 0) flush(true);
     }
     if (merged) {  // uniform: the chunks' sums in chunk order -> slot 0 of the workgroup's first chunk
       __syncthreads();

@@ -83,7 +83,9 @@ static inline int __lane() { return (int)(emu::t_threadIdx.x & 63); }
 static inline int __shfl_up(int v, int delta, int = 64) {
   return (int)(uint32_t)emu::wave_exchange((uint32_t)v, __lane() - delta);
 }
-static inline int __shfl(int v, int src, int = 64) { return (int)(uint32_t)emu::wave_exchange((uint32_t)v, src & 63); }
+static inline int __shfl(int v, int src, int width = 64) {  // src counts inside the lane's segment of `width` lanes
+  return (int)(uint32_t)emu::wave_exchange((uint32_t)v, (__lane() & ~(width - 1)) | (src & (width - 1)));
+}
 static inline int __ffsll(unsigned long long v) { return __builtin_ffsll((long long)v); }
 static inline float __shfl_xor(float v, int mask, int = 64) {
   uint32_t u; memcpy(&u, &v, 4);
