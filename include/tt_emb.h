@@ -314,6 +314,50 @@ tt_status tt_core_sgd_update_batched(int num_tables, tt_batch_item *items, float
                                      size_t desc_bytes, void *stream);
 
 /*
+ * Fused tables.  TT tables with the same column factors d[] and ranks r[] can be stored as ONE TT
+ * table whose core k is the members' cores k laid side by side along the row-factor axis:
+ * [r_k][sum over members of n_k][d_k][r_k+1], member t owning the range [o_k(t), o_k(t) + n_k(t)) of
+ * that axis (o_k = sum of n_k over the members before t).  Row i = (i1, i2, i3) of member t
+ * (index split of Section III-B) is row ((o_1 + i1) * N2 + o_2 + i2) * N3 + o_3 + i3 of the fused
+ * table (N_k = sum of n_k): the same three slices, hence the same product (TT-matrix equation,
+ * Section II-B), the same bag sums and the same core gradients, found at the members' ranges of the
+ * fused cores.  Fused rows that mix slices of different members exist but are never looked up.
+ * One reorder, one forward and one backward over the fused table then replace the members' calls:
+ * fewer, larger launches (the batched prefix products of Section III-C now batch over tables too).
+ *
+ * tt_fuse_shape fills fused->num_rows and fused->n[] (d[], r[] and core[] are the caller's):
+ * TT_ERR_SHAPE if a row factor sum or the row count does not fit (N1*N2*N3 must stay below 2^31).
+ *
+ * tt_fuse_lookups maps one batch of every member into the fused table, member after member:
+ *   indices, offsets  HOST arrays [num_tables] of DEVICE pointers: member t's int64[nnz[t]] and
+ *                     CSR int64[num_bags[t] + 1], as tt_index_reorder takes them
+ *   remaps            HOST array of DEVICE pointers or NULL; a non-NULL entry is member t's row
+ *                     bijection f_index (int64[num_rows of t]), applied before the split
+ *   nnz, num_bags     HOST int64[num_tables]
+ *   fused_indices     DEVICE int64[sum nnz]: member t's lookups at [sum of nnz before t, ...);
+ *                     an index outside [0, num_rows of t) becomes -1, which tt_index_reorder
+ *                     reports and skips like any invalid index
+ *   fused_offsets     DEVICE int64[sum num_bags + 1]: member t's bags at [sum of num_bags before
+ *                     t, ...), so that rows of `out` / `grad_out` of the fused calls are the
+ *                     members' rows, member after member.  An offset outside [0, nnz[t]], a first
+ *                     offset other than 0 or a last one other than nnz[t] is written as -1, which
+ *                     tt_index_reorder reports as an invalid CSR array.
+ * One launch on `stream`; nothing is read on the host.  At most TT_FUSE_MAX_TABLES members.
+ */
+#define TT_FUSE_MAX_TABLES 32
+typedef struct {
+  int32_t num_tables;
+  int32_t n[TT_FUSE_MAX_TABLES][3];     /* row factors of member t                             */
+  int64_t num_rows[TT_FUSE_MAX_TABLES]; /* rows of member t (<= n[t][0]*n[t][1]*n[t][2])       */
+} tt_fuse_members;
+
+tt_status tt_fuse_shape(const tt_fuse_members *members, tt_table *fused);
+tt_status tt_fuse_lookups(const tt_fuse_members *members, const int64_t *const *indices,
+                          const int64_t *const *offsets, const int64_t *const *remaps,
+                          const int64_t *nnz, const int64_t *num_bags, int64_t *fused_indices,
+                          int64_t *fused_offsets, void *stream);
+
+/*
  * Index-graph edges of one batch (Section III-G, index-graph generation algorithm): the weighted
  * co-occurrence graph the offline index bijection is built from.  Offline preprocessing, not part
  * of a training step.

@@ -26,7 +26,7 @@ TT_ERR_UNAVAILABLE = -6
 EXPORTS = ("tt_workspace_bytes", "tt_index_reorder", "tt_emb_bag_forward", "tt_emb_bag_backward",
            "tt_core_sgd_update", "tt_emb_bag_backward_sgd", "tt_emb_bag_forward_static", "tt_reuse_buffer_bytes", "tt_emb_bag_forward_sample",
            "tt_bf16_cores_bytes", "tt_cores_to_bf16", "tt_emb_bag_forward_bf16",
-           "tt_index_graph_workspace_bytes", "tt_index_graph_edges", "tt_plan_status", "tt_strerror", "tt_prof_create", "tt_prof_destroy",
+           "tt_index_graph_workspace_bytes", "tt_index_graph_edges", "tt_fuse_shape", "tt_fuse_lookups", "tt_plan_status", "tt_strerror", "tt_prof_create", "tt_prof_destroy",
            "tt_prof_collect", "tt_kernel_name", "tt_batch_desc_bytes", "tt_index_reorder_batched",
            "tt_emb_bag_forward_batched", "tt_emb_bag_backward_batched", "tt_core_sgd_update_batched")
 KERNELS = {"fwd_contract": 0, "bag_sum": 1, "grad_merge": 2, "bwd_contract": 3, "sort_scatter": 4, "sgd": 5,
@@ -67,6 +67,14 @@ class CBatchItem(ctypes.Structure):
                 ("remap", ctypes.c_void_p), ("workspace", ctypes.c_void_p),
                 ("workspace_bytes", ctypes.c_size_t), ("out", ctypes.c_void_p),
                 ("grad_out", ctypes.c_void_p), ("dcore", ctypes.c_void_p * 3)]
+
+
+TT_FUSE_MAX_TABLES = 32
+
+
+class CFuseMembers(ctypes.Structure):
+    _fields_ = [("num_tables", ctypes.c_int32), ("n", (ctypes.c_int32 * 3) * TT_FUSE_MAX_TABLES),
+                ("num_rows", ctypes.c_int64 * TT_FUSE_MAX_TABLES)]
 
 
 _lib = None
@@ -110,6 +118,10 @@ def load_library():
         lib.tt_index_graph_edges.restype = ctypes.c_int
         lib.tt_index_graph_edges.argtypes = [vp, vp, i64, i64, vp, i64, i64, ctypes.c_int32, vp, ctypes.c_size_t, i64,
                                              vp, vp, vp, vp, vp]
+        lib.tt_fuse_shape.restype = ctypes.c_int
+        lib.tt_fuse_shape.argtypes = [vp, vp]
+        lib.tt_fuse_lookups.restype = ctypes.c_int
+        lib.tt_fuse_lookups.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp]
         lib.tt_plan_status.restype = ctypes.c_int
         lib.tt_plan_status.argtypes = [vp, vp, vp]
         lib.tt_prof_create.restype = vp
@@ -412,6 +424,109 @@ def tt_core_sgd_update(table: Table, plan, dcores, lr: float, stream=None):
 def tt_plan_status(plan: Plan, stream=None) -> int:
     _, st = plan.counts(stream)
     return st
+
+
+# ------------------------------------------------------------------ fused tables
+class FusedTables:
+    """Several TT tables with equal column factors and ranks stored as ONE table: core k of the fused
+    table is `[r_k][sum of the members' n_k][d_k][r_k+1]`, member t owning a range of the middle axis.
+
+    members   list of `(num_rows, (n1, n2, n3))`
+    cores     optional list (per member) of three flat fp32 tensors / arrays to start from; without
+              it the fused cores are left for the caller to fill (`member_core` gives the views)
+    `table` is the fused `Table` every single-table call of this module takes; `fuse_lookups` maps
+    one batch of every member into it; rows of the fused `out` / `grad_out` are the members' bags,
+    member after member (`bag_ranges`).
+    """
+
+    def __init__(self, members, d, r, cores=None, device="cuda"):
+        members = [(int(nr), tuple(int(x) for x in n)) for nr, n in members]
+        if not 1 <= len(members) <= TT_FUSE_MAX_TABLES:
+            raise ValueError("1 to %d member tables" % TT_FUSE_MAX_TABLES)
+        self.members, self.d, self.r = members, tuple(d), tuple(r)
+        c = CFuseMembers()
+        c.num_tables = len(members)
+        for t, (nr, n) in enumerate(members):
+            c.n[t][:] = n
+            c.num_rows[t] = nr
+        self.c = c
+        shape = CTable()
+        _check(load_library().tt_fuse_shape(ctypes.byref(c), ctypes.byref(shape)), "tt_fuse_shape")
+        self.n = tuple(shape.n)
+        self.start = [[sum(m[1][k] for m in members[:t]) for k in range(3)] for t in range(len(members))]
+        fused = [torch.zeros(self.r[k] * self.n[k] * self.d[k] * self.r[k + 1], dtype=torch.float32, device=device)
+                 for k in range(3)]
+        self.table = Table(int(shape.num_rows), self.n, self.d, self.r, fused)
+        if cores is not None:
+            for t in range(len(members)):
+                for k in range(3):
+                    src = torch.as_tensor(cores[t][k]).to(device=device, dtype=torch.float32)
+                    self.member_core(t, k).copy_(src.view(self.r[k], members[t][1][k], self.d[k], self.r[k + 1]))
+
+    def core_view(self, k, core=None):
+        """Core k of the fused table (or a tensor of its size, e.g. a gradient) as `[r_k][N_k][d_k][r_k+1]`."""
+        core = self.table.cores[k] if core is None else core
+        return core.view(self.r[k], self.n[k], self.d[k], self.r[k + 1])
+
+    def member_core(self, t, k, core=None):
+        """Member t's part of (a tensor shaped like) fused core k: a strided view `[r_k][n_k(t)][d_k][r_k+1]`."""
+        o = self.start[t][k]
+        return self.core_view(k, core)[:, o:o + self.members[t][1][k]]
+
+    def bag_ranges(self, num_bags):
+        out, b0 = [], 0
+        for nb in num_bags:
+            out.append((b0, b0 + int(nb)))
+            b0 += int(nb)
+        return out
+
+    def fuse_lookups(self, indices, offsets, remaps=None, out=None, stream=None):
+        """Maps the members' `(indices[t], offsets[t])` (CSR offsets, `bags + 1` long) into the fused
+        table: returns `(fused_indices, fused_offsets)`; `out` may bring the two tensors to write."""
+        T = len(self.members)
+        if len(indices) != T or len(offsets) != T:
+            raise ValueError("one (indices, offsets) pair per member table")
+        idx = [_dev_i64(x, "indices") for x in indices]
+        off = [_dev_i64(x, "offsets") for x in offsets]
+        rm = [None] * T if remaps is None else [_dev_i64(x, "remap") for x in remaps]
+        nnz = [x.numel() for x in idx]
+        nb = [x.numel() - 1 for x in off]
+        dev = off[0].device
+        if out is None:
+            out = (torch.empty(sum(nnz), dtype=torch.int64, device=dev),
+                   torch.empty(sum(nb) + 1, dtype=torch.int64, device=dev))
+        f_idx, f_off = _dev_i64(out[0], "fused_indices"), _dev_i64(out[1], "fused_offsets")
+        if f_idx.numel() != sum(nnz) or f_off.numel() != sum(nb) + 1:
+            raise ValueError("fused_indices / fused_offsets have the wrong length")
+        ptrs = lambda ts: (ctypes.c_void_p * T)(*[None if x is None or x.numel() == 0 else x.data_ptr() for x in ts])
+        i64s = lambda vs: (ctypes.c_int64 * T)(*vs)
+        st = load_library().tt_fuse_lookups(ctypes.byref(self.c), ptrs(idx), ptrs(off), ptrs(rm) if remaps is not None else None,
+                                            i64s(nnz), i64s(nb), _ptr(f_idx), _ptr(f_off), _stream(stream))
+        _check(st, "tt_fuse_lookups")
+        return f_idx, f_off
+
+
+def fusion_groups(members, groups=None, max_factor_sum=1023):
+    """Deals tables to fused groups: `members` is a list of `(num_rows, n)`; returns lists of member
+    positions.  Largest tables first, each into the group with the smallest sum of row factors so
+    far; `groups=None` takes the fewest groups whose factor sums stay within `max_factor_sum` (1023
+    keeps every grouping of the reorder a single radix digit) and whose rows stay below 2^31."""
+    order = sorted(range(len(members)), key=lambda t: -max(members[t][1]))
+    g = max(1, groups or 1)
+    while True:
+        parts, sums = [[] for _ in range(g)], [[0, 0, 0] for _ in range(g)]
+        for t in order:
+            k = min(range(g), key=lambda j: max(sums[j]))
+            parts[k].append(t)
+            for a in range(3):
+                sums[k][a] += members[t][1][a]
+        ok = all(max(sm) <= max_factor_sum and sm[0] * sm[1] * sm[2] < 2 ** 31 - 1 and len(p) <= TT_FUSE_MAX_TABLES
+                 for sm, p in zip(sums, parts) if p)
+        if ok or g >= len(members):
+            if not ok:
+                raise ValueError("no fusion of these tables fits the limits")
+            return [sorted(p) for p in parts if p]
+        g += 1
 
 
 # ------------------------------------------------------------------ batched calls

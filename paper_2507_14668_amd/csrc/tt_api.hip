@@ -417,6 +417,24 @@ tt_status tt_emb_bag_forward_bf16(const tt_table *table, const void *bf16_cores,
   return ttk_bag_sum(b, (hipStream_t)stream);
 }
 
+tt_status tt_fuse_shape(const tt_fuse_members *members, tt_table *fused) {
+  long long N[3];
+  if (!fused) return TT_ERR_INVALID_ARG;
+  const tt_status st = ttk_fuse_shape(members, N);
+  if (st != TT_OK) return st;
+  for (int k = 0; k < 3; ++k) fused->n[k] = (int32_t)N[k];
+  fused->num_rows = N[0] * N[1] * N[2];
+  return TT_OK;
+}
+
+tt_status tt_fuse_lookups(const tt_fuse_members *members, const int64_t *const *indices,
+                          const int64_t *const *offsets, const int64_t *const *remaps,
+                          const int64_t *nnz, const int64_t *num_bags, int64_t *fused_indices,
+                          int64_t *fused_offsets, void *stream) {
+  return ttk_fuse_lookups(members, indices, offsets, remaps, nnz, num_bags, fused_indices, fused_offsets,
+                          (hipStream_t)stream);
+}
+
 size_t tt_index_graph_workspace_bytes(int64_t num_bags, int64_t max_pairs) {
   if (num_bags < 0 || max_pairs < 1 || num_bags >= 2147483646LL || max_pairs >= 2147483647LL) return 0;
   return (ttk_index_graph_workspace_bytes(num_bags, max_pairs) + 255) & ~(size_t)255;

@@ -144,6 +144,13 @@ tt_status ttk_reorder(const TTBatch &b, hipStream_t s);
 int ttk_radix_passes(int key_bits);
 tt_status ttk_sort_slot1(const TTDev &d, int key_bits, hipStream_t s);
 size_t ttk_index_graph_workspace_bytes(long long num_bags, long long max_pairs);
+// Fused tables: sums of the members' row factors (with the limits of a table), and the one-launch
+// map of the members' lookups and bag offsets into the fused table.
+tt_status ttk_fuse_shape(const tt_fuse_members *members, long long N[3]);
+tt_status ttk_fuse_lookups(const tt_fuse_members *members, const int64_t *const *indices,
+                           const int64_t *const *offsets, const int64_t *const *remaps,
+                           const int64_t *nnz, const int64_t *num_bags, int64_t *fused_indices,
+                           int64_t *fused_offsets, hipStream_t s);
 tt_status ttk_index_graph_edges(const int64_t *indices, const int64_t *offsets, long long nnz, long long num_bags,
                                 const int32_t *rank, long long num_rows, long long hot, int max_group,
                                 void *workspace, long long max_pairs, int32_t *eu, int32_t *ev, int32_t *ew,

@@ -23,7 +23,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(os.path.dirname(HERE))
 CSRC = os.path.join(ROOT, "paper_2507_14668_amd", "csrc")
 CLANG = os.environ.get("TT_EMU_CXX", "/opt/rocm/llvm/bin/clang++")
-UNITS = ("tt_api", "tt_reorder", "tt_forward", "tt_forward_mfma", "tt_forward_sample", "tt_bf16", "tt_index_graph", "tt_backward",
+UNITS = ("tt_api", "tt_reorder", "tt_forward", "tt_forward_mfma", "tt_forward_sample", "tt_bf16", "tt_index_graph", "tt_fuse", "tt_backward",
          "tt_backward_mfma")
 
 

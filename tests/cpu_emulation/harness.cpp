@@ -275,6 +275,72 @@ int main(int argc, char **argv) {
       for (int t = 0; t < T; ++t) { mix(single[t].out); for (int k = 0; k < 3; ++k) { mix(single[t].dg[k]); mix(single[t].core[k]); } }
       fprintf(stderr, "checksum of single-table results: %016llx\n", (unsigned long long)h);
     }
+    if (planned) {  // ---- the same tables as ONE fused table: members' results within rounding of the single calls
+      tt_fuse_members mem; memset(&mem, 0, sizeof(mem));
+      mem.num_tables = T;
+      for (int t = 0; t < T; ++t) { for (int k = 0; k < 3; ++k) mem.n[t][k] = tabs[t].t.n[k]; mem.num_rows[t] = tabs[t].t.num_rows; }
+      tt_table ft = tabs[0].t;
+      CK(tt_fuse_shape(&mem, &ft));
+      std::vector<float> fcore[3], fdg[3];
+      float *fdc[3];
+      for (int k = 0; k < 3; ++k) {
+        const size_t inner = (size_t)ft.d[k] * ft.r[k + 1];
+        fcore[k].assign((size_t)ft.r[k] * ft.n[k] * inner + 1, 0.f);
+        fdg[k].assign(fcore[k].size() + 1, -9.f);
+        int o = 0;
+        for (int t = 0; t < T; ++t) {
+          const int nk = tabs[t].t.n[k];
+          for (int r = 0; r < ft.r[k]; ++r)
+            memcpy(fcore[k].data() + g_off + ((size_t)r * ft.n[k] + o) * inner,
+                   tabs[t].core0[k].data() + g_off + (size_t)r * nk * inner, (size_t)nk * inner * sizeof(float));
+          o += nk;
+        }
+        ft.core[k] = fcore[k].data() + g_off;
+        fdc[k] = fdg[k].data() + g_off;
+      }
+      std::vector<const int64_t *> pidx(T), poff(T);
+      std::vector<int64_t> nnzs(T), nbs(T);
+      int64_t tn = 0, tb = 0;
+      for (int t = 0; t < T; ++t) { pidx[t] = tabs[t].idx.data(); poff[t] = tabs[t].off.data(); nnzs[t] = tabs[t].nnz; nbs[t] = tabs[t].bags; tn += nnzs[t]; tb += nbs[t]; }
+      std::vector<int64_t> fidx((size_t)tn), foff((size_t)tb + 1);
+      emu::host_only(&mem, sizeof(mem));
+      emu::host_only(pidx.data(), T * sizeof(void *));
+      emu::host_only(poff.data(), T * sizeof(void *));
+      CK(tt_fuse_lookups(&mem, pidx.data(), poff.data(), nullptr, nnzs.data(), nbs.data(), fidx.data(), foff.data(), nullptr));
+      emu::host_only_release(&mem); emu::host_only_release(pidx.data()); emu::host_only_release(poff.data());
+      emu::host_only(&ft, sizeof(ft));
+      tt_plan fplan; memset(&fplan, 0, sizeof(fplan));
+      const size_t fwb = tt_workspace_bytes(&ft, tn, tb);
+      void *fws = amalloc(fwb);
+      CK(tt_index_reorder(&ft, fidx.data(), foff.data(), tn, tb, nullptr, fws, fwb, &fplan, nullptr));
+      int64_t fcounts[4];
+      CK(tt_plan_status(&fplan, nullptr, fcounts));
+      std::vector<float> fout((size_t)tb * tabs[0].D, -7.f), fgrad;
+      for (int t = 0; t < T; ++t) fgrad.insert(fgrad.end(), tabs[t].grad.begin(), tabs[t].grad.end());
+      CK(tt_emb_bag_forward(&ft, &fplan, fidx.data(), foff.data(), tn, tb, fout.data(), nullptr));
+      CK(tt_emb_bag_backward(&ft, &fplan, fidx.data(), foff.data(), tn, tb, fgrad.data(), fdc, nullptr));
+      emu::host_only_release(&ft);
+      size_t fbad = 0, b0 = 0;
+      auto near = [](float a, float b) { return fabs((double)a - b) <= 1e-4 * (1.0 + fabs((double)b)); };
+      for (int t = 0; t < T; ++t) {
+        for (size_t i = 0; i < single[t].out.size(); ++i) if (!near(fout[b0 * tabs[0].D + i], single[t].out[i])) ++fbad;
+        b0 += (size_t)tabs[t].bags;
+      }
+      for (int k = 0; k < 3; ++k) {
+        const size_t inner = (size_t)ft.d[k] * ft.r[k + 1];
+        int o = 0;
+        for (int t = 0; t < T; ++t) {
+          const int nk = tabs[t].t.n[k];
+          for (int r = 0; r < ft.r[k]; ++r)
+            for (size_t e = 0; e < (size_t)nk * inner; ++e)
+              if (!near(fdg[k][g_off + ((size_t)r * ft.n[k] + o) * inner + e], single[t].dg[k][g_off + (size_t)r * nk * inner + e])) ++fbad;
+          o += nk;
+        }
+      }
+      free(fws);
+      fprintf(stderr, "fused table of %d members: %lld rows, %lld prefixes, %zu values off\n", T, (long long)fcounts[0], (long long)fcounts[1], fbad);
+      if (fbad) return 8;
+    }
     emu::host_only_release(items.data());
     emu::host_only_release(plans.data());
     for (void *w : wss) free(w);
