@@ -37,8 +37,13 @@ def parse_args():
                          "co-occurrence structure) from the batches and pass it to the reorder as `remap`")
     ap.add_argument("--batches", type=int, default=8, help="distinct batches cycled through")
     ap.add_argument("--tables", type=int, default=0, help="use only the first T tables (0 = all)")
-    ap.add_argument("--streams", type=int, default=8,
-                    help="tables are dealt round-robin to this many (compute, reorder) stream pairs")
+    ap.add_argument("--streams", type=int, default=-1,
+                    help="tables are dealt round-robin to this many (compute, reorder) stream pairs "
+                         "(-1: 8, or 2 when the tables are fused)")
+    ap.add_argument("--fuse", type=int, default=-1,
+                    help="deal the tables to this many FUSED tables (tables with equal column factors and ranks "
+                         "stored as one table; the map of the members' lookups, tt_fuse_lookups, runs inside the "
+                         "timed step, in front of the reorder).  0: one table per call; -1: 4 for cfg5, 0 otherwise")
     ap.add_argument("--host-threads", type=int, default=4,
                     help="host threads that enqueue the stream pairs of a step in parallel")
     ap.add_argument("--graph", action="store_true",
@@ -60,7 +65,7 @@ def parse_args():
     return ap.parse_args()
 
 
-def measure(args, workload, arm, steps, warmup, batches, prof_kernels, streams):
+def measure(args, workload, arm, steps, warmup, batches, prof_kernels, streams, fuse=0):
     """One workload and arm: `warmup` + `steps` steps on `streams` stream pairs -> throughput; then, for
     every kernel in `prof_kernels` (planned arm), the same steps on ONE stream pair with that kernel
     bracketed by HIP events -> its roofline entry.  Returns the result dict of the JSON line (the first
@@ -115,20 +120,77 @@ def measure(args, workload, arm, steps, warmup, batches, prof_kernels, streams):
                          remap=None if remap is None else torch.from_numpy(remap).cuda(),
                          out=torch.empty((cfg.batch, shape.dim), dtype=torch.float32, device="cuda"),
                          dcores=table.core_grads_like()))
+    planned = arm != "naive"
+    ntab_members = ntab
+    for T in tabs:
+        T["bags"] = cfg.batch
+    if fuse > 0 and planned:
+        # Fused tables: the members' cores side by side in one table; the members' index and offset
+        # tensors stay the inputs of the step, their map into the fused table is part of the step.
+        sh0 = cfg.tables[0]
+        parts = tt.fusion_groups([(T["shape"].num_rows, T["shape"].n) for T in tabs], groups=fuse)
+        ftabs = []
+        for members in parts:
+            M = [tabs[t] for t in members]
+            fused = tt.FusedTables([(T["shape"].num_rows, T["shape"].n) for T in M], sh0.d, sh0.r,
+                                   cores=[T["table"].cores for T in M])
+            fb = []
+            for b in range(nbatch):
+                xs = [T["batches"][b] for T in M]
+                fb.append(dict(m_idx=[x["idx"] for x in xs], m_off=[x["off"] for x in xs],
+                               grad=torch.cat([x["grad"] for x in xs]), nnz=sum(x["nnz"] for x in xs),
+                               u_r=sum(x["u_r"] for x in xs), u_p=sum(x["u_p"] for x in xs),
+                               groups=sum(x["groups"] for x in xs) if arm == "sample" else None))
+            max_nnz, bags = max(x["nnz"] for x in fb), cfg.batch * len(M)
+            ftabs.append(dict(shape=wl.TableShape(fused.table.num_rows, fused.n, sh0.d, sh0.r), table=fused.table,
+                              fused=fused, members=members, batches=fb, plans=[None, None], bags=bags,
+                              ws=[tt.alloc_workspace(fused.table, max_nnz, bags) for _ in range(2)],
+                              fidx=[torch.empty(max_nnz, dtype=torch.int64, device="cuda") for _ in range(2)],
+                              foff=[torch.empty(bags + 1, dtype=torch.int64, device="cuda") for _ in range(2)],
+                              m_remaps=[T["remap"] for T in M] if args.bijection else None, remap=None,
+                              reuse=(torch.empty(tt.tt_reuse_buffer_bytes(fused.table, max_nnz), dtype=torch.uint8, device="cuda")
+                                     if arm == "sample" else None),
+                              bf16=tt.tt_cores_to_bf16(fused.table) if arm == "bf16" else None,
+                              out=torch.empty((bags, sh0.dim), dtype=torch.float32, device="cuda"),
+                              dcores=fused.table.core_grads_like()))
+        for T in tabs:
+            T["ws"] = T["out"] = T["dcores"] = T["reuse"] = None
+        tabs = ftabs
+        ntab = len(tabs)
     torch.cuda.synchronize()
     t_gen = time.time() - t_gen
 
-    planned = arm != "naive"
+    def make_plan(T, x, buf, stream):
+        """The plan of batch x in plan buffer `buf`; a fused table first maps its members' lookups."""
+        if "fused" in T:
+            idx, off = T["fused"].fuse_lookups(x["m_idx"], x["m_off"], remaps=T["m_remaps"],
+                                               out=(T["fidx"][buf][:x["nnz"]], T["foff"][buf]), stream=stream)
+            T["lookups"][buf] = (idx, off)
+            return tt.tt_index_reorder(T["table"], idx, off, workspace=T["ws"][buf], stream=stream)
+        T["lookups"][buf] = (x["idx"], x["off"])
+        # workspace sized for the largest batch; the plan is rebuilt for this batch's nnz
+        return tt.tt_index_reorder(T["table"], x["idx"], x["off"], remap=T["remap"], workspace=T["ws"][buf], stream=stream)
+
+    for T in tabs:
+        T["lookups"] = [None, None]
     if arm in ("sample", "bf16"):
         assert not do_bwd, "the %s arm is a forward: use a forward-only workload (cfg3)" % arm
 
-    def forward(T, plan, x, stream):
+    def compute_table(T, x, buf, stream):
+        """Forward and (with a backward workload) backward + update of batch x of one table."""
+        plan = T["plans"][buf] if planned else None
+        idx, off = T["lookups"][buf] if planned else (x["idx"], x["off"])
         if arm == "sample":
-            tt.tt_emb_bag_forward_sample(T["table"], plan, x["off"], reuse_buffer=T["reuse"], out=T["out"], stream=stream)
+            tt.tt_emb_bag_forward_sample(T["table"], plan, off, reuse_buffer=T["reuse"], out=T["out"], stream=stream)
         elif arm == "bf16":
-            tt.tt_emb_bag_forward_bf16(T["table"], T["bf16"], plan, x["off"], out=T["out"], stream=stream)
+            tt.tt_emb_bag_forward_bf16(T["table"], T["bf16"], plan, off, out=T["out"], stream=stream)
         else:
-            tt.tt_emb_bag_forward(T["table"], plan, x["idx"], x["off"], out=T["out"], stream=stream)
+            tt.tt_emb_bag_forward(T["table"], plan, idx, off, out=T["out"], stream=stream)
+        if do_bwd and planned and not args.separate_update:
+            tt.tt_emb_bag_backward_sgd(T["table"], plan, idx, off, x["grad"], cfg.lr, stream=stream)
+        elif do_bwd:
+            tt.tt_emb_bag_backward(T["table"], plan, idx, off, x["grad"], dcores=T["dcores"], stream=stream)
+            tt.tt_core_sgd_update(T["table"], plan, T["dcores"], cfg.lr, stream=stream)
 
     prof_kernels = [("bwd_contract" if do_bwd else "fwd_contract") if k == "auto" else k for k in prof_kernels]
     if not planned:
@@ -157,10 +219,7 @@ def measure(args, workload, arm, steps, warmup, batches, prof_kernels, streams):
             buf = b % 2
             for k in range(ns):
                 for T in groups[k]:
-                    x = T["batches"][b % nbatch]
-                    # workspace sized for the largest batch; the plan is rebuilt for this batch's nnz
-                    T["plans"][buf] = tt.tt_index_reorder(T["table"], x["idx"], x["off"], remap=T["remap"],
-                                                          workspace=T["ws"][buf], stream=rs[k])
+                    T["plans"][buf] = make_plan(T, T["batches"][b % nbatch], buf, rs[k])
                     if timing[0]:
                         profs[cur["name"]].attach(T["plans"][buf])
                 if events:
@@ -172,17 +231,7 @@ def measure(args, workload, arm, steps, warmup, batches, prof_kernels, streams):
                 if planned and events:
                     cs[k].wait_event(ready[k][buf])
                 for T in groups[k]:
-                    x = T["batches"][b % nbatch]
-                    plan = T["plans"][buf] if planned else None
-                    if do_fwd:
-                        forward(T, plan, x, cs[k])
-                    if do_bwd and planned and not args.separate_update:
-                        tt.tt_emb_bag_backward_sgd(T["table"], plan, x["idx"], x["off"], x["grad"], cfg.lr,
-                                                   stream=cs[k])
-                    elif do_bwd:
-                        tt.tt_emb_bag_backward(T["table"], plan, x["idx"], x["off"], x["grad"], dcores=T["dcores"],
-                                               stream=cs[k])
-                        tt.tt_core_sgd_update(T["table"], plan, T["dcores"], cfg.lr, stream=cs[k])
+                    compute_table(T, T["batches"][b % nbatch], buf, cs[k])
                 if events:
                     free[k][buf].record(cs[k])
 
@@ -203,24 +252,13 @@ def measure(args, workload, arm, steps, warmup, batches, prof_kernels, streams):
             if planned:
                 rs[k].wait_event(free[k][nxt])
                 for T in groups[k]:
-                    x = T["batches"][(b + 1) % nbatch]
-                    T["plans"][nxt] = tt.tt_index_reorder(T["table"], x["idx"], x["off"], remap=T["remap"],
-                                                          workspace=T["ws"][nxt], stream=rs[k])
+                    T["plans"][nxt] = make_plan(T, T["batches"][(b + 1) % nbatch], nxt, rs[k])
                     if timing[0]:
                         profs[cur["name"]].attach(T["plans"][nxt])
                 ready[k][nxt].record(rs[k])
                 cs[k].wait_event(ready[k][buf])
             for T in groups[k]:
-                x = T["batches"][b % nbatch]
-                plan = T["plans"][buf] if planned else None
-                if do_fwd:
-                    forward(T, plan, x, cs[k])
-                if do_bwd and planned and not args.separate_update:
-                    tt.tt_emb_bag_backward_sgd(T["table"], plan, x["idx"], x["off"], x["grad"], cfg.lr, stream=cs[k])
-                elif do_bwd:
-                    tt.tt_emb_bag_backward(T["table"], plan, x["idx"], x["off"], x["grad"], dcores=T["dcores"],
-                                           stream=cs[k])
-                    tt.tt_core_sgd_update(T["table"], plan, T["dcores"], cfg.lr, stream=cs[k])
+                compute_table(T, T["batches"][b % nbatch], buf, cs[k])
             free[k][buf].record(cs[k])
 
         def capture(b):
@@ -294,7 +332,7 @@ def measure(args, workload, arm, steps, warmup, batches, prof_kernels, streams):
             work = 0.0
             for k in range(steps):
                 for T in tabs:
-                    work += kernel_work(prof_name, T["shape"], T["batches"][(first + k) % nbatch], cfg.batch)
+                    work += kernel_work(prof_name, T["shape"], T["batches"][(first + k) % nbatch], T["bags"])
             bound, unit, peak, scale = KERNEL_BOUND[prof_name]
             if launches > 0 and kernel_ms > 0:
                 achieved = work / (kernel_ms * 1e-3) / scale
@@ -311,6 +349,8 @@ def measure(args, workload, arm, steps, warmup, batches, prof_kernels, streams):
     # contention, so the roofline of the dominant kernel is then taken from a second timed pass of
     # the same K steps on ONE pair, where the bracketed kernel has the chip to itself (this is also
     # the condition under which a rocprofv3 kernel trace, which serialises dispatches, sees it).
+    if streams <= 0:
+        streams = 2 if ntab != ntab_members else 8
     ns = max(1, min(streams, ntab))
     solo_main = ns == 1 and not args.graph and len(prof_kernels) == 1
     main_region = run_region(ns, warmup, steps, bracket=solo_main and bool(prof_kernels), use_graph=args.graph)
@@ -347,12 +387,14 @@ def measure(args, workload, arm, steps, warmup, batches, prof_kernels, streams):
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s: %d TT tables, D=%d, ranks (1,%d,%d,1), batch %d %s bags per table, "
                                "Zipf(alpha=%g)%s, %s, %s arm" %
-                               (workload, ntab, cfg.tables[0].dim, cfg.tables[0].r[1], cfg.tables[0].r[2],
+                               (workload, ntab_members, cfg.tables[0].dim, cfg.tables[0].r[1], cfg.tables[0].r[2],
                                 cfg.batch, "multi-hot" if cfg.multi_hot else "one-hot", cfg.alpha,
                                 (" + row permutation" if (args.permute or cfg.permute_rows) else "") +
                                 (" + offline index bijection" if args.bijection else ""),
-                                phases, arm),
-                   "lookups_per_step": lookups // max(1, steps), "tables": ntab,
+                                phases, arm) + (", tables fused into %d (lookup map inside the step)" % ntab
+                                                if ntab != ntab_members else ""),
+                   "lookups_per_step": lookups // max(1, steps), "tables": ntab_members,
+                   "fused_tables": ntab if ntab != ntab_members else 0,
                    "overlap_second_stream": (not args.no_overlap) and planned, "stream_pairs": ns,
                    "hip_graph_replay": bool(args.graph), "host_enqueue_threads": args.host_threads,
                    "host_enqueue_ms_per_step": round(1e3 * t_enqueue / steps, 3),
@@ -367,11 +409,12 @@ def measure(args, workload, arm, steps, warmup, batches, prof_kernels, streams):
         for k in range(steps):
             for T in tabs:
                 x = T["batches"][(first + k) % nbatch]
-                flops += kernel_work("fwd_contract", T["shape"], x, cfg.batch) + x["nnz"] * T["shape"].dim
-                bytes_ += 8.0 * x["nnz"] + 8.0 * (cfg.batch + 1) + 4.0 * cfg.batch * T["shape"].dim  # indices, offsets, out
+                nt = len(T.get("members", [0]))  # every member table brings its own offsets array
+                flops += kernel_work("fwd_contract", T["shape"], x, T["bags"]) + x["nnz"] * T["shape"].dim
+                bytes_ += 8.0 * x["nnz"] + 8.0 * (T["bags"] + nt) + 4.0 * T["bags"] * T["shape"].dim  # indices, offsets, out
                 if do_bwd:
-                    flops += kernel_work("bwd_contract", T["shape"], x, cfg.batch) + x["nnz"] * T["shape"].dim
-                    bytes_ += 4.0 * cfg.batch * T["shape"].dim  # output gradients
+                    flops += kernel_work("bwd_contract", T["shape"], x, T["bags"]) + x["nnz"] * T["shape"].dim
+                    bytes_ += 4.0 * T["bags"] * T["shape"].dim  # output gradients
         t_flop, t_hbm = flops / steps / (PEAK_FP32_TFLOPS * 1e12), bytes_ / steps / (PEAK_HBM_GBS * 1e9)
         result["config"]["step_bound_ms"] = {"fp32_mfma": round(1e3 * t_flop, 4), "hbm": round(1e3 * t_hbm, 4),
                                              "frac_of_measured": round(max(t_flop, t_hbm) / (dt / steps), 4)}
@@ -418,7 +461,9 @@ def main():
         return
     tt.load_library()
     headline_kernels = [args.prof_kernel] if args.prof_kernel != "auto" else ["auto"]
-    result = measure(args, args.workload, args.arm, args.steps, args.warmup, args.batches, headline_kernels, args.streams)
+    fuse = args.fuse if args.fuse >= 0 else (4 if args.workload == "cfg5" else 0)
+    result = measure(args, args.workload, args.arm, args.steps, args.warmup, args.batches, headline_kernels, args.streams,
+                     fuse=fuse)
     if args.other_configs and args.workload == "cfg5" and args.arm == "plan":
         # the other configurations the target names, in the same line: fewer steps and batches (the
         # naive arms take tens to hundreds of milliseconds per step)

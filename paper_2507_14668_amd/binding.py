@@ -427,23 +427,17 @@ def tt_plan_status(plan: Plan, stream=None) -> int:
 
 
 # ------------------------------------------------------------------ fused tables
-class FusedTables:
-    """Several TT tables with equal column factors and ranks stored as ONE table: core k of the fused
-    table is `[r_k][sum of the members' n_k][d_k][r_k+1]`, member t owning a range of the middle axis.
+class FusedLayout:
+    """Index space of several TT tables stored as one: `members` is a list of `(num_rows, (n1, n2, n3))`;
+    `n` are the fused row factors, `start[t][k]` member t's first index in fused core k.
+    `fuse_lookups` maps one batch of every member into the fused table; rows of the fused `out` /
+    `grad_out` are the members' bags, member after member (`bag_ranges`)."""
 
-    members   list of `(num_rows, (n1, n2, n3))`
-    cores     optional list (per member) of three flat fp32 tensors / arrays to start from; without
-              it the fused cores are left for the caller to fill (`member_core` gives the views)
-    `table` is the fused `Table` every single-table call of this module takes; `fuse_lookups` maps
-    one batch of every member into it; rows of the fused `out` / `grad_out` are the members' bags,
-    member after member (`bag_ranges`).
-    """
-
-    def __init__(self, members, d, r, cores=None, device="cuda"):
+    def __init__(self, members):
         members = [(int(nr), tuple(int(x) for x in n)) for nr, n in members]
         if not 1 <= len(members) <= TT_FUSE_MAX_TABLES:
             raise ValueError("1 to %d member tables" % TT_FUSE_MAX_TABLES)
-        self.members, self.d, self.r = members, tuple(d), tuple(r)
+        self.members = members
         c = CFuseMembers()
         c.num_tables = len(members)
         for t, (nr, n) in enumerate(members):
@@ -452,26 +446,8 @@ class FusedTables:
         self.c = c
         shape = CTable()
         _check(load_library().tt_fuse_shape(ctypes.byref(c), ctypes.byref(shape)), "tt_fuse_shape")
-        self.n = tuple(shape.n)
+        self.n, self.num_rows = tuple(shape.n), int(shape.num_rows)
         self.start = [[sum(m[1][k] for m in members[:t]) for k in range(3)] for t in range(len(members))]
-        fused = [torch.zeros(self.r[k] * self.n[k] * self.d[k] * self.r[k + 1], dtype=torch.float32, device=device)
-                 for k in range(3)]
-        self.table = Table(int(shape.num_rows), self.n, self.d, self.r, fused)
-        if cores is not None:
-            for t in range(len(members)):
-                for k in range(3):
-                    src = torch.as_tensor(cores[t][k]).to(device=device, dtype=torch.float32)
-                    self.member_core(t, k).copy_(src.view(self.r[k], members[t][1][k], self.d[k], self.r[k + 1]))
-
-    def core_view(self, k, core=None):
-        """Core k of the fused table (or a tensor of its size, e.g. a gradient) as `[r_k][N_k][d_k][r_k+1]`."""
-        core = self.table.cores[k] if core is None else core
-        return core.view(self.r[k], self.n[k], self.d[k], self.r[k + 1])
-
-    def member_core(self, t, k, core=None):
-        """Member t's part of (a tensor shaped like) fused core k: a strided view `[r_k][n_k(t)][d_k][r_k+1]`."""
-        o = self.start[t][k]
-        return self.core_view(k, core)[:, o:o + self.members[t][1][k]]
 
     def bag_ranges(self, num_bags):
         out, b0 = [], 0
@@ -504,6 +480,40 @@ class FusedTables:
                                             i64s(nnz), i64s(nb), _ptr(f_idx), _ptr(f_off), _stream(stream))
         _check(st, "tt_fuse_lookups")
         return f_idx, f_off
+
+
+class FusedTables(FusedLayout):
+    """Several TT tables with equal column factors and ranks stored as ONE table: core k of the fused
+    table is `[r_k][sum of the members' n_k][d_k][r_k+1]`, member t owning a range of the middle axis.
+
+    members   list of `(num_rows, (n1, n2, n3))`
+    cores     optional list (per member) of three flat fp32 tensors / arrays to start from; without
+              it the fused cores are zero and left for the caller to fill (`member_core` gives the views)
+    `table` is the fused `Table` that every single-table call of this module takes.
+    """
+
+    def __init__(self, members, d, r, cores=None, device="cuda"):
+        super().__init__(members)
+        self.d, self.r = tuple(d), tuple(r)
+        members = self.members
+        fused = [torch.zeros(self.r[k] * self.n[k] * self.d[k] * self.r[k + 1], dtype=torch.float32, device=device)
+                 for k in range(3)]
+        self.table = Table(self.num_rows, self.n, self.d, self.r, fused)
+        if cores is not None:
+            for t in range(len(members)):
+                for k in range(3):
+                    src = torch.as_tensor(cores[t][k]).to(device=device, dtype=torch.float32)
+                    self.member_core(t, k).copy_(src.view(self.r[k], members[t][1][k], self.d[k], self.r[k + 1]))
+
+    def core_view(self, k, core=None):
+        """Core k of the fused table (or a tensor of its size, e.g. a gradient) as `[r_k][N_k][d_k][r_k+1]`."""
+        core = self.table.cores[k] if core is None else core
+        return core.view(self.r[k], self.n[k], self.d[k], self.r[k + 1])
+
+    def member_core(self, t, k, core=None):
+        """Member t's part of (a tensor shaped like) fused core k: a strided view `[r_k][n_k(t)][d_k][r_k+1]`."""
+        o = self.start[t][k]
+        return self.core_view(k, core)[:, o:o + self.members[t][1][k]]
 
 
 def fusion_groups(members, groups=None, max_factor_sum=1023):

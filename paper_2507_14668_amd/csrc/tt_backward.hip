@@ -491,7 +491,7 @@ k_seg_whole(TTArg<BATCHED> arg, int nseg_a, int lanes_a, int parts_a, int lanes_
 #define TT_SEG_WHOLE_PARTS 8  // column parts of a core-0 segment
 #endif
 #ifndef TT_SEG_WHOLE_MAX_AVG
-#define TT_SEG_WHOLE_MAX_AVG 2048  // positions per segment (capacity / segments) up to which whole segments are used
+#define TT_SEG_WHOLE_MAX_AVG 4096  // positions per segment (capacity / segments) up to which whole segments are used
 #endif
 
 // The core-2 and core-0 reductions are independent.  With segments of moderate length they take one

@@ -18,6 +18,10 @@ Two more forward routes of the library are selectable:
     unchanged (it only needs the plan);
   * `bf16_inference()` / `forward_bf16(...)`: forward on bf16 copies of the cores with fp32
     accumulation, for inference (no gradient); the copies are refreshed on request.
+
+`TTFusedEmbeddingBags` holds SEVERAL tables of equal column factors and ranks as one fused TT table
+(cores side by side along the row-factor axis) and serves all of them with one reorder, one forward
+and one backward: what a model with many small tables needs to fill the GPU.
 """
 from __future__ import annotations
 
@@ -51,6 +55,22 @@ class _TTBagFunction(torch.autograd.Function):
             return None, None, None, None, None, None
         dcores = binding.tt_emb_bag_backward(ctx.table, ctx.plan, indices, offsets, grad_out)
         return dcores[0], dcores[1], dcores[2], None, None, None
+
+
+def _csr_offsets(input, offsets, include_last_offset):
+    """torch.nn.EmbeddingBag's (input, offsets) conventions -> flat indices + CSR offsets (bags + 1)."""
+    if input.dim() == 2:
+        if offsets is not None:
+            raise ValueError("offsets must be None for 2-D input")
+        bags, length = input.shape
+        offsets = torch.arange(0, (bags + 1) * length, length, dtype=torch.int64, device=input.device)
+        return input.reshape(-1).contiguous(), offsets
+    if input.dim() != 1 or offsets is None:
+        raise ValueError("1-D input needs offsets")
+    offsets = offsets.to(torch.int64)
+    if not include_last_offset:  # the library takes CSR offsets of length bags + 1
+        offsets = torch.cat([offsets, torch.full((1,), input.numel(), dtype=torch.int64, device=input.device)])
+    return input.contiguous(), offsets.contiguous()
 
 
 class TTEmbeddingBag(torch.nn.Module):
@@ -102,18 +122,7 @@ class TTEmbeddingBag(torch.nn.Module):
         return binding.Table(self.num_embeddings, self.n, self.d, self.r, [c.detach() for c in cores])
 
     def _bag_offsets(self, input, offsets):
-        if input.dim() == 2:
-            if offsets is not None:
-                raise ValueError("offsets must be None for 2-D input")
-            bags, length = input.shape
-            offsets = torch.arange(0, (bags + 1) * length, length, dtype=torch.int64, device=input.device)
-            return input.reshape(-1).contiguous(), offsets
-        if input.dim() != 1 or offsets is None:
-            raise ValueError("1-D input needs offsets")
-        offsets = offsets.to(torch.int64)
-        if not self.include_last_offset:  # the library takes CSR offsets of length bags + 1
-            offsets = torch.cat([offsets, torch.full((1,), input.numel(), dtype=torch.int64, device=input.device)])
-        return input.contiguous(), offsets.contiguous()
+        return _csr_offsets(input, offsets, self.include_last_offset)
 
     def forward(self, input, offsets=None, per_sample_weights=None):
         if per_sample_weights is not None:
@@ -160,6 +169,86 @@ class TTEmbeddingBag(torch.nn.Module):
             n2 += 1
         n1 = max(1, -(-num_embeddings // (n2 * n3)))
         return (n1, n2, n3)
+
+
+class TTFusedEmbeddingBags(torch.nn.Module):
+    """Several sum-pooling embedding bags of one embedding_dim, one set of column factors `d` and one
+    pair of ranks, held as ONE fused TT table: core k is `[r_k][sum of the tables' n_k][d_k][r_k+1]`
+    and table t owns a range of the middle axis of every core.  A row of table t is the product of
+    its own three slices (TT-matrix equation, Section II-B; index split per table, Section III-B), so
+    outputs and gradients are those of the separate tables -- computed with one reorder, one forward
+    and one backward for all of them.
+
+    tables    list of `(num_embeddings, (n1, n2, n3))`; the sums of the row factors must keep the
+              fused row count below 2^31 (split the tables over several modules otherwise:
+              `binding.fusion_groups` deals them out)
+    forward(inputs) takes one `(input, offsets)` pair (or a 2-D `input`) per table, as
+    `TTEmbeddingBag.forward` does, and returns the list of pooled outputs in table order (views of
+    one `[all bags x embedding_dim]` tensor).  `fused_sgd_lr` as for `TTEmbeddingBag`.
+    """
+
+    def __init__(self, tables, embedding_dim: int, d, ranks, include_last_offset: bool = False,
+                 init_row_std: float = 0.1, fused_sgd_lr=None, device="cuda", generator=None):
+        super().__init__()
+        d, ranks = tuple(int(x) for x in d), tuple(int(x) for x in ranks)
+        if len(d) != 3 or len(ranks) != 2 or d[0] * d[1] * d[2] != embedding_dim:
+            raise ValueError("three column factors with prod(d) == embedding_dim and two ranks are required")
+        tables = [(int(rows), tuple(int(x) for x in n)) for rows, n in tables]
+        for rows, n in tables:
+            if len(n) != 3 or n[0] * n[1] * n[2] < rows:
+                raise ValueError("every table needs three row factors with prod(n) >= num_embeddings")
+        self.tables, self.embedding_dim = tables, int(embedding_dim)
+        self.d, self.r = d, (1, ranks[0], ranks[1], 1)
+        self.include_last_offset = bool(include_last_offset)
+        self.fused_sgd_lr = None if fused_sgd_lr is None else float(fused_sgd_lr)
+        self.forward_route = "batch"
+        self.n = tuple(sum(n[k] for _, n in tables) for k in range(3))
+        self.num_embeddings = self.n[0] * self.n[1] * self.n[2]  # rows of the fused table
+        if self.num_embeddings >= 2 ** 31 - 1:
+            raise ValueError("the fused table would have 2^31 rows or more: fuse fewer tables")
+        self._fused = None  # binding.FusedLayout, built on first use (it needs the library)
+        s = (init_row_std ** 2 / (ranks[0] * ranks[1])) ** (1.0 / 6.0)
+        for k in range(3):
+            w = torch.empty(self.r[k] * self.n[k] * d[k] * self.r[k + 1], dtype=torch.float32, device=device)
+            w.normal_(0.0, s, generator=generator)
+            self.register_parameter("core%d" % k, torch.nn.Parameter(w))
+
+    def cores(self):
+        return [self.core0, self.core1, self.core2]
+
+    def member_core(self, t: int, k: int, core=None):
+        """Table t's part of fused core k (or of a tensor of its size, e.g. `.grad`): a strided view
+        `[r_k][n_k(t)][d_k][r_k+1]`."""
+        core = self.cores()[k] if core is None else core
+        o = sum(n[k] for _, n in self.tables[:t])
+        return core.view(self.r[k], self.n[k], self.d[k], self.r[k + 1])[:, o:o + self.tables[t][1][k]]
+
+    def _table(self, cores) -> binding.Table:
+        return binding.Table(self.num_embeddings, self.n, self.d, self.r, [c.detach() for c in cores])
+
+    def forward(self, inputs):
+        inputs = list(inputs)
+        if len(inputs) != len(self.tables):
+            raise ValueError("one input per table: got %d for %d tables" % (len(inputs), len(self.tables)))
+        if not self.core0.is_cuda:
+            raise RuntimeError("the TT embedding bag runs on the GPU only (there is no CPU path)")
+        idx, off = [], []
+        for x in inputs:
+            inp, o = x if isinstance(x, (tuple, list)) else (x, None)
+            if inp.dtype != torch.int64:
+                inp = inp.to(torch.int64)
+            i, o = _csr_offsets(inp, o, self.include_last_offset)
+            idx.append(i)
+            off.append(o)
+        if self._fused is None:
+            self._fused = binding.FusedLayout(self.tables)
+        f_idx, f_off = self._fused.fuse_lookups(idx, off)
+        out = _TTBagFunction.apply(self.core0, self.core1, self.core2, f_idx, f_off, self)
+        return list(torch.split(out, [o.numel() - 1 for o in off]))
+
+    def extra_repr(self) -> str:
+        return "%d tables fused into %s rows x %d, d=%s, ranks=%s" % (
+            len(self.tables), "x".join(str(x) for x in self.n), self.embedding_dim, self.d, self.r[1:3])
 
 
 class TTEmbeddingBagCollection(torch.nn.Module):

@@ -28,7 +28,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def _header_struct_fields(name):
-    """(field, array length or 0) of every member of `typedef struct { ... } name;` in the header."""
+    """(field, array suffix) of every member of `typedef struct { ... } name;` in the header."""
     text = open(os.path.join(ROOT, "include", "tt_emb.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     body = re.search(r"typedef struct \{([^}]*)\} %s;" % name, text).group(1)
@@ -38,8 +38,8 @@ def _header_struct_fields(name):
         if not decl:
             continue
         for part in decl.split(","):
-            m = re.search(r"(\w+)\s*(?:\[(\d+)\])?\s*$", part.strip())
-            fields.append((m.group(1), int(m.group(2) or 0)))
+            m = re.search(r"(\w+)\s*((?:\[\w+\])*)\s*$", part.strip())
+            fields.append((m.group(1), m.group(2)))
     return fields
 
 
@@ -49,7 +49,8 @@ def test_struct_mirrors_match_header_layout(tmp_path):
     the ctypes classes must have the same members at the same offsets."""
     import subprocess
     from paper_2507_14668_amd import binding
-    pairs = (("tt_table", binding.CTable), ("tt_plan", binding.CPlan), ("tt_batch_item", binding.CBatchItem))
+    pairs = (("tt_table", binding.CTable), ("tt_plan", binding.CPlan), ("tt_batch_item", binding.CBatchItem),
+             ("tt_fuse_members", binding.CFuseMembers))
     lines = ["#include <stdio.h>", "#include <stddef.h>", '#include "tt_emb.h"', "int main(void) {"]
     for cname, _ in pairs:
         lines.append('printf("%s sizeof %%zu\\n", sizeof(%s));' % (cname, cname))
@@ -103,3 +104,36 @@ def test_batched_entry_points_are_switched_off():
         assert getattr(lib, name)(1, items, None, 0, None) == binding.TT_ERR_UNAVAILABLE
     assert lib.tt_core_sgd_update_batched(1, items, 0.1, None, 0, None) == binding.TT_ERR_UNAVAILABLE
     assert lib.tt_batch_desc_bytes(4) > 0
+
+
+def test_fused_table_shape_and_host_validation_without_gpu():
+    """tt_fuse_shape is host arithmetic; tt_fuse_lookups rejects bad arguments before any launch."""
+    from paper_2507_14668_amd import binding
+    lib = binding.load_library()
+    assert binding.TT_FUSE_MAX_TABLES == int(re.search(r"#define TT_FUSE_MAX_TABLES (\d+)",
+                                                       open(os.path.join(ROOT, "include", "tt_emb.h")).read()).group(1))
+    layout = binding.FusedLayout([(1000, (10, 10, 10)), (55, (3, 4, 5)), (8, (2, 2, 2))])
+    assert layout.n == (15, 16, 17) and layout.num_rows == 15 * 16 * 17
+    assert layout.start == [[0, 0, 0], [10, 10, 10], [13, 14, 15]]
+    assert layout.bag_ranges([4, 0, 7]) == [(0, 4), (4, 4), (4, 11)]
+    m = binding.CFuseMembers()
+    t = binding.CTable()
+    assert lib.tt_fuse_shape(ctypes.byref(m), ctypes.byref(t)) == binding.TT_ERR_INVALID_ARG  # no members
+    m.num_tables = 2
+    for k in range(2):
+        m.n[k][:] = (1200, 1200, 1200)
+        m.num_rows[k] = 1200 ** 3
+    assert lib.tt_fuse_shape(ctypes.byref(m), ctypes.byref(t)) == binding.TT_ERR_SHAPE  # 2400^3 rows
+    m.n[1][:] = (3, 4, 5)
+    m.num_rows[1] = 61
+    assert lib.tt_fuse_shape(ctypes.byref(m), ctypes.byref(t)) == binding.TT_ERR_SHAPE  # more rows than 3*4*5
+    m.num_rows[1] = 60
+    assert lib.tt_fuse_shape(ctypes.byref(m), ctypes.byref(t)) == 0 and tuple(t.n) == (1203, 1204, 1205)
+    assert lib.tt_fuse_lookups(ctypes.byref(m), None, None, None, None, None, None, None, None) == binding.TT_ERR_INVALID_ARG
+    # deal-out helper: largest first, balanced, within the limits
+    members = [(n ** 3, (n, n, n)) for n in (10, 342, 26, 44, 500, 900, 31)]
+    parts = binding.fusion_groups(members)
+    assert sorted(t for p in parts for t in p) == list(range(7))
+    for p in parts:
+        assert sum(members[t][1][0] for t in p) <= 1023
+    assert len(binding.fusion_groups(members, groups=5)) == 5

@@ -168,3 +168,45 @@ def test_module_sample_route_and_bf16_inference(g, ora):
                         shape.dim, "module forward_bf16 after refresh")
     with pytest.raises(ValueError):
         _module_like(tt, shape, cores, forward_route="nope")
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("d,r", [((2, 3, 4), (1, 5, 6, 1)), ((4, 8, 4), (1, 32, 32, 1))])
+def test_fused_module_matches_oracle_per_table(g, ora, d, r):
+    """Several tables in one fused module: every table's outputs, autograd gradients and (fused-update
+    mode) updated cores against the oracle on that table alone."""
+    import paper_2507_14668_amd as tt
+    print("case fused module d=%s r=%s" % (d, r), flush=True)
+    ns = [(6, 5, 7), (3, 4, 2), (2, 9, 5)]
+    probs = [wl.small_random_problem(200 + t, n=n, d=d, r=r, num_bags=60 + 25 * t, max_len=5, sigma=0.2) for t, n in enumerate(ns)]
+    tables = [(p[0].num_rows, p[0].n) for p in probs]
+    dim = d[0] * d[1] * d[2]
+
+    def build(**kw):
+        m = tt.TTFusedEmbeddingBags(tables, dim, d, r[1:3], **kw)
+        with torch.no_grad():
+            for t, p in enumerate(probs):
+                for k in range(3):
+                    m.member_core(t, k).copy_(torch.from_numpy(p[1][k]).view(p[0].core_shape(k)))
+        return m
+
+    inputs = [(g.to_dev(p[2], torch.int64), g.to_dev(p[3], torch.int64)[:-1]) for p in probs]
+    m = build()
+    outs = m(inputs)
+    loss = sum((o * g.to_dev(p[4], torch.float32).view_as(o)).sum() for o, p in zip(outs, probs))
+    loss.backward()
+    for t, (shape, cores, idx, off, grad) in enumerate(probs):
+        g.assert_close_rows(outs[t].detach().cpu().numpy(), ora.forward(shape, cores, idx, off), g.FWD_RTOL, shape.dim,
+                            "fused module forward table %d" % t)
+        got = [m.member_core(t, k, core=m.cores()[k].grad).contiguous().view(-1) for k in range(3)]
+        g.assert_grads_close(shape, got, ora.backward(shape, cores, idx, off, grad), what="fused module dG table %d " % t)
+    lr = 0.05
+    mf = build(fused_sgd_lr=lr)
+    outs_f = mf(inputs)
+    sum((o * g.to_dev(p[4], torch.float32).view_as(o)).sum() for o, p in zip(outs_f, probs)).backward()
+    torch.cuda.synchronize()
+    assert all(c.grad is None for c in mf.cores())
+    for t, (shape, cores, idx, off, grad) in enumerate(probs):
+        got = [mf.member_core(t, k).detach().contiguous().view(-1) for k in range(3)]
+        g.assert_grads_close(shape, got, ora.sgd(cores, ora.backward(shape, cores, idx, off, grad), lr),
+                             what="fused module updated G table %d " % t)
