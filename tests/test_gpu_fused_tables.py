@@ -187,3 +187,55 @@ def test_config4_two_tables_fused_full_size(g, ora):
         probs.append((cfg.tables[t], wl.make_cores(cfg, t), idx, off, wl.make_grad(cfg, t)))
     print("case cfg4 fused tables 2+5", flush=True)
     run_fused(g, ora, probs, "cfg4 fused", lr=cfg.lr)
+
+
+def test_fused_two_stream_pipeline_equals_sequential(g):
+    """The step as bench.py runs it: the lookup map and the reorder of batch b+1 on a second stream
+    (two plan buffers, two pairs of fused index buffers) while batch b computes -- bitwise equal to
+    running everything on one stream."""
+    import paper_2507_14668_amd as tt
+    print("case fused pipeline", flush=True)
+    cfg = wl.get_config(5)
+    members, nb, nbatch = [0, 7, 13, 23], 4096, 5
+    shapes = [cfg.tables[t] for t in members]
+    host = [[wl.make_batch(cfg, t, batch=b, num_bags=nb) for t in members] for b in range(nbatch)]
+    dev = [[(g.to_dev(i, torch.int64), g.to_dev(o, torch.int64)) for i, o in hb] for hb in host]
+    grads = [g.to_dev(np.concatenate([wl.make_grad(cfg, t, batch=b, num_bags=nb) for t in members]), torch.float32)
+             for b in range(nbatch)]
+
+    def run(pipelined):
+        fused = tt.FusedTables([(s.num_rows, s.n) for s in shapes], shapes[0].d, shapes[0].r,
+                               cores=[wl.make_cores(cfg, t) for t in members])
+        s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+        rs = s2 if pipelined else s1
+        nnz, bags = nb * len(members), nb * len(members)
+        ws = [tt.alloc_workspace(fused.table, nnz, bags) for _ in range(2)]
+        fbuf = [(torch.empty(nnz, dtype=torch.int64, device="cuda"), torch.empty(bags + 1, dtype=torch.int64, device="cuda"))
+                for _ in range(2)]
+        ready = [torch.cuda.Event(), torch.cuda.Event()]
+        free = [torch.cuda.Event(), torch.cuda.Event()]
+        torch.cuda.synchronize()
+
+        def plan_of(b, buf):
+            fi, fo = fused.fuse_lookups([x[0] for x in dev[b]], [x[1] for x in dev[b]], out=fbuf[buf], stream=rs)
+            p = tt.tt_index_reorder(fused.table, fi, fo, workspace=ws[buf], stream=rs)
+            ready[buf].record(rs)
+            return p
+
+        plans, outs = [plan_of(0, 0), None], []
+        for b in range(nbatch):
+            cur, nxt = b % 2, (b + 1) % 2
+            if b + 1 < nbatch:
+                if b >= 1:
+                    rs.wait_event(free[nxt])
+                plans[nxt] = plan_of(b + 1, nxt)
+            s1.wait_event(ready[cur])
+            outs.append(tt.tt_emb_bag_forward(fused.table, plans[cur], fbuf[cur][0], fbuf[cur][1], stream=s1))
+            tt.tt_emb_bag_backward_sgd(fused.table, plans[cur], fbuf[cur][0], fbuf[cur][1], grads[b], cfg.lr, stream=s1)
+            free[cur].record(s1)
+        torch.cuda.synchronize()
+        return [o.clone() for o in outs], [c.clone() for c in fused.table.cores]
+
+    seq, pipe = run(False), run(True)
+    for a, b in zip(seq[0] + seq[1], pipe[0] + pipe[1]):
+        assert torch.equal(a, b)
