@@ -79,7 +79,6 @@ def measure(args, workload, arm, steps, warmup, batches, prof_kernels, streams, 
 
     cfg_id = int(workload[3:])
     cfg = wl.get_config(cfg_id)
-    do_fwd = True
     do_bwd = cfg_id != 3
     ntab = len(cfg.tables) if args.tables <= 0 else min(args.tables, len(cfg.tables))
     nbatch = max(2, batches + (batches % 2))  # even, so batch b always uses plan buffer b%2
