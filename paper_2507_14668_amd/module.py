@@ -259,37 +259,81 @@ class TTEmbeddingBagCollection(torch.nn.Module):
     streams   number of side streams the tables are dealt to in forward (1: the current stream).
               Tables are independent and a table's kernels are short, so several streams let the
               GPU overlap them; autograd runs a table's backward on the stream of its forward.
+    fuse      store tables of one family (same column factors, ranks, offset convention and update
+              mode) as fused tables (`TTFusedEmbeddingBags`, dealt out by `binding.fusion_groups`) and
+              serve each fused table with one set of launches.  The parameters are then the fused
+              cores (`self.fused[g].core0..2`; `member_core` gives a table's part); the given tables'
+              core values are copied in.  `fuse_groups`: number of fused tables per family (None: the
+              fewest the limits allow).
     forward(inputs) takes one `(input, offsets)` pair (or a 2-D `input`) per table and returns the
     list of pooled outputs `[bags x embedding_dim]`, in table order.
     """
 
-    def __init__(self, tables, streams: int = 1):
+    def __init__(self, tables, streams: int = 1, fuse: bool = False, fuse_groups=None):
         super().__init__()
-        self.tables = torch.nn.ModuleList(
-            [t if isinstance(t, TTEmbeddingBag) else TTEmbeddingBag(**t) for t in tables])
+        tables = [t if isinstance(t, TTEmbeddingBag) else TTEmbeddingBag(**t) for t in tables]
         if streams < 1:
             raise ValueError("streams must be at least 1")
         self.num_streams = int(streams)
         self._side = None
+        self.num_tables = len(tables)
+        if not fuse:
+            self.tables = torch.nn.ModuleList(tables)
+            self.fused, self._where = None, None
+            return
+        self.tables = None
+        families = {}
+        for t, bag in enumerate(tables):
+            key = (bag.d, bag.r, bag.include_last_offset, bag.fused_sgd_lr, bag.core0.device)
+            families.setdefault(key, []).append(t)
+        fused, where = [], [None] * len(tables)
+        for (d, r, last, lr, dev), idxs in families.items():
+            members = [(tables[t].num_embeddings, tables[t].n) for t in idxs]
+            for part in binding.fusion_groups(members, groups=fuse_groups):
+                m = TTFusedEmbeddingBags([members[p] for p in part], d[0] * d[1] * d[2], d, r[1:3],
+                                         include_last_offset=last, fused_sgd_lr=lr, device=dev)
+                with torch.no_grad():
+                    for pos, p in enumerate(part):
+                        src = tables[idxs[p]]
+                        for k in range(3):
+                            m.member_core(pos, k).copy_(src.cores()[k].view(r[k], src.n[k], d[k], r[k + 1]))
+                        where[idxs[p]] = (len(fused), pos)
+                fused.append(m)
+        self.fused = torch.nn.ModuleList(fused)
+        self._where = where
 
     def forward(self, inputs):
         inputs = list(inputs)
-        if len(inputs) != len(self.tables):
-            raise ValueError("one input per table: got %d for %d tables" % (len(inputs), len(self.tables)))
-        pairs = [x if isinstance(x, (tuple, list)) else (x, None) for x in inputs]
+        if len(inputs) != self.num_tables:
+            raise ValueError("one input per table: got %d for %d tables" % (len(inputs), self.num_tables))
+        if self.fused is not None:
+            per_group = [[None] * len(m.tables) for m in self.fused]
+            for t, x in enumerate(inputs):
+                gi, pos = self._where[t]
+                per_group[gi][pos] = x
+            units = [(m, xs) for m, xs in zip(self.fused, per_group)]
+            run = lambda unit: unit[0](unit[1])
+        else:
+            pairs = [x if isinstance(x, (tuple, list)) else (x, None) for x in inputs]
+            units = list(zip(self.tables, pairs))
+            run = lambda unit: unit[0](unit[1][0], unit[1][1])
         if self.num_streams == 1:
-            return [bag(inp, off) for bag, (inp, off) in zip(self.tables, pairs)]
-        if self._side is None:
-            self._side = [torch.cuda.Stream() for _ in range(self.num_streams)]
-        cur = torch.cuda.current_stream()
-        for s in self._side:
-            s.wait_stream(cur)
-        outs = []
-        for i, (bag, (inp, off)) in enumerate(zip(self.tables, pairs)):
-            with torch.cuda.stream(self._side[i % self.num_streams]):
-                outs.append(bag(inp, off))
-        for s in self._side:
-            cur.wait_stream(s)
-        for o in outs:
-            o.record_stream(cur)
-        return outs
+            results = [run(u) for u in units]
+        else:
+            if self._side is None:
+                self._side = [torch.cuda.Stream() for _ in range(self.num_streams)]
+            cur = torch.cuda.current_stream()
+            for s in self._side:
+                s.wait_stream(cur)
+            results = []
+            for i, u in enumerate(units):
+                with torch.cuda.stream(self._side[i % self.num_streams]):
+                    results.append(run(u))
+            for s in self._side:
+                cur.wait_stream(s)
+            for r in results:
+                for o in (r if isinstance(r, list) else [r]):
+                    o.record_stream(cur)
+        if self.fused is None:
+            return results
+        return [results[gi][pos] for gi, pos in self._where]

@@ -25,6 +25,23 @@ def test_module_argument_checks_and_shapes():
         assert n[0] * n[1] * n[2] >= rows and (n[0] - 1) * n[1] * n[2] < rows and max(n) - min(n) <= max(1, n[2])
 
 
+def test_fused_collection_layout_on_cpu():
+    """Construction only (no launch): families by (d, ranks), core values copied into the members' views."""
+    import paper_2507_14668_amd as tt
+    bags = [tt.TTEmbeddingBag(1000, 16, n=(10, 10, 10), d=(2, 2, 4), ranks=(4, 4), device="cpu"),
+            tt.TTEmbeddingBag(60, 16, n=(3, 4, 5), d=(2, 2, 4), ranks=(3, 4), device="cpu"),
+            tt.TTEmbeddingBag(60, 16, n=(3, 4, 5), d=(2, 2, 4), ranks=(4, 4), device="cpu")]
+    coll = tt.TTEmbeddingBagCollection(bags, fuse=True)
+    assert coll._where == [(0, 0), (1, 0), (0, 1)] and coll.fused[0].n == (13, 14, 15)
+    for t, bag in enumerate(bags):
+        gi, pos = coll._where[t]
+        for k in range(3):
+            assert torch.equal(coll.fused[gi].member_core(pos, k).contiguous().view(-1), bag.cores()[k])
+    assert sum(p.numel() for p in coll.parameters()) == sum(p.numel() for b in bags for p in b.parameters())
+    with pytest.raises(ValueError):
+        tt.TTFusedEmbeddingBags([(10 ** 9, (1000, 1000, 1000)), (10 ** 9, (1000, 1000, 1000))], 16, (2, 2, 4), (4, 4), device="meta")
+
+
 @pytest.fixture(scope="module")
 def g():
     import gpu_util
@@ -210,3 +227,31 @@ def test_fused_module_matches_oracle_per_table(g, ora, d, r):
         got = [mf.member_core(t, k).detach().contiguous().view(-1) for k in range(3)]
         g.assert_grads_close(shape, got, ora.sgd(cores, ora.backward(shape, cores, idx, off, grad), lr),
                              what="fused module updated G table %d " % t)
+
+
+@pytest.mark.gpu
+def test_fused_collection_matches_oracle_per_table(g, ora):
+    """A collection with `fuse=True`: tables of two families (different ranks) interleaved; each family
+    becomes fused tables, outputs come back in table order and match the oracle table by table; the
+    gradients of the fused cores, cut per table, match the oracle's."""
+    import paper_2507_14668_amd as tt
+    print("case fused collection", flush=True)
+    specs = [((6, 5, 7), (4, 8, 4), (1, 32, 32, 1)), ((3, 4, 11), (2, 3, 4), (1, 5, 6, 1)), ((9, 3, 5), (4, 8, 4), (1, 32, 32, 1)),
+             ((2, 2, 3), (2, 3, 4), (1, 5, 6, 1)), ((4, 4, 4), (4, 8, 4), (1, 32, 32, 1))]
+    problems = [wl.small_random_problem(500 + k, n=n, d=d, r=r, num_bags=120 + 10 * k, max_len=4, sigma=0.3)
+                for k, (n, d, r) in enumerate(specs)]
+    coll = tt.TTEmbeddingBagCollection([_module_like(tt, p[0], p[1], include_last_offset=True) for p in problems],
+                                       streams=2, fuse=True)
+    assert len(coll.fused) == 2 and sorted(len(m.tables) for m in coll.fused) == [2, 3]
+    inputs = [(torch.from_numpy(p[2]).cuda(), torch.from_numpy(p[3]).cuda()) for p in problems]
+    outs = coll(inputs)
+    loss = sum((o * torch.from_numpy(p[4]).cuda().view_as(o)).sum() for o, p in zip(outs, problems))
+    loss.backward()
+    torch.cuda.synchronize()
+    for t, (shape, cores, idx, off, grad) in enumerate(problems):
+        g.assert_close_rows(outs[t].detach().cpu().numpy(), ora.forward(shape, cores, idx, off), g.FWD_RTOL, shape.dim,
+                            "fused collection forward table %d" % t)
+        gi, pos = coll._where[t]
+        m = coll.fused[gi]
+        got = [m.member_core(pos, k, core=m.cores()[k].grad).contiguous().view(-1) for k in range(3)]
+        g.assert_grads_close(shape, got, ora.backward(shape, cores, idx, off, grad), what="fused collection dG table %d " % t)
