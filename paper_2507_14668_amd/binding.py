@@ -518,7 +518,7 @@ class FusedTables(FusedLayout):
 
 def fusion_groups(members, groups=None, max_factor_sum=1023):
     """Deals tables to fused groups: `members` is a list of `(num_rows, n)`; returns lists of member
-    positions.  Largest tables first, each into the group with the smallest sum of row factors so
+    positions, largest member first.  Largest tables first, each into the group with the smallest sum of row factors so
     far; `groups=None` takes the fewest groups whose factor sums stay within `max_factor_sum` (1023
     keeps every grouping of the reorder a single radix digit) and whose rows stay below 2^31."""
     order = sorted(range(len(members)), key=lambda t: -max(members[t][1]))
@@ -535,7 +535,7 @@ def fusion_groups(members, groups=None, max_factor_sum=1023):
         if ok or g >= len(members):
             if not ok:
                 raise ValueError("no fusion of these tables fits the limits")
-            return [sorted(p) for p in parts if p]
+            return [p for p in parts if p]  # largest member first: its long-running workgroups start early
         g += 1
 
 
