@@ -471,8 +471,13 @@ def main():
                                     ("cfg3", "sample", 10, ["bag_chains", "p12_fill"]),
                                     ("cfg3", "bf16", 10, ["fwd_contract"]),
                                     ("cfg4", "plan", 10, ["bwd_contract", "grad_merge", "fwd_contract", "bag_sum"]),
-                                    ("cfg4", "naive", 2, [])):
-            r = measure(args, wk, arm_, st_, 2 if arm_ != "naive" else 1, 2, kern, args.streams)
+                                    ("cfg4", "naive", 2, []),
+                                    # the headline workload with one call per table instead of fused tables
+                                    ("cfg5", "plan_per_table", 10, ["bwd_contract", "fwd_contract"])):
+            if arm_ == "plan_per_table":
+                r = measure(args, wk, "plan", st_, 2, 2, kern, args.streams, fuse=0)
+            else:
+                r = measure(args, wk, arm_, st_, 2 if arm_ != "naive" else 1, 2, kern, args.streams)
             entry = {"ms_per_step": r["ms_per_step"], "lookups_per_s": r["value"], "steps": st_,
                      "workload": r["config"]["workload"]}
             for key in ("bag_prefix_groups_batch0", "lookups_batch0", "distinct_rows_last_batch", "distinct_prefixes_last_batch"):
