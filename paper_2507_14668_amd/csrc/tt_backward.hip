@@ -39,6 +39,14 @@ struct Vec {
       v[0] = *p;
     }
   }
+  __device__ __forceinline__ void load_stream(const float *p) {  // data read exactly once
+    if (VEC == 4) {
+      const float4 t = tt_load_stream4(p);
+      v[0] = t.x; v[1 % VEC] = t.y; v[2 % VEC] = t.z; v[3 % VEC] = t.w;
+    } else {
+      v[0] = *p;
+    }
+  }
   __device__ __forceinline__ void store(float *p) const {
     if (VEC == 4) *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1 % VEC], v[2 % VEC], v[3 % VEC]);
     else *p = v[0];
@@ -80,15 +88,18 @@ struct SegView {
   float *partial;
   int fused;                 // out is the core itself: finished sums are applied as out -= lr * sum
   float lr;
+  int stream_src;            // every source vector is read once: non-temporal loads
 };
 __device__ __forceinline__ SegView seg_view(const TTDev &d, int kind) {
   SegView v;
   v.partial = d.plan.partial;
   v.fused = 0; v.lr = d.lr;
+  v.stream_src = 1;  // the hand-off buffers are read once; the output gradients only with one lookup per bag
   if (kind == SEG_GAGG) {  // merge grad_out over the occurrences of each distinct row
     v.W = d.sh.D; v.count_ptr = d.plan.counts + 2; v.seg_src = d.plan.slot_of_sorted; v.seg_div = 1;
     v.gidx = d.plan.bag_of_sorted; v.seg_off = d.plan.row_seg; v.src = d.grad_out; v.nsub = 1;
     v.out = d.plan.gagg; v.out_inner = d.sh.D; v.nseg = (int)d.plan.max_rows; v.dense = 0;
+    v.stream_src = d.nnz == d.num_bags;
   } else if (kind == SEG_DG3) {  // core 2: per-row contributions of all rows sharing i3
     v.W = d.sh.S3; v.count_ptr = d.plan.counts + 0; v.seg_src = d.plan.i3_of_sorted; v.seg_div = 1;
     v.gidx = d.plan.rows_by_i3; v.seg_off = d.plan.i3_seg; v.src = d.plan.t3buf; v.nsub = 1;
@@ -136,7 +147,7 @@ k_seg_stage1(TTArg<BATCHED> arg, SegLaunch L, int lanes) {
   float *__restrict__ out = sv.out, *__restrict__ partial = sv.partial + pk.poff;
   const int M = *sv.count_ptr;
   const int nchunks = (M + chunk - 1) / chunk;
-  const int fused = sv.fused;
+  const int fused = sv.fused, stream_src = sv.stream_src;
   const float lr = sv.lr;
   const int groups = blockDim.x / lanes, g = threadIdx.x / lanes, lane = threadIdx.x - g * lanes;
   extern __shared__ float red[];  // [groups][W]
@@ -170,7 +181,8 @@ k_seg_stage1(TTArg<BATCHED> arg, SegLaunch L, int lanes) {
       } else if (active) acc.store(partial + ((size_t)c * 2 + (starts_in ? 1 : 0)) * W + e);
     };
     auto load_row = [&](int row, int e, Vec<VEC> &x) {
-      x.load(src + (size_t)row * nsub * W + e);
+      if (stream_src) x.load_stream(src + (size_t)row * nsub * W + e);
+      else x.load(src + (size_t)row * nsub * W + e);
       for (int t = 1; t < nsub; ++t) {
         Vec<VEC> y;
         y.load(src + ((size_t)row * nsub + t) * W + e);
@@ -448,10 +460,10 @@ k_seg_whole(TTArg<BATCHED> arg, int nseg_a, int lanes_a, int parts_a, int lanes_
   }
   auto load_pos = [&](int pos, int e, Vec<VEC> &x) {
     const int row = gidx ? gidx[pos] : pos;
-    x.load(src + (size_t)row * nsub * W + e0 + e);
+    x.load_stream(src + (size_t)row * nsub * W + e0 + e);  // hand-off buffers: every vector is read once
     for (int t = 1; t < nsub; ++t) {
       Vec<VEC> y;
-      y.load(src + ((size_t)row * nsub + t) * W + e0 + e);
+      y.load_stream(src + ((size_t)row * nsub + t) * W + e0 + e);
       x.add(y);
     }
   };

@@ -137,7 +137,7 @@ k_bag_sum(TTArg<BATCHED> a, int lanes) {
 #pragma unroll
         for (int v = 0; v < VEC; ++v) t[v] = 0.f + (0.f + x[k][v]);
         float *dst = out + (size_t)(b + k * stride) * D + c;
-        if (VEC == 4) *reinterpret_cast<float4 *>(dst) = make_float4(t[0], t[1 % VEC], t[2 % VEC], t[3 % VEC]);
+        if (VEC == 4) tt_store_stream4(dst, t[0], t[1 % VEC], t[2 % VEC], t[3 % VEC]);
         else dst[0] = t[0];
       }
     }
@@ -178,8 +178,7 @@ k_bag_sum(TTArg<BATCHED> a, int lanes) {
         for (int v = 0; v < VEC; ++v) tot[v] += acc[v];
       }
       if (VEC == 4) {
-        *reinterpret_cast<float4 *>(out + (size_t)b * D + c) =
-            make_float4(tot[0], tot[1 % VEC], tot[2 % VEC], tot[3 % VEC]);
+        tt_store_stream4(out + (size_t)b * D + c, tot[0], tot[1 % VEC], tot[2 % VEC], tot[3 % VEC]);
       } else {
         out[(size_t)b * D + c] = tot[0];
       }
