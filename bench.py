@@ -459,7 +459,9 @@ def main():
                           "bytes_written_per_launch": 4 * n}))
         return
     tt.load_library()
-    headline_kernels = [args.prof_kernel] if args.prof_kernel != "auto" else ["auto"]
+    # the dominant kernel first (-> `roofline`); with the default choice also the other kernels of the step
+    headline_kernels = [args.prof_kernel] if args.prof_kernel != "auto" else (
+        ["auto", "fwd_contract", "bag_sum", "grad_merge"] if args.arm == "plan" and args.workload != "cfg3" else ["auto"])
     fuse = args.fuse if args.fuse >= 0 else (4 if args.workload == "cfg5" else 0)
     result = measure(args, args.workload, args.arm, args.steps, args.warmup, args.batches, headline_kernels, args.streams,
                      fuse=fuse)
@@ -490,7 +492,10 @@ def main():
                                     for k, v in r["kernel_rooflines"].items()}
             other["%s_%s" % (wk, arm_)] = entry
         result["other_configs"] = other
-    result.pop("kernel_rooflines", None)
+    kr = result.pop("kernel_rooflines", None) or {}
+    if len(kr) > 1:  # the step's other kernels, each from its own timed pass on one stream pair
+        result["kernels"] = {k: {x: v[x] for x in ("bound", "achieved", "peak", "unit", "frac", "avg_launch_us")}
+                             for k, v in kr.items()}
     cfg = __import__("tt_workloads").get_config(int(args.workload[3:]))
     wl = __import__("tt_workloads")
     np = __import__("numpy")
