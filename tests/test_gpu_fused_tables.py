@@ -239,3 +239,19 @@ def test_fused_two_stream_pipeline_equals_sequential(g):
     seq, pipe = run(False), run(True)
     for a, b in zip(seq[0] + seq[1], pipe[0] + pipe[1]):
         assert torch.equal(a, b)
+
+
+def test_fused_seeded_random_members(g, ora):
+    """Twelve seeded random fused tables: two to seven members with random row factors, row counts
+    (some padded), batch sizes and bag lengths, on both kernel families."""
+    rng = np.random.default_rng(20251)
+    for case in range(12):
+        mfma = case % 2 == 0
+        d, r = ((4, 8, 4), (1, 32, 32, 1) if case % 4 == 0 else (1, 64, 64, 1)) if mfma else ((2, 3, 2), (1, int(rng.integers(2, 6)), int(rng.integers(2, 6)), 1))
+        members = int(rng.integers(2, 8))
+        ns = [tuple(int(x) for x in rng.integers(1, 13, size=3)) for _ in range(members)]
+        rows = [int(rng.integers(max(1, n[0] * n[1] * n[2] - n[2] + 1), n[0] * n[1] * n[2] + 1)) for n in ns]
+        bags = [int(rng.integers(0, 70)) for _ in range(members)]
+        print("case fused random %d d=%s r=%s ns=%s rows=%s bags=%s" % (case, d, r, ns, rows, bags), flush=True)
+        probs = make_members(7000 + 10 * case, ns, d, r, num_bags=bags, max_len=int(rng.integers(1, 9)), num_rows=rows)
+        run_fused(g, ora, probs, "fused random %d" % case)
