@@ -466,20 +466,20 @@ def main():
     result = measure(args, args.workload, args.arm, args.steps, args.warmup, args.batches, headline_kernels, args.streams,
                      fuse=fuse)
     if args.other_configs and args.workload == "cfg5" and args.arm == "plan":
-        # the other configurations the target names, in the same line: fewer steps and batches (the
-        # naive arms take tens to hundreds of milliseconds per step)
+        # the other configurations the target names, in the same line: two batches each, and few steps for
+        # the naive arms (they take tens to hundreds of milliseconds per step)
         other = {}
-        for wk, arm_, st_, kern in (("cfg3", "plan", 10, ["fwd_contract", "bag_sum"]), ("cfg3", "naive", 3, []),
-                                    ("cfg3", "sample", 10, ["bag_chains", "p12_fill"]),
-                                    ("cfg3", "bf16", 10, ["fwd_contract"]),
-                                    ("cfg4", "plan", 10, ["bwd_contract", "grad_merge", "fwd_contract", "bag_sum"]),
+        for wk, arm_, st_, kern in (("cfg3", "plan", 30, ["fwd_contract", "bag_sum"]), ("cfg3", "naive", 3, []),
+                                    ("cfg3", "sample", 30, ["bag_chains", "p12_fill"]),
+                                    ("cfg3", "bf16", 30, ["fwd_contract"]),
+                                    ("cfg4", "plan", 30, ["bwd_contract", "grad_merge", "fwd_contract", "bag_sum"]),
                                     ("cfg4", "naive", 2, []),
                                     # the headline workload with one call per table instead of fused tables
-                                    ("cfg5", "plan_per_table", 10, ["bwd_contract", "fwd_contract"])):
+                                    ("cfg5", "plan_per_table", 20, ["bwd_contract", "fwd_contract"])):
             if arm_ == "plan_per_table":
-                r = measure(args, wk, "plan", st_, 2, 2, kern, args.streams, fuse=0)
+                r = measure(args, wk, "plan", st_, 3, 2, kern, args.streams, fuse=0)
             else:
-                r = measure(args, wk, arm_, st_, 2 if arm_ != "naive" else 1, 2, kern, args.streams)
+                r = measure(args, wk, arm_, st_, 3 if arm_ != "naive" else 1, 2, kern, args.streams)
             entry = {"ms_per_step": r["ms_per_step"], "lookups_per_s": r["value"], "steps": st_,
                      "workload": r["config"]["workload"]}
             for key in ("bag_prefix_groups_batch0", "lookups_batch0", "distinct_rows_last_batch", "distinct_prefixes_last_batch"):
