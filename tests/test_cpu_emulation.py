@@ -114,6 +114,9 @@ def _run(emu, shape, cores, idx, off, grad, lr):
     # than 32 distinct rows (row batches that cut a prefix's rows at any position)
     ("mfma_r32_refill", (75, 1, 3), (4, 8, 4), (1, 32, 32, 1), 400, 3),
     ("mfma_r64_row_batches", (2, 2, 45), (4, 8, 4), (1, 64, 64, 1), 300, 4),
+    # row factors above 1023: the groupings by i2 / i3 become radix sorts of more than one digit
+    ("mfma_r32_wide_n2", (1, 2100, 2), (4, 8, 4), (1, 32, 32, 1), 200, 3),
+    ("plain_wide_n3", (2, 1, 1500), (2, 3, 2), (1, 3, 5, 1), 300, 3),
 ])
 def test_emulated_kernels_match_oracle(emu, ora, name, n, d, r, nb, ml):
     import gpu_util as g
@@ -202,7 +205,8 @@ def asan_harness():
     return emu_build.build_harness(BUILD_DIR, "address")
 
 
-@pytest.mark.parametrize("kind,shuffle", [("mfma", None), ("plain", None), ("unaligned", None), ("mfma", "11"), ("plain", "12")])
+@pytest.mark.parametrize("kind,shuffle", [("mfma", None), ("plain", None), ("unaligned", None), ("wide", None), ("mfma", "11"),
+                                          ("plain", "12")])
 def test_sanitized_single_and_batched_calls(asan_harness, kind, shuffle):
     """Every entry point under AddressSanitizer + UBSan.  While a launch runs, the host structs of the
     C ABI (tables, plans, batch items) and the library's host copies of the table descriptors are

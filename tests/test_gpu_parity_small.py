@@ -70,6 +70,8 @@ def run_all(g, ora, shape, cores, idx, off, grad, lr=0.01, check_plan=True, rema
     (3, (5, 2, 7), (1, 4, 3), (1, 5, 2, 1), 300, 9),
     (4, (7, 6, 5), (4, 2, 4), (1, 8, 16, 1), 1000, 12),
     (5, (1, 1, 9), (2, 2, 2), (1, 1, 1, 1), 50, 4),
+    (6, (2, 1, 1500), (2, 3, 2), (1, 3, 5, 1), 700, 4),   # a row factor above 1023: grouping sorts of two digits
+    (7, (1, 3000, 3), (2, 3, 2), (1, 3, 4, 1), 900, 5),
 ])
 def test_small_shapes(g, ora, seed, n, d, r, nb, ml):
     print("case small_shapes seed=%d n=%s d=%s r=%s" % (seed, n, d, r), flush=True)
@@ -86,6 +88,8 @@ def test_small_shapes(g, ora, seed, n, d, r, nb, ml):
     (67, (150, 1, 5), (1, 64, 64, 1), 2500, 3),
     (68, (3, 2, 90), (1, 64, 64, 1), 1500, 5),    # up to 90 distinct rows per prefix: several row batches
     (69, (2, 3, 70), (1, 32, 32, 1), 1200, 4),
+    (70, (1, 2100, 2), (1, 32, 32, 1), 1500, 3),  # a row factor above 1023: grouping sorts of two digits
+    (71, (1, 2, 1100), (1, 64, 64, 1), 800, 4),
 ])
 def test_matrix_core_shapes(g, ora, seed, n, r, nb, ml):
     """Shapes served by the MFMA kernels (d = 4x8x4, ranks 32 or 64) on small tables."""
