@@ -117,6 +117,9 @@ def _run(emu, shape, cores, idx, off, grad, lr):
     # row factors above 1023: the groupings by i2 / i3 become radix sorts of more than one digit
     ("mfma_r32_wide_n2", (1, 2100, 2), (4, 8, 4), (1, 32, 32, 1), 200, 3),
     ("plain_wide_n3", (2, 1, 1500), (2, 3, 2), (1, 3, 5, 1), 300, 3),
+    # few i1 / i3 values under thousands of prefixes and rows: the core-0 / core-2 reductions leave the
+    # whole-segment kernel for the two-stage sum (capacity per segment above 4096)
+    ("mfma_r32_long_segments", (1, 5000, 2), (4, 8, 4), (1, 32, 32, 1), 3000, 7),
 ])
 def test_emulated_kernels_match_oracle(emu, ora, name, n, d, r, nb, ml):
     import gpu_util as g

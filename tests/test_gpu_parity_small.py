@@ -72,6 +72,8 @@ def run_all(g, ora, shape, cores, idx, off, grad, lr=0.01, check_plan=True, rema
     (5, (1, 1, 9), (2, 2, 2), (1, 1, 1, 1), 50, 4),
     (6, (2, 1, 1500), (2, 3, 2), (1, 3, 5, 1), 700, 4),   # a row factor above 1023: grouping sorts of two digits
     (7, (1, 3000, 3), (2, 3, 2), (1, 3, 4, 1), 900, 5),
+    # capacity per i1 / i3 segment above 4096: the core-0 / core-2 reductions take the two-stage sum
+    (8, (1, 5000, 2), (2, 3, 2), (1, 3, 5, 1), 4000, 7),
 ])
 def test_small_shapes(g, ora, seed, n, d, r, nb, ml):
     print("case small_shapes seed=%d n=%s d=%s r=%s" % (seed, n, d, r), flush=True)
@@ -90,6 +92,9 @@ def test_small_shapes(g, ora, seed, n, d, r, nb, ml):
     (69, (2, 3, 70), (1, 32, 32, 1), 1200, 4),
     (70, (1, 2100, 2), (1, 32, 32, 1), 1500, 3),  # a row factor above 1023: grouping sorts of two digits
     (71, (1, 2, 1100), (1, 64, 64, 1), 800, 4),
+    # capacity per i1 / i3 segment above 4096: the core-0 / core-2 reductions take the two-stage sum
+    (72, (1, 5000, 2), (1, 32, 32, 1), 4000, 7),
+    (73, (2, 9000, 1), (1, 64, 64, 1), 5000, 5),
 ])
 def test_matrix_core_shapes(g, ora, seed, n, r, nb, ml):
     """Shapes served by the MFMA kernels (d = 4x8x4, ranks 32 or 64) on small tables."""
