@@ -120,6 +120,8 @@ def _run(emu, shape, cores, idx, off, grad, lr):
     # few i1 / i3 values under thousands of prefixes and rows: the core-0 / core-2 reductions leave the
     # whole-segment kernel for the two-stage sum (capacity per segment above 4096)
     ("mfma_r32_long_segments", (1, 5000, 2), (4, 8, 4), (1, 32, 32, 1), 3000, 7),
+    # 31-bit row keys (2.1e9 rows): four radix passes
+    ("plain_31_bit_keys", (1290, 1290, 1290), (2, 3, 2), (1, 3, 5, 1), 300, 4),
 ])
 def test_emulated_kernels_match_oracle(emu, ora, name, n, d, r, nb, ml):
     import gpu_util as g
@@ -208,8 +210,8 @@ def asan_harness():
     return emu_build.build_harness(BUILD_DIR, "address")
 
 
-@pytest.mark.parametrize("kind,shuffle", [("mfma", None), ("plain", None), ("unaligned", None), ("wide", None), ("mfma", "11"),
-                                          ("plain", "12")])
+@pytest.mark.parametrize("kind,shuffle", [("mfma", None), ("plain", None), ("unaligned", None), ("wide", None), ("keys31", None),
+                                          ("mfma", "11"), ("plain", "12")])
 def test_sanitized_single_and_batched_calls(asan_harness, kind, shuffle):
     """Every entry point under AddressSanitizer + UBSan.  While a launch runs, the host structs of the
     C ABI (tables, plans, batch items) and the library's host copies of the table descriptors are

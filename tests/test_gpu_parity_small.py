@@ -74,6 +74,7 @@ def run_all(g, ora, shape, cores, idx, off, grad, lr=0.01, check_plan=True, rema
     (7, (1, 3000, 3), (2, 3, 2), (1, 3, 4, 1), 900, 5),
     # capacity per i1 / i3 segment above 4096: the core-0 / core-2 reductions take the two-stage sum
     (8, (1, 5000, 2), (2, 3, 2), (1, 3, 5, 1), 4000, 7),
+    (9, (1290, 1290, 1290), (2, 3, 2), (1, 3, 5, 1), 3000, 5),  # 31-bit row keys (2.1e9 rows): four radix passes
 ])
 def test_small_shapes(g, ora, seed, n, d, r, nb, ml):
     print("case small_shapes seed=%d n=%s d=%s r=%s" % (seed, n, d, r), flush=True)
@@ -95,6 +96,7 @@ def test_small_shapes(g, ora, seed, n, d, r, nb, ml):
     # capacity per i1 / i3 segment above 4096: the core-0 / core-2 reductions take the two-stage sum
     (72, (1, 5000, 2), (1, 32, 32, 1), 4000, 7),
     (73, (2, 9000, 1), (1, 64, 64, 1), 5000, 5),
+    (74, (1290, 1290, 1290), (1, 32, 32, 1), 3000, 5),  # 31-bit row keys (2.1e9 rows): four radix passes
 ])
 def test_matrix_core_shapes(g, ora, seed, n, r, nb, ml):
     """Shapes served by the MFMA kernels (d = 4x8x4, ranks 32 or 64) on small tables."""
