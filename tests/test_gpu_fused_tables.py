@@ -255,3 +255,25 @@ def test_fused_seeded_random_members(g, ora):
         print("case fused random %d d=%s r=%s ns=%s rows=%s bags=%s" % (case, d, r, ns, rows, bags), flush=True)
         probs = make_members(7000 + 10 * case, ns, d, r, num_bags=bags, max_len=int(rng.integers(1, 9)), num_rows=rows)
         run_fused(g, ora, probs, "fused random %d" % case)
+
+
+def test_fuse_lookups_more_lookups_than_one_grid_pass(g):
+    """A member with 1.3 million lookups (the map's grid is capped and strides) beside a small one and an
+    empty one: the map bit for bit against numpy."""
+    import paper_2507_14668_amd as tt
+    print("case fuse_lookups 1.3M", flush=True)
+    rng = np.random.default_rng(5)
+    members = [(90000, (45, 50, 40)), (60, (3, 4, 5)), (1000, (10, 10, 10))]
+    lens = [rng.integers(0, 6, size=520_000), np.zeros(0, dtype=np.int64), rng.integers(0, 3, size=77)]
+    idx, off = [], []
+    for (nr, _), ln in zip(members, lens):
+        o = np.zeros(len(ln) + 1, dtype=np.int64)
+        np.cumsum(ln, out=o[1:])
+        off.append(o)
+        idx.append(rng.integers(-2, nr + 2, size=int(o[-1]), dtype=np.int64))  # a few invalid ones on both sides
+    assert len(idx[0]) > 1_200_000
+    layout = tt.FusedLayout(members)
+    f_idx, f_off = layout.fuse_lookups([g.to_dev(x, torch.int64) for x in idx], [g.to_dev(x, torch.int64) for x in off])
+    ref_idx, ref_off = numpy_fuse(members, idx, off)
+    assert np.array_equal(f_idx.cpu().numpy(), ref_idx) and np.array_equal(f_off.cpu().numpy(), ref_off)
+    assert (ref_idx == -1).sum() > 10
