@@ -83,11 +83,11 @@ int main(int argc, char **argv) {
     for (int t = 0; t < 3; ++t)
       tabs.push_back(make_tab(ns[t], d, 32, 32, bags[t], 5, (int64_t)ns[t][0] * ns[t][1] * ns[t][2] - (t == 1 ? 3 : 0)));
   } else if (!strcmp(kind, "wide")) {  // row factors above 1023: the groupings become radix sorts of two digits
-    const int d[3] = {4, 8, 4};
+    const int d[3] = {2, 3, 4};  // (small cores: what is under test here is the reorder)
     const int ns[3][3] = {{1, 2100, 2}, {2, 1, 1500}, {3, 1100, 1}};
     const int bags[3] = {120, 90, 60};
     for (int t = 0; t < 3; ++t)
-      tabs.push_back(make_tab(ns[t], d, 32, 32, bags[t], 4, (int64_t)ns[t][0] * ns[t][1] * ns[t][2] - (t == 2 ? 7 : 0)));
+      tabs.push_back(make_tab(ns[t], d, 5, 6, bags[t], 4, (int64_t)ns[t][0] * ns[t][1] * ns[t][2] - (t == 2 ? 7 : 0)));
   } else if (!strcmp(kind, "keys31")) {  // 31-bit row keys: four radix passes
     const int d[3] = {2, 3, 4};
     const int ns[2][3] = {{1290, 1290, 1290}, {7, 5, 3}};
